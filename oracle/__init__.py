@@ -1,0 +1,150 @@
+"""Reference CPU implementation of the MX cast / dequantize / dot product.
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by __graft_entry__.smoke() and
+by bench.py's cpu_baseline leg; never by the GPU package.  Thin ctypes layer
+over oracle/libmx_oracle.so (plain C, see mx_oracle.c); all arrays are numpy
+arrays in host memory.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+FP8_E4M3, FP8_E5M2, FP6_E3M2, FP6_E2M3, FP4_E2M1, INT8 = range(6)
+FORMATS = (FP8_E4M3, FP8_E5M2, FP6_E3M2, FP6_E2M3, FP4_E2M1, INT8)
+FORMAT_NAMES = ("fp8_e4m3", "fp8_e5m2", "fp6_e3m2", "fp6_e2m3", "fp4_e2m1", "int8")
+ROUND_RNE, ROUND_HALF_AWAY = 0, 1
+DT_F32, DT_BF16 = 0, 1
+BLOCK = 32
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        from . import build as _build
+        path = _build.build(force=False)
+        L = ctypes.CDLL(path)
+        i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        L.mxo_elem_bits.argtypes = [ci]
+        L.mxo_emax.argtypes = [ci]
+        L.mxo_decode.argtypes = [ci, ctypes.c_uint]
+        L.mxo_decode.restype = ctypes.c_double
+        L.mxo_encode.argtypes = [ci, ci, ctypes.c_double]
+        L.mxo_encode.restype = ctypes.c_uint
+        L.mxo_quantize_block.argtypes = [vp, ci, ci, vp, vp]
+        L.mxo_quantize_block.restype = None
+        L.mxo_quantize.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp]
+        L.mxo_dequantize.argtypes = [vp, vp, ci, i64, i64, ci, vp, ci, i64]
+        L.mxo_gemm.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, vp]
+        L.mxo_gemm_entries.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, i64, vp, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def elem_bits(fmt):
+    return lib().mxo_elem_bits(fmt)
+
+
+def emax(fmt):
+    return lib().mxo_emax(fmt)
+
+
+def decode(fmt, code):
+    return lib().mxo_decode(fmt, int(code))
+
+
+def encode(fmt, rnd, x):
+    return lib().mxo_encode(fmt, rnd, float(x))
+
+
+def num_threads():
+    return lib().mxo_num_threads()
+
+
+def quantize_block(values, fmt, rnd=ROUND_RNE):
+    """values: 32 floats (widened to double).  Returns (scale_byte, codes[32])."""
+    v = np.ascontiguousarray(values, dtype=np.float64)
+    assert v.shape == (BLOCK,)
+    scale = np.zeros(1, dtype=np.uint8)
+    codes = np.zeros(BLOCK, dtype=np.uint32)
+    lib().mxo_quantize_block(_ptr(v), fmt, rnd, _ptr(scale), _ptr(codes))
+    return int(scale[0]), codes
+
+
+def _src_dt(src):
+    """src is float32, or uint16 holding bf16 bit patterns."""
+    if src.dtype == np.float32:
+        return DT_F32
+    if src.dtype == np.uint16:
+        return DT_BF16
+    raise TypeError("source must be float32 or uint16 (bf16 bits)")
+
+
+def quantize(src, axis, fmt, rnd=ROUND_RNE):
+    """src: 2-D C-contiguous float32 array or uint16 array of bf16 bits.
+    Returns (elems uint8 [n_out, len*bits/8], scales uint8 [n_out, len/32])."""
+    src = np.ascontiguousarray(src)
+    rows, cols = src.shape
+    n_out, length = (rows, cols) if axis == 1 else (cols, rows)
+    w = elem_bits(fmt)
+    elems = np.zeros((n_out, length * w // 8), dtype=np.uint8)
+    scales = np.zeros((n_out, length // BLOCK), dtype=np.uint8)
+    st = lib().mxo_quantize(_ptr(src), _src_dt(src), rows, cols, cols, axis, fmt, rnd,
+                            _ptr(elems), _ptr(scales))
+    if st != 0:
+        raise ValueError("mxo_quantize rejected its arguments")
+    return elems, scales
+
+
+def dequantize(elems, scales, fmt, rows, cols, axis, dst_dt=DT_F32):
+    """Returns float32 [rows, cols], or uint16 bf16 bits when dst_dt is DT_BF16."""
+    elems = np.ascontiguousarray(elems, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.uint8)
+    dst = np.zeros((rows, cols), dtype=np.float32 if dst_dt == DT_F32 else np.uint16)
+    st = lib().mxo_dequantize(_ptr(elems), _ptr(scales), fmt, rows, cols, axis,
+                              _ptr(dst), dst_dt, cols)
+    if st != 0:
+        raise ValueError("mxo_dequantize rejected its arguments")
+    return dst
+
+
+def gemm(A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, K, want_abs=False):
+    """C[M,N] (float64) = A[M,K] . B[N,K]^T on MX operands blocked along K."""
+    A_elems = np.ascontiguousarray(A_elems, dtype=np.uint8)
+    B_elems = np.ascontiguousarray(B_elems, dtype=np.uint8)
+    A_scales = np.ascontiguousarray(A_scales, dtype=np.uint8)
+    B_scales = np.ascontiguousarray(B_scales, dtype=np.uint8)
+    M, N = A_scales.shape[0], B_scales.shape[0]
+    C = np.zeros((M, N), dtype=np.float64)
+    Cabs = np.zeros((M, N), dtype=np.float64) if want_abs else None
+    st = lib().mxo_gemm(M, N, K, _ptr(A_elems), _ptr(A_scales), fmtA,
+                        _ptr(B_elems), _ptr(B_scales), fmtB, _ptr(C),
+                        _ptr(Cabs) if want_abs else None)
+    if st != 0:
+        raise ValueError("mxo_gemm rejected its arguments")
+    return (C, Cabs) if want_abs else C
+
+
+def gemm_entries(A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, K, mi, ni):
+    """Dot products for the listed (m, n) pairs.  Returns (C, Cabs) float64 [n]."""
+    A_elems = np.ascontiguousarray(A_elems, dtype=np.uint8)
+    B_elems = np.ascontiguousarray(B_elems, dtype=np.uint8)
+    A_scales = np.ascontiguousarray(A_scales, dtype=np.uint8)
+    B_scales = np.ascontiguousarray(B_scales, dtype=np.uint8)
+    mi = np.ascontiguousarray(mi, dtype=np.int64)
+    ni = np.ascontiguousarray(ni, dtype=np.int64)
+    M, N = A_scales.shape[0], B_scales.shape[0]
+    C = np.zeros(mi.shape[0], dtype=np.float64)
+    Cabs = np.zeros(mi.shape[0], dtype=np.float64)
+    st = lib().mxo_gemm_entries(M, N, K, _ptr(A_elems), _ptr(A_scales), fmtA,
+                                _ptr(B_elems), _ptr(B_scales), fmtB, mi.shape[0],
+                                _ptr(mi), _ptr(ni), _ptr(C), _ptr(Cabs))
+    if st != 0:
+        raise ValueError("mxo_gemm_entries rejected its arguments")
+    return C, Cabs

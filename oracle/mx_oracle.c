@@ -1,0 +1,479 @@
+/*
+ * mx_oracle.c -- reference CPU implementation of the MX cast (Algorithm 1 of
+ * arXiv 2310.10537), of v = X * P (Section 2) and of the MX dot product
+ * (Section 4.1).  TEST INFRASTRUCTURE: plain, slow, written to be read next
+ * to the paper.  Shares nothing with the GPU library.
+ *
+ * Arithmetic: every real number that occurs (a Float32 or BFloat16 input, a
+ * power of two between 2^-127 and 2^127, their quotient, an element value) is
+ * exactly representable in IEEE double, and all scalings are by powers of two
+ * through ldexp, so no step before the one explicit rounding is inexact.
+ */
+#include "mx_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------
+ * Element formats (Table 1 gives name and width; "ExMy" fixes the rest:
+ * sign-magnitude, x exponent bits with bias 2^(x-1)-1, y mantissa bits,
+ * exponent field 0 = subnormals).  Special codes: FP8 E5M2 keeps IEEE Inf and
+ * NaN in its top exponent; FP8 E4M3 has no Inf and a single NaN mantissa
+ * pattern (all ones); the 6- and 4-bit formats have neither (Section 2.1:
+ * Inf/NaN per element only "depending on the element format").
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    int bits;    /* total width                                   */
+    int ebits;   /* exponent field width (0 for INT8)             */
+    int mbits;   /* mantissa field width                          */
+    int bias;    /* exponent bias                                 */
+    int emax;    /* exponent of the largest normal (Algorithm 1)  */
+    int has_inf; /* element codes for +-Inf exist                 */
+    int has_nan; /* element codes for NaN exist                   */
+} fmt_t;
+
+static const fmt_t FMT[MXO_NUM_FORMATS] = {
+    /* FP8 E4M3 */ {8, 4, 3, 7, 8, 0, 1},
+    /* FP8 E5M2 */ {8, 5, 2, 15, 15, 1, 1},
+    /* FP6 E3M2 */ {6, 3, 2, 3, 4, 0, 0},
+    /* FP6 E2M3 */ {6, 2, 3, 1, 2, 0, 0},
+    /* FP4 E2M1 */ {4, 2, 1, 1, 2, 0, 0},
+    /* INT8     */ {8, 0, 0, 0, 0, 0, 0},
+};
+
+static int fmt_ok(int fmt) { return fmt >= 0 && fmt < MXO_NUM_FORMATS; }
+
+int mxo_elem_bits(int fmt) { return fmt_ok(fmt) ? FMT[fmt].bits : -1; }
+int mxo_emax(int fmt) { return fmt_ok(fmt) ? FMT[fmt].emax : -1; }
+
+int mxo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* floor(log2(a)) for finite a > 0 */
+static int floor_log2(double a)
+{
+    int e;
+    (void)frexp(a, &e); /* a = f * 2^e with f in [0.5, 1) */
+    return e - 1;
+}
+
+/* Largest normal magnitude of a floating-point element format. */
+static double fp_max_normal(const fmt_t *f)
+{
+    int top_e = (1 << f->ebits) - 1;
+    int top_m = (1 << f->mbits) - 1;
+    if (f->has_inf) top_e -= 1;            /* E5M2: top exponent is Inf/NaN */
+    else if (f->has_nan) top_m -= 1;       /* E4M3: only S.1111.111 is NaN  */
+    return ldexp((double)((1 << f->mbits) + top_m), top_e - f->bias - f->mbits);
+}
+
+/* ------------------------------------------------------------------------
+ * decode: element code -> P
+ * ---------------------------------------------------------------------- */
+double mxo_decode(int fmt, unsigned code)
+{
+    if (!fmt_ok(fmt)) return NAN;
+    const fmt_t *f = &FMT[fmt];
+    code &= (1u << f->bits) - 1u;
+
+    if (fmt == MXO_INT8) {
+        /* two's complement integer with an implied scale of 2^-6 */
+        int v = (code & 0x80u) ? (int)code - 256 : (int)code;
+        return ldexp((double)v, -6);
+    }
+
+    unsigned sign = code >> (f->bits - 1);
+    unsigned E = (code >> f->mbits) & ((1u << f->ebits) - 1u);
+    unsigned M = code & ((1u << f->mbits) - 1u);
+    double s = sign ? -1.0 : 1.0;
+
+    if (f->has_inf && E == (1u << f->ebits) - 1u)     /* E5M2 top exponent */
+        return M == 0 ? s * INFINITY : NAN;
+    if (!f->has_inf && f->has_nan &&                   /* E4M3 S.1111.111  */
+        E == (1u << f->ebits) - 1u && M == (1u << f->mbits) - 1u)
+        return NAN;
+
+    if (E == 0) /* subnormal: 0.M * 2^(1-bias) */
+        return s * ldexp((double)M, 1 - f->bias - f->mbits);
+    /* normal: 1.M * 2^(E-bias) */
+    return s * ldexp((double)((1u << f->mbits) + M), (int)E - f->bias - f->mbits);
+}
+
+/* Round the non-negative exact quotient q to an integer. */
+static double round_q(double q, int rnd)
+{
+    double fl = floor(q);
+    double d = q - fl; /* exact: q has at most 53 significant bits */
+    if (rnd == MXO_ROUND_HALF_AWAY) {
+        if (d >= 0.5) fl += 1.0;
+    } else { /* ties to even */
+        if (d > 0.5 || (d == 0.5 && fmod(fl, 2.0) != 0.0)) fl += 1.0;
+    }
+    return fl;
+}
+
+/* ------------------------------------------------------------------------
+ * encode: quantize_to_element_format (Algorithm 1 line 4 and the notes
+ * after it), applied to x = V / X.
+ * ---------------------------------------------------------------------- */
+unsigned mxo_encode(int fmt, int rnd, double x)
+{
+    if (!fmt_ok(fmt)) return 0;
+    const fmt_t *f = &FMT[fmt];
+    unsigned sign = signbit(x) ? 1u : 0u;
+    unsigned signbit_code = sign << (f->bits - 1);
+
+    if (isnan(x)) {
+        if (fmt == MXO_FP8_E4M3) return signbit_code | 0x7Fu;
+        if (fmt == MXO_FP8_E5M2) return signbit_code | 0x7Eu; /* S.11111.10 */
+        return 0;
+    }
+    if (isinf(x)) { /* never clamped */
+        if (fmt == MXO_FP8_E5M2) return signbit_code | 0x7Cu;
+        if (fmt == MXO_FP8_E4M3) return signbit_code | 0x7Fu; /* no Inf code */
+        return 0;
+    }
+
+    double a = fabs(x);
+
+    if (fmt == MXO_INT8) {
+        double q = round_q(ldexp(a, 6), rnd); /* grid step 2^-6 */
+        if (q > 127.0) q = 127.0;             /* symmetric clamp */
+        int iq = (int)q;
+        if (sign) iq = -iq;
+        return (unsigned)iq & 0xFFu;
+    }
+
+    if (a == 0.0) return signbit_code;
+
+    int emin = 1 - f->bias; /* exponent of the smallest normal */
+    int step_exp;           /* grid step is 2^step_exp around a  */
+    if (a < ldexp(1.0, emin))
+        step_exp = emin - f->mbits; /* subnormal grid */
+    else
+        step_exp = floor_log2(a) - f->mbits;
+
+    double q = round_q(ldexp(a, -step_exp), rnd);
+    double r = ldexp(q, step_exp);
+    double vmax = fp_max_normal(f);
+    if (r > vmax) r = vmax; /* clamp normals, keep sign */
+
+    /* write r (exactly on the grid now) as sign / exponent / mantissa */
+    if (r == 0.0) return signbit_code;
+    unsigned E, M;
+    if (r < ldexp(1.0, emin)) {
+        E = 0;
+        M = (unsigned)ldexp(r, -(emin - f->mbits));
+    } else {
+        int e = floor_log2(r);
+        E = (unsigned)(e + f->bias);
+        M = (unsigned)ldexp(r, -(e - f->mbits)) - (1u << f->mbits);
+    }
+    return signbit_code | (E << f->mbits) | M;
+}
+
+/* ------------------------------------------------------------------------
+ * Algorithm 1 on one block.
+ * ---------------------------------------------------------------------- */
+#define F32_MIN_NORMAL 0x1p-126 /* smallest normal Float32 */
+
+void mxo_quantize_block(const double v[MXO_BLOCK], int fmt, int rnd,
+                        uint8_t *scale, unsigned codes[MXO_BLOCK])
+{
+    const fmt_t *f = &FMT[fmt];
+    int any_nonfinite = 0;
+    double m = 0.0; /* max |V_i| over normal finite inputs */
+
+    for (int i = 0; i < MXO_BLOCK; i++) {
+        if (isnan(v[i]) || isinf(v[i])) { any_nonfinite = 1; continue; }
+        double a = fabs(v[i]);
+        if (a < F32_MIN_NORMAL) continue; /* Float32 subnormal or zero */
+        if (a > m) m = a;
+    }
+
+    /* formats with no element Inf/NaN: the only NaN encoding left is X = NaN */
+    if (any_nonfinite && !f->has_nan) {
+        *scale = MXO_SCALE_NAN;
+        for (int i = 0; i < MXO_BLOCK; i++) codes[i] = 0;
+        return;
+    }
+
+    /* line 1: shared_exp = floor(log2(max |V_i|)) - emax_elem,
+     * kept inside what E8M0 can hold as a number (bytes 0..254) */
+    int s;
+    if (m == 0.0) {
+        s = 0; /* log2(0) = -inf, clamped */
+    } else {
+        int shared_exp = floor_log2(m) - f->emax;
+        s = shared_exp + 127;
+        if (s < 0) s = 0;
+        if (s > 254) s = 254;
+    }
+    *scale = (uint8_t)s;
+
+    /* lines 3-5: P_i = quantize(V_i / X), X = 2^(s-127) */
+    for (int i = 0; i < MXO_BLOCK; i++) {
+        double x;
+        if (isnan(v[i]) || isinf(v[i]))
+            x = v[i];
+        else if (fabs(v[i]) < F32_MIN_NORMAL)
+            x = copysign(0.0, v[i]); /* Float32 subnormal -> P_i = 0 */
+        else
+            x = ldexp(v[i], 127 - s);
+        codes[i] = mxo_encode(fmt, rnd, x);
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * Tensor level
+ * ---------------------------------------------------------------------- */
+static double load_scalar(const void *src, int dt, int64_t idx)
+{
+    if (dt == MXO_DT_F32) {
+        float fv;
+        memcpy(&fv, (const char *)src + 4 * idx, 4);
+        return (double)fv;
+    } else { /* bf16 = upper half of a Float32 */
+        uint16_t h;
+        memcpy(&h, (const char *)src + 2 * idx, 2);
+        uint32_t u = (uint32_t)h << 16;
+        float fv;
+        memcpy(&fv, &u, 4);
+        return (double)fv;
+    }
+}
+
+/* element j of a packed row: bits [j*w, (j+1)*w), little-endian */
+static void put_code(uint8_t *row, int64_t j, int w, unsigned code)
+{
+    int64_t bit = j * w;
+    for (int b = 0; b < w; b++, bit++) {
+        uint8_t mask = (uint8_t)(1u << (bit & 7));
+        if ((code >> b) & 1u) row[bit >> 3] |= mask;
+        else row[bit >> 3] &= (uint8_t)~mask;
+    }
+}
+
+static unsigned get_code(const uint8_t *row, int64_t j, int w)
+{
+    int64_t bit = j * w;
+    unsigned code = 0;
+    for (int b = 0; b < w; b++, bit++)
+        code |= (unsigned)((row[bit >> 3] >> (bit & 7)) & 1u) << b;
+    return code;
+}
+
+static int shape_ok(int64_t rows, int64_t cols, int axis)
+{
+    if (rows <= 0 || cols <= 0) return 0;
+    if (axis == 1) return cols % MXO_BLOCK == 0;
+    if (axis == 0) return rows % MXO_BLOCK == 0;
+    return 0;
+}
+
+int mxo_quantize(const void *src, int src_dt, int64_t rows, int64_t cols,
+                 int64_t ld, int axis, int fmt, int rnd,
+                 uint8_t *elems_out, uint8_t *scales_out)
+{
+    if (!src || !elems_out || !scales_out || !fmt_ok(fmt)) return MXO_ERR_ARG;
+    if (src_dt != MXO_DT_F32 && src_dt != MXO_DT_BF16) return MXO_ERR_ARG;
+    if (rnd != MXO_ROUND_RNE && rnd != MXO_ROUND_HALF_AWAY) return MXO_ERR_ARG;
+    if (!shape_ok(rows, cols, axis) || ld < cols) return MXO_ERR_ARG;
+
+    int w = FMT[fmt].bits;
+    /* the output is indexed [o][l]: o = the axis that is not blocked,
+     * l = position along the block axis */
+    int64_t n_out = axis == 1 ? rows : cols;
+    int64_t len = axis == 1 ? cols : rows;
+    int64_t row_bytes = len * w / 8;
+    int64_t nblk = len / MXO_BLOCK;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < n_out; o++) {
+        uint8_t *erow = elems_out + o * row_bytes;
+        for (int64_t b = 0; b < nblk; b++) {
+            double v[MXO_BLOCK];
+            unsigned codes[MXO_BLOCK];
+            for (int i = 0; i < MXO_BLOCK; i++) {
+                int64_t l = b * MXO_BLOCK + i;
+                int64_t idx = axis == 1 ? o * ld + l : l * ld + o;
+                v[i] = load_scalar(src, src_dt, idx);
+            }
+            mxo_quantize_block(v, fmt, rnd, &scales_out[o * nblk + b], codes);
+            for (int i = 0; i < MXO_BLOCK; i++)
+                put_code(erow, b * MXO_BLOCK + i, w, codes[i]);
+        }
+    }
+    return MXO_OK;
+}
+
+/* X * P as a double; X = NaN gives NaN (Section 2) */
+static double block_value(int fmt, unsigned code, uint8_t s)
+{
+    if (s == MXO_SCALE_NAN) return NAN;
+    return ldexp(mxo_decode(fmt, code), (int)s - 127);
+}
+
+/* double -> bf16 bits, round to nearest even, done on the bf16 grid directly */
+static uint16_t to_bf16_bits(double v)
+{
+    if (isnan(v)) return 0x7FC0;
+    uint16_t sign = signbit(v) ? 0x8000 : 0;
+    double a = fabs(v);
+    if (isinf(a)) return sign | 0x7F80;
+    if (a == 0.0) return sign;
+    int step_exp = (a < F32_MIN_NORMAL) ? -126 - 7 : floor_log2(a) - 7;
+    double r = ldexp(round_q(ldexp(a, -step_exp), MXO_ROUND_RNE), step_exp);
+    if (r > 0x1.FEp127) return sign | 0x7F80; /* above the largest bf16 */
+    float fr = (float)r; /* exact: r is on the bf16 grid */
+    uint32_t u;
+    memcpy(&u, &fr, 4);
+    return sign | (uint16_t)(u >> 16);
+}
+
+static void store_scalar(void *dst, int dt, int64_t idx, double v)
+{
+    if (dt == MXO_DT_F32) {
+        float fv = (float)v; /* beyond Float32 range -> +-Inf */
+        uint32_t u;
+        memcpy(&u, &fv, 4);
+        if (isnan(v)) u = 0x7FC00000u; /* one canonical quiet NaN */
+        memcpy((char *)dst + 4 * idx, &u, 4);
+    } else {
+        uint16_t h = to_bf16_bits(v);
+        memcpy((char *)dst + 2 * idx, &h, 2);
+    }
+}
+
+int mxo_dequantize(const uint8_t *elems, const uint8_t *scales, int fmt,
+                   int64_t rows, int64_t cols, int axis,
+                   void *dst, int dst_dt, int64_t ld)
+{
+    if (!elems || !scales || !dst || !fmt_ok(fmt)) return MXO_ERR_ARG;
+    if (dst_dt != MXO_DT_F32 && dst_dt != MXO_DT_BF16) return MXO_ERR_ARG;
+    if (!shape_ok(rows, cols, axis) || ld < cols) return MXO_ERR_ARG;
+
+    int w = FMT[fmt].bits;
+    int64_t n_out = axis == 1 ? rows : cols;
+    int64_t len = axis == 1 ? cols : rows;
+    int64_t row_bytes = len * w / 8;
+    int64_t nblk = len / MXO_BLOCK;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < n_out; o++) {
+        const uint8_t *erow = elems + o * row_bytes;
+        for (int64_t l = 0; l < len; l++) {
+            uint8_t s = scales[o * nblk + l / MXO_BLOCK];
+            double v = block_value(fmt, get_code(erow, l, w), s);
+            int64_t idx = axis == 1 ? o * ld + l : l * ld + o;
+            store_scalar(dst, dst_dt, idx, v);
+        }
+    }
+    return MXO_OK;
+}
+
+/* ------------------------------------------------------------------------
+ * MX dot product.  Because every X is a power of two, sum over blocks of
+ * X_A * X_B * sum_j a_j * b_j equals the plain sum of products of the
+ * dequantized values; each product is exact in double.
+ * ---------------------------------------------------------------------- */
+static void dequant_row(const uint8_t *elems, const uint8_t *scales, int fmt,
+                        int64_t K, int64_t r, double *out)
+{
+    int w = FMT[fmt].bits;
+    const uint8_t *erow = elems + r * (K * w / 8);
+    const uint8_t *srow = scales + r * (K / MXO_BLOCK);
+    for (int64_t k = 0; k < K; k++)
+        out[k] = block_value(fmt, get_code(erow, k, w), srow[k / MXO_BLOCK]);
+}
+
+static int gemm_args_ok(int64_t M, int64_t N, int64_t K, const void *a,
+                        const void *as, int fa, const void *b, const void *bs,
+                        int fb, const void *C)
+{
+    if (!a || !as || !b || !bs || !C) return 0;
+    if (!fmt_ok(fa) || !fmt_ok(fb)) return 0;
+    if (M <= 0 || N <= 0 || K <= 0 || K % MXO_BLOCK) return 0;
+    return 1;
+}
+
+int mxo_gemm(int64_t M, int64_t N, int64_t K,
+             const uint8_t *A_elems, const uint8_t *A_scales, int fmtA,
+             const uint8_t *B_elems, const uint8_t *B_scales, int fmtB,
+             double *C, double *Cabs)
+{
+    if (!gemm_args_ok(M, N, K, A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, C))
+        return MXO_ERR_ARG;
+
+    /* working copies of the operands as doubles (freed before returning) */
+    double *Ad = (double *)malloc((size_t)M * K * sizeof(double));
+    double *Bd = (double *)malloc((size_t)N * K * sizeof(double));
+    if (!Ad || !Bd) { free(Ad); free(Bd); return MXO_ERR_ARG; }
+
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; m++)
+        dequant_row(A_elems, A_scales, fmtA, K, m, Ad + m * K);
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; n++)
+        dequant_row(B_elems, B_scales, fmtB, K, n, Bd + n * K);
+
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; m++) {
+        for (int64_t n = 0; n < N; n++) {
+            double acc = 0.0, accabs = 0.0;
+            for (int64_t k = 0; k < K; k++) {
+                double p = Ad[m * K + k] * Bd[n * K + k];
+                acc += p;
+                accabs += fabs(p);
+            }
+            C[m * N + n] = acc;
+            if (Cabs) Cabs[m * N + n] = accabs;
+        }
+    }
+    free(Ad);
+    free(Bd);
+    return MXO_OK;
+}
+
+int mxo_gemm_entries(int64_t M, int64_t N, int64_t K,
+                     const uint8_t *A_elems, const uint8_t *A_scales, int fmtA,
+                     const uint8_t *B_elems, const uint8_t *B_scales, int fmtB,
+                     int64_t n, const int64_t *mi, const int64_t *ni,
+                     double *C, double *Cabs)
+{
+    if (!gemm_args_ok(M, N, K, A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, C))
+        return MXO_ERR_ARG;
+    if (n < 0 || !mi || !ni) return MXO_ERR_ARG;
+    for (int64_t t = 0; t < n; t++)
+        if (mi[t] < 0 || mi[t] >= M || ni[t] < 0 || ni[t] >= N) return MXO_ERR_ARG;
+
+    int wa = FMT[fmtA].bits, wb = FMT[fmtB].bits;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; t++) {
+        const uint8_t *ea = A_elems + mi[t] * (K * wa / 8);
+        const uint8_t *sa = A_scales + mi[t] * (K / MXO_BLOCK);
+        const uint8_t *eb = B_elems + ni[t] * (K * wb / 8);
+        const uint8_t *sb = B_scales + ni[t] * (K / MXO_BLOCK);
+        double acc = 0.0, accabs = 0.0;
+        for (int64_t k = 0; k < K; k++) {
+            double a = block_value(fmtA, get_code(ea, k, wa), sa[k / MXO_BLOCK]);
+            double b = block_value(fmtB, get_code(eb, k, wb), sb[k / MXO_BLOCK]);
+            double p = a * b;
+            acc += p;
+            accabs += fabs(p);
+        }
+        C[t] = acc;
+        if (Cabs) Cabs[t] = accabs;
+    }
+    return MXO_OK;
+}

@@ -1,0 +1,116 @@
+/*
+ * mx_oracle.h -- reference CPU implementation of the Microscaling (MX) cast,
+ * its inverse, and the MX dot product (arXiv 2310.10537, Sections 2, 3, 4.1).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is slow on purpose: every function is the
+ * definition written out in double precision and integer arithmetic, with no
+ * blocking, fusion or reordering, so that it can be checked against the paper
+ * by eye.  It shares no code with the GPU library and must never be linked
+ * into, or called from, the product path.
+ *
+ * All pointers are HOST pointers and caller-owned; nothing is retained.
+ * Only mxo_gemm allocates (working copies of its operands, freed on return).
+ *
+ * Parity unpinned (conventions of this build, the paper leaves them open):
+ *   - the scale byte of a block with no normal finite value (0x00);
+ *   - Inf/NaN inputs to element formats that have no Inf/NaN code
+ *     (whole block marked NaN by scale byte 0xFF, element codes 0);
+ *   - Inf input to FP8 E4M3 (encoded as the element NaN, sign kept).
+ */
+#ifndef MX_ORACLE_H
+#define MX_ORACLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element data formats of Table 1.  Numbering is part of the interface. */
+enum {
+    MXO_FP8_E4M3 = 0,
+    MXO_FP8_E5M2 = 1,
+    MXO_FP6_E3M2 = 2,
+    MXO_FP6_E2M3 = 3,
+    MXO_FP4_E2M1 = 4,
+    MXO_INT8     = 5,
+    MXO_NUM_FORMATS = 6
+};
+
+/* Rounding used by quantize_to_element_format (Section 4.3: ties to even;
+ * Section 4.5: ties away from zero). */
+enum { MXO_ROUND_RNE = 0, MXO_ROUND_HALF_AWAY = 1 };
+
+/* Scalar float types of tensors handed to the cast. */
+enum { MXO_DT_F32 = 0, MXO_DT_BF16 = 1 };
+
+enum { MXO_OK = 0, MXO_ERR_ARG = 1 };
+
+#define MXO_BLOCK 32          /* block size k of every concrete format (Table 1) */
+#define MXO_SCALE_NAN 0xFF    /* E8M0 code of X = NaN (Section 2.1)              */
+
+/* Bit width of one element (Table 1); -1 for an unknown format. */
+int mxo_elem_bits(int fmt);
+
+/* emax_elem of Algorithm 1: exponent of the largest normal number. */
+int mxo_emax(int fmt);
+
+/* Value of one element code P (Section 2: v = X * P, this is P).
+ * May return +-Inf or NaN for FP8 codes that encode them. */
+double mxo_decode(int fmt, unsigned code);
+
+/* quantize_to_element_format of Algorithm 1, line 4, for one already scaled
+ * value x = V / X.  x may be any double including +-0, +-Inf and NaN.
+ * Finite magnitudes beyond the largest normal are clamped to it, sign kept;
+ * Inf and NaN are never clamped.  For formats without Inf/NaN codes the
+ * caller handles non-finite inputs at block level and this returns 0. */
+unsigned mxo_encode(int fmt, int rnd, double x);
+
+/* Algorithm 1 on one block of 32 values, already widened (exactly) from
+ * Float32 or BFloat16 to double.  Inputs below 2^-126 in magnitude are
+ * Float32 subnormals and become P_i = 0.  Writes the E8M0 byte and the 32
+ * element codes. */
+void mxo_quantize_block(const double v[MXO_BLOCK], int fmt, int rnd,
+                        uint8_t *scale, unsigned codes[MXO_BLOCK]);
+
+/* Cast a row-major [rows, cols] tensor (leading dimension ld, in elements).
+ * axis = 1: blocks of 32 along the last dimension;
+ *           elems [rows][cols*bits/8], scales [rows][cols/32].
+ * axis = 0: blocks of 32 along dimension 0, output written as the cast of the
+ *           transpose: elems [cols][rows*bits/8], scales [cols][rows/32].
+ * Elements are densely bit-packed little-endian: element j of an output row
+ * occupies bits [j*w, (j+1)*w) of that row's byte string. */
+int mxo_quantize(const void *src, int src_dt, int64_t rows, int64_t cols,
+                 int64_t ld, int axis, int fmt, int rnd,
+                 uint8_t *elems_out, uint8_t *scales_out);
+
+/* Inverse: v = X * P (Section 2), X = NaN makes the whole block NaN, results
+ * beyond Float32 range become +-Inf.  Writes row-major [rows, cols]. */
+int mxo_dequantize(const uint8_t *elems, const uint8_t *scales, int fmt,
+                   int64_t rows, int64_t cols, int axis,
+                   void *dst, int dst_dt, int64_t ld);
+
+/* MX dot products (Section 4.1): C[m][n] = sum_k A[m][k] * B[n][k] with both
+ * operands MX tensors whose blocks run along K (A: [M][K], B: [N][K], as
+ * written by mxo_quantize with axis = 1).  Accumulated in double in plain k
+ * order.  Cabs (may be NULL) receives sum_k |A[m][k]| * |B[n][k]|. */
+int mxo_gemm(int64_t M, int64_t N, int64_t K,
+             const uint8_t *A_elems, const uint8_t *A_scales, int fmtA,
+             const uint8_t *B_elems, const uint8_t *B_scales, int fmtB,
+             double *C, double *Cabs);
+
+/* Same dot product for a list of n (m, n) output coordinates only. */
+int mxo_gemm_entries(int64_t M, int64_t N, int64_t K,
+                     const uint8_t *A_elems, const uint8_t *A_scales, int fmtA,
+                     const uint8_t *B_elems, const uint8_t *B_scales, int fmtB,
+                     int64_t n, const int64_t *mi, const int64_t *ni,
+                     double *C, double *Cabs);
+
+/* Number of threads the loops over rows use (OpenMP); 1 if built without. */
+int mxo_num_threads(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,314 @@
+"""Pins for the reference implementation's cast and dequantize (CPU only):
+hand-worked blocks (tests/golden/handworked_blocks.txt), the closed form of the
+shared scale, the largest-binade property of Section 3, the rounding error
+bound, idempotence, the non-commutation of cast and transpose, exactness of
+v = X * P, and an independent recomputation through PyTorch's float8 cast.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2310_10537_amd import inputs
+
+E4M3, E5M2, E3M2, E2M3, E2M1, INT8 = range(6)
+RNE, AWAY = 0, 1
+EMAX = {E4M3: 8, E5M2: 15, E3M2: 4, E2M3: 2, E2M1: 2, INT8: 0}
+MBITS = {E4M3: 3, E5M2: 2, E3M2: 2, E2M3: 3, E2M1: 1, INT8: 6}
+VMAX = {E4M3: 448.0, E5M2: 57344.0, E3M2: 28.0, E2M3: 7.5, E2M1: 6.0, INT8: 127 / 64}
+BITS = {E4M3: 8, E5M2: 8, E3M2: 6, E2M3: 6, E2M1: 4, INT8: 8}
+NAMES = {"fp8_e4m3": E4M3, "fp8_e5m2": E5M2, "fp6_e3m2": E3M2, "fp6_e2m3": E2M3, "fp4_e2m1": E2M1, "int8": INT8}
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "handworked_blocks.txt")
+
+
+def _num(tok):
+    try:
+        return float(tok)
+    except ValueError:
+        return float.fromhex(tok)
+
+
+def _golden_cases():
+    cases = []
+    with open(GOLDEN) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            kv = dict(tok.split("=", 1) for tok in line.split())
+            cases.append((NAMES[kv["fmt"]], RNE if kv["rnd"] == "rne" else AWAY,
+                          [_num(t) for t in kv["in"].split(",")], int(kv["scale"], 16),
+                          [int(t, 16) for t in kv["codes"].split(",")], line))
+    return cases
+
+
+def unpack(elems, w):
+    """Little-endian dense bit string -> codes, written independently of the
+    reference's own packer: element j sits at bits [j*w, (j+1)*w)."""
+    bits = np.unpackbits(np.ascontiguousarray(elems), axis=-1, bitorder="little")
+    bits = bits.reshape(*elems.shape[:-1], -1, w)
+    return (bits.astype(np.uint32) << np.arange(w, dtype=np.uint32)).sum(axis=-1).astype(np.uint32)
+
+
+@pytest.mark.parametrize("case", _golden_cases(), ids=lambda c: c[5][:60])
+def test_handworked_blocks(oracle, case):
+    fmt, rnd, vals, scale, codes, _ = case
+    v = np.zeros(32, dtype=np.float32)
+    v[: len(vals)] = np.array(vals, dtype=np.float32)
+    s, c = oracle.quantize_block(v.astype(np.float64), fmt, rnd)
+    assert s == scale
+    assert list(c[: len(codes)]) == codes
+    assert not c[len(codes):].any()
+    # the same block through the tensor-level entry point, in both orientations,
+    # as float32 and (when the values survive) as bfloat16
+    for axis in (1, 0):
+        src = v.reshape(1, 32) if axis == 1 else v.reshape(32, 1)
+        e, sc = oracle.quantize(src, axis, fmt, rnd)
+        assert sc.shape == (1, 1) and int(sc[0, 0]) == scale
+        assert list(unpack(e, BITS[fmt])[0][: len(codes)]) == codes
+    hb = inputs.f32_to_bf16_bits(v)
+    back = inputs.bf16_bits_to_f32(hb)
+    if np.array_equal(back.view(np.uint32), v.view(np.uint32)):
+        e, sc = oracle.quantize(hb.reshape(1, 32), 1, fmt, rnd)
+        assert int(sc[0, 0]) == scale and list(unpack(e, BITS[fmt])[0][: len(codes)]) == codes
+
+
+@pytest.mark.parametrize("fmt", range(6))
+def test_scale_closed_form(oracle, fmt):
+    """For a block whose largest magnitude has Float32 exponent field E, the
+    shared scale byte is max(E - emax, 0), whatever the mantissa and sign."""
+    for E in range(1, 255):
+        for mant in (0, 1, 0x400000, 0x7FFFFF):
+            for sign in (0, 1):
+                top = np.array([(sign << 31) | (E << 23) | mant], dtype=np.uint32).view(np.float32)[0]
+                v = np.zeros(32)
+                v[5] = float(top)
+                v[9] = float(top) / 3
+                s, _ = oracle.quantize_block(v, fmt, RNE)
+                assert s == max(E - EMAX[fmt], 0), (E, mant)
+
+
+@pytest.mark.parametrize("fmt", range(6))
+@pytest.mark.parametrize("rnd", [RNE, AWAY])
+def test_largest_binade_and_error_bound(oracle, fmt, rnd):
+    """Section 3: the offset by emax maps the block maximum onto the element
+    format's largest binade.  And rounding to nearest bounds the error of every
+    unclamped element by half a grid step."""
+    rng = np.random.default_rng(fmt * 2 + rnd)
+    x = (rng.standard_normal((256, 32)) * np.exp2(rng.integers(-60, 60, (256, 1)))).astype(np.float32)
+    e, s = oracle.quantize(x, 1, fmt, rnd)
+    codes = unpack(e, BITS[fmt])
+    emin = {E4M3: -6, E5M2: -14, E3M2: -2, E2M3: 0, E2M1: 0, INT8: 0}[fmt]
+    for r in range(256):
+        X = Fraction(2) ** (int(s[r, 0]) - 127)
+        top = np.abs(x[r]).max()
+        assert X * 2 ** EMAX[fmt] <= Fraction(float(top)) < X * 2 ** (EMAX[fmt] + 1)
+        for i in range(32):
+            v = Fraction(float(x[r, i]))
+            p = Fraction(oracle.decode(fmt, int(codes[r, i])))
+            if abs(v / X) > Fraction(VMAX[fmt]):
+                assert abs(p) == Fraction(VMAX[fmt]) and (p > 0) == (v > 0)
+                continue
+            if fmt == INT8 or v == 0:
+                step = Fraction(1, 64)
+            else:
+                ex = max(math.floor(math.log2(abs(float(v / X)))), emin)
+                step = Fraction(2) ** (ex - MBITS[fmt])
+            assert abs(v / X - p) <= step / 2, (r, i)
+
+
+@pytest.mark.parametrize("fmt", range(6))
+def test_rounding_modes_differ_only_on_ties(oracle, fmt):
+    rng = np.random.default_rng(3)
+    # values on a 1/16 grid (max 4.0 => X is a power of two): many exact ties
+    x = rng.integers(-64, 65, (64, 32)).astype(np.float32) / 16
+    x[:, 0] = 4.0
+    e0, s0 = oracle.quantize(x, 1, fmt, RNE)
+    e1, s1 = oracle.quantize(x, 1, fmt, AWAY)
+    assert np.array_equal(s0, s1)
+    c0, c1 = unpack(e0, BITS[fmt]).astype(np.int64), unpack(e1, BITS[fmt]).astype(np.int64)
+    X = np.exp2(s0.astype(np.float64) - 127)
+    d0 = np.vectorize(lambda c: oracle.decode(fmt, int(c)))(c0) * X
+    d1 = np.vectorize(lambda c: oracle.decode(fmt, int(c)))(c1) * X
+    diff = c0 != c1
+    # wherever they differ the input is exactly midway between the two results
+    assert np.all(np.abs(d0[diff] - x[diff]) == np.abs(d1[diff] - x[diff]))
+    assert np.all(np.abs(d1[diff]) > np.abs(d0[diff]))
+    # and wherever the input is not a tie they agree: a non-tie has a unique nearest
+    nontie = np.abs(d0 - x) != np.abs(d1 - x)
+    assert not nontie.any()
+    if fmt in (E3M2, E2M3, E2M1):
+        assert diff.any()
+
+
+@pytest.mark.parametrize("fmt", range(6))
+@pytest.mark.parametrize("rnd", [RNE, AWAY])
+def test_idempotent(oracle, fmt, rnd):
+    """quantize(dequantize(q)) == q byte for byte on normal-range data."""
+    x = inputs.student_t_f32((64, 256), seed=9)
+    e, s = oracle.quantize(x, 1, fmt, rnd)
+    y = oracle.dequantize(e, s, fmt, 64, 256, 1)
+    e2, s2 = oracle.quantize(y, 1, fmt, rnd)
+    # the block maximum stays inside its binade (2^e is on the grid, so rounding
+    # down stops there; rounding up past the largest normal is clamped), hence
+    # the same scale, and on-grid elements re-encode to themselves
+    assert np.array_equal(s, s2)
+    assert np.array_equal(e, e2)
+    # bf16 destination carries every element exactly too (<= 7 significant bits)
+    yb = oracle.dequantize(e, s, fmt, 64, 256, 1, dst_dt=1)
+    assert np.array_equal(inputs.bf16_bits_to_f32(yb).view(np.uint32), y.view(np.uint32))
+
+
+def test_idempotence_fails_by_design_on_subnormal_results(oracle):
+    # E4M3 code 0x01 (2^-9) at scale byte 0 dequantizes to 2^-136, a Float32
+    # subnormal, which the cast maps to zero (Section 3)
+    e = np.zeros((1, 32), dtype=np.uint8)
+    e[0, 0] = 0x01
+    s = np.zeros((1, 1), dtype=np.uint8)
+    y = oracle.dequantize(e, s, E4M3, 1, 32, 1)
+    assert y[0, 0] == np.float32(2.0**-136)
+    e2, _ = oracle.quantize(y, 1, E4M3)
+    assert e2[0, 0] == 0
+
+
+@pytest.mark.parametrize("fmt", range(6))
+def test_axis0_is_cast_of_transpose_and_does_not_commute(oracle, fmt):
+    x = inputs.student_t_f32((96, 64), seed=4)
+    e0, s0 = oracle.quantize(x, 0, fmt)
+    et, st = oracle.quantize(np.ascontiguousarray(x.T), 1, fmt)
+    assert np.array_equal(e0, et) and np.array_equal(s0, st)
+    # Section 3: conversion and transposition do not commute
+    x2 = inputs.student_t_f32((64, 64), seed=5)
+    a = oracle.dequantize(*oracle.quantize(x2, 1, fmt), fmt, 64, 64, 1)
+    b = oracle.dequantize(*oracle.quantize(x2, 0, fmt), fmt, 64, 64, 0)
+    assert a.shape == b.shape == (64, 64)
+    assert not np.array_equal(a, b)
+    # leading dimension: a view into a wider buffer gives the same bytes
+    wide = np.zeros((96, 160), dtype=np.float32)
+    wide[:, :64] = x
+    import ctypes
+    L = oracle.lib()
+    w = BITS[fmt]
+    e = np.zeros((96, 64 * w // 8), dtype=np.uint8)
+    s = np.zeros((96, 2), dtype=np.uint8)
+    p = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    assert L.mxo_quantize(p(wide), 0, 96, 64, 160, 1, fmt, 0, p(e), p(s)) == 0
+    e1, s1 = oracle.quantize(x, 1, fmt)
+    assert np.array_equal(e, e1) and np.array_equal(s, s1)
+
+
+@pytest.mark.parametrize("fmt", range(6))
+def test_dequantize_exact_for_every_code_and_scale(oracle, fmt):
+    """v = X * P exactly, for every element code and every scale byte."""
+    w = BITS[fmt]
+    ncode = 1 << w
+    codes = np.arange(ncode, dtype=np.uint32)
+    reps = 32 * 8 // ncode if ncode < 256 else 1  # make the row a whole number of blocks
+    row = np.tile(codes, max(reps, 1))
+    n = row.size
+    assert n % 32 == 0
+    bits = ((row[:, None] >> np.arange(w)) & 1).astype(np.uint8).reshape(-1)
+    packed = np.packbits(bits, bitorder="little")
+    elems = np.tile(packed, (256, 1))
+    scales = np.repeat(np.arange(256, dtype=np.uint8)[:, None], n // 32, axis=1)
+    y = oracle.dequantize(elems, scales, fmt, 256, n, 1)
+    P = np.array([oracle.decode(fmt, int(c)) for c in row])
+    for s in range(255):
+        with np.errstate(over="ignore"):
+            ref = (P * 2.0 ** (s - 127)).astype(np.float32)  # power-of-two product: exact in double
+        got = y[s]
+        assert np.array_equal(np.isnan(ref), np.isnan(got))
+        ok = ~np.isnan(ref)
+        assert np.array_equal(ref[ok].view(np.uint32), got[ok].view(np.uint32)), s
+    assert np.isnan(y[255]).all()  # X = NaN
+    assert (y[255].view(np.uint32) == 0x7FC00000).all()
+
+
+def test_dequantize_overflow_and_bf16_rounding(oracle):
+    # largest E5M2 value at the largest scale is beyond Float32: +-Inf
+    e = np.zeros((1, 32), dtype=np.uint8)
+    e[0, 0], e[0, 1], e[0, 2] = 0x7B, 0xFB, 0x04
+    s = np.full((1, 1), 254, dtype=np.uint8)
+    y = oracle.dequantize(e, s, E5M2, 1, 32, 1)
+    assert y[0, 0] == np.inf and y[0, 1] == -np.inf and y[0, 2] == np.float32(2.0**-14 * 2.0**127)
+    # bf16 destination below 2^-126: spacing 2^-133, nearest-even
+    e[0, :4] = [0x01, 0x02, 0x03, 0x05]          # E4M3: 1, 2, 3, 5 times 2^-9
+    s[0, 0] = 0x02                                # X = 2^-125 -> multiples of 2^-134
+    yb = oracle.dequantize(e, s, E4M3, 1, 32, 1, dst_dt=1)
+    # 1*2^-134 is a tie between 0 and 2^-133 -> 0; 2 -> 1; 3 -> tie 1|2 -> 2; 5 -> tie 2|3 -> 2
+    assert list(yb[0, :4]) == [0, 1, 2, 2]
+    ref = torch.from_numpy(oracle.dequantize(e, s, E4M3, 1, 32, 1)).to(torch.bfloat16).view(torch.int16).numpy()
+    assert np.array_equal(yb.view(np.int16), ref)
+
+
+@pytest.mark.parametrize("fmt,dt", [(E4M3, torch.float8_e4m3fn), (E5M2, torch.float8_e5m2)])
+def test_cast_against_torch_float8_pipeline(oracle, fmt, dt):
+    """Independent recomputation of the whole cast for the FP8 formats: scale from
+    numpy's frexp, division by a power of two in float32 (exact), clamp, then
+    PyTorch's own float8 conversion."""
+    x = inputs.student_t_f32((128, 256), seed=21)
+    e, s = oracle.quantize(x, 1, fmt)
+    blk = x.reshape(128, 8, 32)
+    _, ex = np.frexp(np.abs(blk).max(axis=2))
+    sb = np.clip(ex - 1 - EMAX[fmt] + 127, 0, 254)
+    assert np.array_equal(sb.astype(np.uint8), s)
+    scaled = (blk.astype(np.float64) * np.exp2(127.0 - sb)[..., None]).astype(np.float32)
+    scaled = np.clip(scaled, -VMAX[fmt], VMAX[fmt])
+    ref = torch.from_numpy(scaled.reshape(128, 256)).to(dt).view(torch.uint8).numpy()
+    assert np.array_equal(ref, e)
+
+
+def test_int8_cast_against_numpy_rint(oracle):
+    x = inputs.gaussian_f32((64, 128), seed=22)
+    e, s = oracle.quantize(x, 1, INT8)
+    blk = x.reshape(64, 4, 32).astype(np.float64)
+    _, ex = np.frexp(np.abs(blk).max(axis=2))
+    q = np.rint(blk * np.exp2(127.0 - (ex - 1 + 127))[..., None] * 64)  # rint: ties to even
+    q = np.clip(q, -127, 127).astype(np.int8).reshape(64, 128)
+    assert np.array_equal(q.view(np.uint8), e)
+    assert np.array_equal((ex - 1 + 127).astype(np.uint8), s)
+
+
+@pytest.mark.parametrize("fmt", range(6))
+def test_packing_layout_and_sizes(oracle, fmt):
+    """Table 1 widths: bytes(elements) = n*bits/8, bytes(scales) = n/32; element
+    j of a row occupies bits [j*w, (j+1)*w) little-endian."""
+    x = inputs.gaussian_f32((8, 64), seed=2)
+    e, s = oracle.quantize(x, 1, fmt)
+    w = BITS[fmt]
+    assert e.shape == (8, 64 * w // 8) and s.shape == (8, 2)
+    codes = unpack(e, w)
+    for r in range(8):
+        for b in range(2):
+            sb, cb = oracle.quantize_block(x[r, 32 * b: 32 * b + 32].astype(np.float64), fmt)
+            assert sb == s[r, b] and np.array_equal(cb, codes[r, 32 * b: 32 * b + 32])
+    if w == 4:   # two per byte, even element in the low nibble
+        assert np.array_equal(e[:, 0], (codes[:, 0] | (codes[:, 1] << 4)).astype(np.uint8))
+    if w == 6:   # four per three bytes
+        word = codes[:, 0] | (codes[:, 1] << 6) | (codes[:, 2] << 12) | (codes[:, 3] << 18)
+        assert np.array_equal(e[:, 0], (word & 0xFF).astype(np.uint8))
+        assert np.array_equal(e[:, 1], ((word >> 8) & 0xFF).astype(np.uint8))
+        assert np.array_equal(e[:, 2], ((word >> 16) & 0xFF).astype(np.uint8))
+
+
+def test_rejects_bad_shapes(oracle):
+    x = np.zeros((32, 48), dtype=np.float32)
+    with pytest.raises(ValueError):
+        oracle.quantize(x, 1, E4M3)          # 48 is not a multiple of 32
+    oracle.quantize(x, 0, E4M3)              # 32 rows along axis 0 is fine
+    with pytest.raises(ValueError):
+        oracle.quantize(np.zeros((48, 32), dtype=np.float32), 0, E4M3)
+
+
+def test_adversarial_generator_covers_special_blocks(oracle):
+    x = inputs.adversarial_f32(64, 256, seed=0)
+    for fmt in range(6):
+        e, s = oracle.quantize(x, 1, fmt)
+        if fmt in (E3M2, E2M3, E2M1, INT8):
+            assert (s == 0xFF).any()
+        else:
+            assert not (s == 0xFF).any()
+        assert (s == 0).any()
