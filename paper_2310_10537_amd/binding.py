@@ -1,0 +1,149 @@
+"""ctypes binding of libmx.so (C ABI in include/mx.h).
+
+Argument marshalling only: every step of the cast, the dequantize and the GEMM
+runs in the HIP kernels of the library.  PyTorch is used for device memory and
+for the current stream.  There is no fallback: a missing library is an error.
+"""
+import ctypes
+import os
+
+import torch
+
+FP8_E4M3, FP8_E5M2, FP6_E3M2, FP6_E2M3, FP4_E2M1, INT8 = range(6)
+FORMAT_NAMES = ("fp8_e4m3", "fp8_e5m2", "fp6_e3m2", "fp6_e2m3", "fp4_e2m1", "int8")
+FORMAT_BITS = (8, 8, 6, 6, 4, 8)
+ROUND_RNE, ROUND_HALF_AWAY = 0, 1
+DT_F32, DT_BF16 = 0, 1
+MX_OK = 0
+BLOCK = 32
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmx.so")
+_lib = None
+
+
+class MxError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"mx status {status}: {text}")
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library with argument types declared."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2310_10537_amd.build` "
+                "(hipcc, --offload-arch=gfx950); there is no CPU fallback")
+        L = ctypes.CDLL(_LIB_PATH)
+        i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        L.mx_elem_bytes.argtypes = [ci, i64, i64, ci]
+        L.mx_elem_bytes.restype = ctypes.c_size_t
+        L.mx_scale_bytes.argtypes = [i64, i64, ci]
+        L.mx_scale_bytes.restype = ctypes.c_size_t
+        L.mx_quantize.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp]
+        L.mx_dequantize.argtypes = [vp, vp, ci, i64, i64, ci, vp, ci, i64, vp]
+        L.mx_gemm.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, ci, i64, vp]
+        L.mx_gemm_qa.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
+        L.mx_strerror.argtypes = [ci]
+        L.mx_strerror.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != MX_OK:
+        raise MxError(status, lib().mx_strerror(status).decode())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return DT_F32
+    if t.dtype == torch.bfloat16:
+        return DT_BF16
+    raise TypeError("tensor must be float32 or bfloat16")
+
+
+def _dev(t: torch.Tensor, name: str):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+
+
+def mx_elem_bytes(fmt, rows, cols, axis=1):
+    return lib().mx_elem_bytes(fmt, rows, cols, axis)
+
+
+def mx_scale_bytes(rows, cols, axis=1):
+    return lib().mx_scale_bytes(rows, cols, axis)
+
+
+def mx_strerror(status):
+    return lib().mx_strerror(status).decode()
+
+
+def mx_quantize(src, axis, fmt, rnd=ROUND_RNE, elems_out=None, scales_out=None, stream=None):
+    """src: 2-D device tensor (float32 / bfloat16, last dim contiguous).
+    Returns (elems uint8 [n_out, len*bits/8], scales uint8 [n_out, len/32])."""
+    _dev(src, "src")
+    assert src.dim() == 2 and (src.shape[1] == 0 or src.stride(1) == 1)
+    rows, cols = src.shape
+    ld = src.stride(0) if rows > 1 else cols
+    n_out, length = (rows, cols) if axis == 1 else (cols, rows)
+    w = FORMAT_BITS[fmt] if 0 <= fmt < 6 else 8
+    if elems_out is None:
+        elems_out = torch.empty((n_out, length * w // 8), dtype=torch.uint8, device=src.device)
+    if scales_out is None:
+        scales_out = torch.empty((n_out, length // BLOCK), dtype=torch.uint8, device=src.device)
+    _check(lib().mx_quantize(src.data_ptr(), _dt(src), rows, cols, ld, axis, fmt, rnd,
+                             elems_out.data_ptr(), scales_out.data_ptr(), _stream(stream)))
+    return elems_out, scales_out
+
+
+def mx_dequantize(elems, scales, fmt, rows, cols, axis, dtype=torch.float32, out=None, stream=None):
+    """Returns the row-major [rows, cols] tensor of X * P."""
+    _dev(elems, "elems")
+    _dev(scales, "scales")
+    if out is None:
+        out = torch.empty((rows, cols), dtype=dtype, device=elems.device)
+    ld = out.stride(0) if rows > 1 else cols
+    _check(lib().mx_dequantize(elems.data_ptr(), scales.data_ptr(), fmt, rows, cols, axis,
+                               out.data_ptr(), _dt(out), ld, _stream(stream)))
+    return out
+
+
+def mx_gemm(A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, K, dtype=torch.float32, out=None, stream=None):
+    """C[M, N] = A[M, K] . B[N, K]^T on MX operands blocked along K."""
+    for t, n in ((A_elems, "A_elems"), (A_scales, "A_scales"), (B_elems, "B_elems"), (B_scales, "B_scales")):
+        _dev(t, n)
+    M, N = A_scales.shape[0], B_scales.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=dtype, device=A_elems.device)
+    ldc = out.stride(0) if M > 1 else N
+    _check(lib().mx_gemm(M, N, K, A_elems.data_ptr(), A_scales.data_ptr(), fmtA,
+                         B_elems.data_ptr(), B_scales.data_ptr(), fmtB,
+                         out.data_ptr(), _dt(out), ldc, _stream(stream)))
+    return out
+
+
+def mx_gemm_qa(A_bf16, fmtA, rnd, B_elems, B_scales, fmtB, dtype=torch.float32, out=None, stream=None):
+    """Same product with A given as raw bf16 [M, K] and cast to fmtA on load."""
+    _dev(A_bf16, "A_bf16")
+    _dev(B_elems, "B_elems")
+    _dev(B_scales, "B_scales")
+    assert A_bf16.dtype == torch.bfloat16 and A_bf16.dim() == 2
+    M, K = A_bf16.shape
+    N = B_scales.shape[0]
+    lda = A_bf16.stride(0) if M > 1 else K
+    if out is None:
+        out = torch.empty((M, N), dtype=dtype, device=A_bf16.device)
+    ldc = out.stride(0) if M > 1 else N
+    _check(lib().mx_gemm_qa(M, N, K, A_bf16.data_ptr(), lda, fmtA, rnd,
+                            B_elems.data_ptr(), B_scales.data_ptr(), fmtB,
+                            out.data_ptr(), _dt(out), ldc, _stream(stream)))
+    return out

@@ -1,0 +1,117 @@
+// C ABI of the MX library (see include/mx.h): argument validation and
+// dispatch.  No state, no allocation; every call enqueues on the caller's stream.
+#include "../../include/mx.h"
+
+#include "mx_device.hpp"
+#include "mx_launch.hpp"
+
+namespace {
+
+bool fmt_ok(int f) { return f >= 0 && f < mx::NUM_FORMATS; }
+bool dt_ok(int d) { return d == MX_DT_F32 || d == MX_DT_BF16; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+int esize(int dt) { return dt == MX_DT_BF16 ? 2 : 4; }
+
+int tensor_shape_status(int64_t rows, int64_t cols, int axis, int64_t ld)
+{
+    if (rows < 0 || cols < 0) return MX_ERR_SHAPE;
+    if ((axis == 1 ? cols : rows) % mx::BLOCK) return MX_ERR_SHAPE;
+    if (ld < cols) return MX_ERR_SHAPE;
+    return MX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t mx_elem_bytes(mx_format_t fmt, int64_t rows, int64_t cols, int axis)
+{
+    (void)axis;
+    if (!fmt_ok(fmt) || rows < 0 || cols < 0) return 0;
+    return (size_t)rows * (size_t)cols * (size_t)mx::fmt_bits(fmt) / 8;
+}
+
+size_t mx_scale_bytes(int64_t rows, int64_t cols, int axis)
+{
+    (void)axis;
+    if (rows < 0 || cols < 0) return 0;
+    return (size_t)rows * (size_t)cols / mx::BLOCK;
+}
+
+int mx_quantize(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols, int64_t ld, int axis, mx_format_t fmt,
+                mx_round_t rnd, void *elems_out, uint8_t *scales_out, void *hip_stream)
+{
+    if (!fmt_ok(fmt) || !dt_ok(src_dt) || (rnd != MX_ROUND_RNE && rnd != MX_ROUND_HALF_AWAY) || (axis != 0 && axis != 1))
+        return MX_ERR_ENUM;
+    if (int st = tensor_shape_status(rows, cols, axis, ld)) return st;
+    if (rows == 0 || cols == 0) return MX_OK;
+    if (!src || !elems_out || !scales_out) return MX_ERR_NULL;
+    if (!aligned16(src) || !aligned16(elems_out) || !aligned16(scales_out) || (ld * esize(src_dt)) % 16)
+        return MX_ERR_ALIGN;
+    hipError_t e = mx::launch_cast(src, src_dt, rows, cols, ld, axis, fmt, rnd, static_cast<uint8_t *>(elems_out),
+                                   scales_out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+}
+
+int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt, int64_t rows, int64_t cols, int axis,
+                  void *dst, mx_dtype_t dst_dt, int64_t ld, void *hip_stream)
+{
+    if (!fmt_ok(fmt) || !dt_ok(dst_dt) || (axis != 0 && axis != 1)) return MX_ERR_ENUM;
+    if (int st = tensor_shape_status(rows, cols, axis, ld)) return st;
+    if (rows == 0 || cols == 0) return MX_OK;
+    if (!elems || !scales || !dst) return MX_ERR_NULL;
+    if (!aligned16(elems) || !aligned16(scales) || !aligned16(dst) || (ld * esize(dst_dt)) % 16) return MX_ERR_ALIGN;
+    hipError_t e = mx::launch_dequant(static_cast<const uint8_t *>(elems), scales, fmt, rows, cols, axis, dst, dst_dt, ld,
+                                      static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+}
+
+static int gemm_common(bool qa, int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_t *A_scales,
+                       const void *A_bf16, int64_t lda, int rnd, mx_format_t fmtA, const void *B_elems, const uint8_t *B_scales,
+                       mx_format_t fmtB, void *C, mx_dtype_t c_dt, int64_t ldc, void *hip_stream)
+{
+    if (!fmt_ok(fmtA) || !fmt_ok(fmtB) || !dt_ok(c_dt)) return MX_ERR_ENUM;
+    if (qa && rnd != MX_ROUND_RNE && rnd != MX_ROUND_HALF_AWAY) return MX_ERR_ENUM;
+    if (M < 0 || N < 0 || K < 0 || K % mx::BLOCK || ldc < N || (qa && lda < K)) return MX_ERR_SHAPE;
+    if (fmtA == MX_INT8 || fmtB == MX_INT8) return MX_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return MX_OK;
+    if (!C || (K > 0 && ((qa ? !A_bf16 : (!A_elems || !A_scales)) || !B_elems || !B_scales))) return MX_ERR_NULL;
+    if (!aligned16(B_elems) || !aligned16(B_scales) || !aligned16(C)) return MX_ERR_ALIGN;
+    if (qa ? (!aligned16(A_bf16) || (lda * 2) % 16) : (!aligned16(A_elems) || !aligned16(A_scales))) return MX_ERR_ALIGN;
+    hipError_t e = mx::launch_gemm(M, N, K, static_cast<const uint8_t *>(A_elems), A_scales, qa ? A_bf16 : nullptr, lda, rnd, fmtA,
+                                   static_cast<const uint8_t *>(B_elems), B_scales, fmtB, C, c_dt, ldc,
+                                   static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+}
+
+int mx_gemm(int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
+            const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB, void *C, mx_dtype_t c_dt, int64_t ldc,
+            void *hip_stream)
+{
+    return gemm_common(false, M, N, K, A_elems, A_scales, nullptr, 0, MX_ROUND_RNE, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc,
+                       hip_stream);
+}
+
+int mx_gemm_qa(int64_t M, int64_t N, int64_t K, const void *A_bf16, int64_t lda, mx_format_t fmtA, mx_round_t rnd,
+               const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB, void *C, mx_dtype_t c_dt, int64_t ldc,
+               void *hip_stream)
+{
+    return gemm_common(true, M, N, K, nullptr, nullptr, A_bf16, lda, rnd, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc,
+                       hip_stream);
+}
+
+const char *mx_strerror(int status)
+{
+    switch (status) {
+        case MX_OK: return "ok";
+        case MX_ERR_NULL: return "a required pointer is NULL";
+        case MX_ERR_ENUM: return "format, rounding, dtype or axis out of range";
+        case MX_ERR_SHAPE: return "bad shape: negative size, block axis not a multiple of 32, or leading dimension too small";
+        case MX_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
+        case MX_ERR_UNSUPPORTED: return "MX_INT8 operands are not supported by the GEMM";
+        case MX_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

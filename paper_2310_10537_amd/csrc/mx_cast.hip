@@ -1,0 +1,220 @@
+// MX cast kernels (Algorithm 1, Section 3 of arXiv 2310.10537) for gfx950.
+//
+//   cast_row_kernel  blocks of 32 along the contiguous axis.  A lane owns EPL
+//                    consecutive elements (8, 16 or 32), 32/EPL adjacent lanes
+//                    share a block; the block maximum is an integer max over
+//                    the magnitude bits combined across lanes with DPP.
+//   cast_col_kernel  blocks of 32 along dimension 0, output stored as the cast
+//                    of the transpose.  A work-group stages a [128 x 64] tile
+//                    in LDS with coalesced row loads; each lane then walks one
+//                    column of one 32-row block, so the maximum is in-lane, and
+//                    four adjacent lanes write one contiguous output line.
+#include "mx_device.hpp"
+#include "mx_launch.hpp"
+
+namespace mx {
+
+// ---------------------------------------------------------------------------
+// Source loaders: N consecutive elements as Float32 bit patterns.
+// ---------------------------------------------------------------------------
+template <int SRC, int N>
+__device__ __forceinline__ void load_as_f32_bits(const void *p, uint32_t (&v)[N])
+{
+    if (SRC == DT_BF16) {
+        static_assert(N % 8 == 0, "");
+#pragma unroll
+        for (int i = 0; i < N / 8; i++) {
+            uint4 d = ld16(reinterpret_cast<const char *>(p) + 16 * i);
+            const uint32_t dw[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                v[8 * i + 2 * j] = dw[j] << 16;
+                v[8 * i + 2 * j + 1] = dw[j] & 0xFFFF0000u;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < N / 4; i++) {
+            uint4 d = ld16(reinterpret_cast<const char *>(p) + 16 * i);
+            v[4 * i] = d.x; v[4 * i + 1] = d.y; v[4 * i + 2] = d.z; v[4 * i + 3] = d.w;
+        }
+    }
+}
+
+struct __attribute__((packed, aligned(4))) dword3 { uint32_t a, b, c; };
+
+// store ND dwords to a pointer aligned to min(16, largest power of two dividing 4*ND)
+template <int ND>
+__device__ __forceinline__ void store_dwords(void *p, const uint32_t *d)
+{
+    char *c = reinterpret_cast<char *>(p);
+    if (ND % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < ND / 4; i++) st16(c + 16 * i, make_uint4(d[4 * i], d[4 * i + 1], d[4 * i + 2], d[4 * i + 3]));
+    } else if (ND % 2 == 0) {
+#pragma unroll
+        for (int i = 0; i < ND / 2; i++) *reinterpret_cast<uint2 *>(c + 8 * i) = make_uint2(d[2 * i], d[2 * i + 1]);
+    } else if (ND == 3) {
+        dword3 t{d[0], d[1], d[2]};
+        *reinterpret_cast<dword3 *>(c) = t;
+    } else {
+#pragma unroll
+        for (int i = 0; i < ND; i++) *reinterpret_cast<uint32_t *>(c + 4 * i) = d[i];
+    }
+}
+
+// Quantize the N elements a lane holds, given the block's scale byte.
+template <int FMT, int RND, int N>
+__device__ __forceinline__ void encode_lane(const uint32_t (&v)[N], uint32_t s, uint32_t *packed)
+{
+    uint32_t c[N];
+    if (!Fmt<FMT>::elem_nan && s == SCALE_NAN) {
+#pragma unroll
+        for (int i = 0; i < N; i++) c[i] = 0;
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; i++) c[i] = encode_elem<FMT, RND>(v[i], s);
+    }
+    pack_codes<FMT, N>(c, packed);
+}
+
+// ---------------------------------------------------------------------------
+// Row cast.  unit = one lane-iteration = EPL elements; units are numbered in
+// row-major order over the tensor, so unit u belongs to block u / G.
+// ---------------------------------------------------------------------------
+template <int SRC, int FMT, int RND, int EPL>
+__global__ __launch_bounds__(256) void cast_row_kernel(const void *__restrict__ src, int64_t cols, int64_t ld,
+                                                       uint8_t *__restrict__ elems, uint8_t *__restrict__ scales,
+                                                       int64_t n_units)
+{
+    constexpr int G = BLOCK / EPL;
+    constexpr int w = Fmt<FMT>::bits;
+    constexpr int esz = SRC == DT_BF16 ? 2 : 4;
+    constexpr int ND = EPL * w / 32;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const int64_t units_per_row = cols / EPL;
+    const bool flat = (ld == cols);
+
+    for (int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x; u < n_units; u += stride) {
+        int64_t off;  // element offset of this lane's first element
+        if (flat) {
+            off = u * EPL;
+        } else {
+            int64_t r = u / units_per_row;
+            off = r * ld + (u - r * units_per_row) * EPL;
+        }
+        uint32_t v[EPL];
+        load_as_f32_bits<SRC, EPL>(reinterpret_cast<const char *>(src) + off * esz, v);
+
+        uint32_t amax = 0;
+#pragma unroll
+        for (int i = 0; i < EPL; i++) {
+            uint32_t k = amax_key<FMT>(v[i]);
+            amax = amax > k ? amax : k;
+        }
+        amax = group_max<G>(amax);
+        const uint32_t s = scale_byte<FMT>(amax);
+
+        uint32_t packed[ND];
+        encode_lane<FMT, RND, EPL>(v, s, packed);
+        store_dwords<ND>(elems + u * (EPL * w / 8), packed);
+        if (G == 1 || (threadIdx.x & (G - 1)) == 0) scales[u / G] = (uint8_t)s;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Column cast (blocks along dimension 0), simple form: one lane per
+// (32-row block, column), adjacent lanes take adjacent columns so that every
+// load instruction of a wave reads one contiguous run of a source row.
+// ---------------------------------------------------------------------------
+template <int SRC, int FMT, int RND>
+__global__ __launch_bounds__(256) void cast_col_simple_kernel(const void *__restrict__ src, int64_t rows, int64_t cols,
+                                                              int64_t ld, uint8_t *__restrict__ elems,
+                                                              uint8_t *__restrict__ scales)
+{
+    constexpr int w = Fmt<FMT>::bits;
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t rb = blockIdx.y;
+    if (c >= cols) return;
+    uint32_t v[BLOCK];
+#pragma unroll
+    for (int i = 0; i < BLOCK; i++) {
+        int64_t idx = (rb * BLOCK + i) * ld + c;
+        if (SRC == DT_BF16) v[i] = (uint32_t)reinterpret_cast<const uint16_t *>(src)[idx] << 16;
+        else v[i] = reinterpret_cast<const uint32_t *>(src)[idx];
+    }
+    uint32_t amax = 0;
+#pragma unroll
+    for (int i = 0; i < BLOCK; i++) {
+        uint32_t k = amax_key<FMT>(v[i]);
+        amax = amax > k ? amax : k;
+    }
+    const uint32_t s = scale_byte<FMT>(amax);
+    uint32_t packed[w];
+    encode_lane<FMT, RND, BLOCK>(v, s, packed);
+    const int64_t nrb = rows / BLOCK;
+    store_dwords<w>(elems + (c * nrb + rb) * (BLOCK * w / 8), packed);
+    scales[c * nrb + rb] = (uint8_t)s;
+}
+
+// ---------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------
+template <int SRC, int FMT, int RND>
+static hipError_t launch_row(const void *src, int64_t rows, int64_t cols, int64_t ld, uint8_t *elems, uint8_t *scales,
+                             hipStream_t st)
+{
+    // FP6 needs at least 16 elements per lane to store whole dwords
+    constexpr int EPL = (Fmt<FMT>::bits == 6) ? 16 : 8;
+    const int64_t n_units = rows * cols / EPL;
+    int64_t nb = (n_units + 255) / 256;
+    const int64_t cap = 256 * 32;   // enough work-groups to fill 256 CUs several times over
+    if (nb > cap) nb = cap;
+    hipLaunchKernelGGL((cast_row_kernel<SRC, FMT, RND, EPL>), dim3((unsigned)nb), dim3(256), 0, st, src, cols, ld, elems,
+                       scales, n_units);
+    return hipGetLastError();
+}
+
+template <int SRC, int FMT, int RND>
+static hipError_t launch_col(const void *src, int64_t rows, int64_t cols, int64_t ld, uint8_t *elems, uint8_t *scales,
+                             hipStream_t st)
+{
+    dim3 grid((unsigned)((cols + 255) / 256), (unsigned)(rows / BLOCK));
+    hipLaunchKernelGGL((cast_col_simple_kernel<SRC, FMT, RND>), grid, dim3(256), 0, st, src, rows, cols, ld, elems, scales);
+    return hipGetLastError();
+}
+
+template <int SRC, int FMT>
+static hipError_t dispatch_rnd(int rnd, int axis, const void *src, int64_t rows, int64_t cols, int64_t ld, uint8_t *elems,
+                               uint8_t *scales, hipStream_t st)
+{
+    if (axis == 1) {
+        return rnd == ROUND_RNE ? launch_row<SRC, FMT, ROUND_RNE>(src, rows, cols, ld, elems, scales, st)
+                                : launch_row<SRC, FMT, ROUND_HALF_AWAY>(src, rows, cols, ld, elems, scales, st);
+    }
+    return rnd == ROUND_RNE ? launch_col<SRC, FMT, ROUND_RNE>(src, rows, cols, ld, elems, scales, st)
+                            : launch_col<SRC, FMT, ROUND_HALF_AWAY>(src, rows, cols, ld, elems, scales, st);
+}
+
+template <int SRC>
+static hipError_t dispatch_fmt(int fmt, int rnd, int axis, const void *src, int64_t rows, int64_t cols, int64_t ld,
+                               uint8_t *elems, uint8_t *scales, hipStream_t st)
+{
+    switch (fmt) {
+        case FP8_E4M3: return dispatch_rnd<SRC, FP8_E4M3>(rnd, axis, src, rows, cols, ld, elems, scales, st);
+        case FP8_E5M2: return dispatch_rnd<SRC, FP8_E5M2>(rnd, axis, src, rows, cols, ld, elems, scales, st);
+        case FP6_E3M2: return dispatch_rnd<SRC, FP6_E3M2>(rnd, axis, src, rows, cols, ld, elems, scales, st);
+        case FP6_E2M3: return dispatch_rnd<SRC, FP6_E2M3>(rnd, axis, src, rows, cols, ld, elems, scales, st);
+        case FP4_E2M1: return dispatch_rnd<SRC, FP4_E2M1>(rnd, axis, src, rows, cols, ld, elems, scales, st);
+        default:       return dispatch_rnd<SRC, INT8>(rnd, axis, src, rows, cols, ld, elems, scales, st);
+    }
+}
+
+hipError_t launch_cast(const void *src, int src_dt, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,
+                       uint8_t *elems, uint8_t *scales, hipStream_t st)
+{
+    return src_dt == DT_BF16 ? dispatch_fmt<DT_BF16>(fmt, rnd, axis, src, rows, cols, ld, elems, scales, st)
+                             : dispatch_fmt<DT_F32>(fmt, rnd, axis, src, rows, cols, ld, elems, scales, st);
+}
+
+}  // namespace mx

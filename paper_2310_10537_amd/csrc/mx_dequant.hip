@@ -1,0 +1,113 @@
+// MX dequantize kernels: v = X * P (Section 2 of arXiv 2310.10537) for gfx950.
+// One lane turns 8 consecutive element codes of a block (w bytes) into 8 values.
+#include "mx_device.hpp"
+#include "mx_launch.hpp"
+
+namespace mx {
+
+// 8 codes = w bytes starting at a w-byte-aligned address
+template <int FMT>
+__device__ __forceinline__ void load_codes8(const uint8_t *p, uint32_t (&c)[8])
+{
+    constexpr int w = Fmt<FMT>::bits;
+    uint64_t bits;
+    if (w == 8) {
+        uint2 d = *reinterpret_cast<const uint2 *>(p);
+        bits = (uint64_t)d.x | ((uint64_t)d.y << 32);
+    } else if (w == 4) {
+        bits = *reinterpret_cast<const uint32_t *>(p);
+    } else {
+        const uint16_t *h = reinterpret_cast<const uint16_t *>(p);
+        bits = (uint64_t)h[0] | ((uint64_t)h[1] << 16) | ((uint64_t)h[2] << 32);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i++) c[i] = (uint32_t)(bits >> (w * i)) & ((1u << w) - 1u);
+}
+
+// TR = false: dst[o][l .. l+7] contiguous (blocks along the last axis).
+// TR = true : the MX tensor is the cast of the transpose; value (o, l) goes to dst[l][o].
+template <int FMT, int DST, bool TR>
+__global__ __launch_bounds__(256) void dequant_kernel(const uint8_t *__restrict__ elems,
+                                                      const uint8_t *__restrict__ scales, void *__restrict__ dst,
+                                                      int64_t n_out, int64_t len, int64_t ld)
+{
+    constexpr int w = Fmt<FMT>::bits;
+    const int64_t units_per_row = len / 8;
+    const int64_t n_units = n_out * units_per_row;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x; u < n_units; u += stride) {
+        int64_t o, l;
+        if (TR) {   // adjacent lanes take adjacent o so that the strided stores coalesce across the wave
+            l = (u / n_out) * 8;
+            o = u % n_out;
+        } else {
+            o = u / units_per_row;
+            l = (u % units_per_row) * 8;
+        }
+        const int64_t unit_in_tensor = o * units_per_row + l / 8;
+        uint32_t c[8];
+        load_codes8<FMT>(elems + unit_in_tensor * w, c);
+        const uint32_t s = scales[unit_in_tensor / 4];
+        float f[8];
+#pragma unroll
+        for (int i = 0; i < 8; i++) f[i] = decode_scaled<FMT>(c[i], s);
+        if (!TR) {
+            if (DST == DT_F32) {
+                float *d = reinterpret_cast<float *>(dst) + o * ld + l;
+                *reinterpret_cast<float4 *>(d) = make_float4(f[0], f[1], f[2], f[3]);
+                *reinterpret_cast<float4 *>(d + 4) = make_float4(f[4], f[5], f[6], f[7]);
+            } else {
+                uint32_t h[4];
+#pragma unroll
+                for (int i = 0; i < 4; i++) h[i] = f32_to_bf16_bits(f[2 * i]) | (f32_to_bf16_bits(f[2 * i + 1]) << 16);
+                st16(reinterpret_cast<uint16_t *>(dst) + o * ld + l, make_uint4(h[0], h[1], h[2], h[3]));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                if (DST == DT_F32) reinterpret_cast<float *>(dst)[(l + i) * ld + o] = f[i];
+                else reinterpret_cast<uint16_t *>(dst)[(l + i) * ld + o] = (uint16_t)f32_to_bf16_bits(f[i]);
+            }
+        }
+    }
+}
+
+template <int FMT, int DST>
+static hipError_t launch_t(const uint8_t *elems, const uint8_t *scales, int64_t rows, int64_t cols, int axis, void *dst,
+                           int64_t ld, hipStream_t st)
+{
+    const int64_t n_out = axis == 1 ? rows : cols;
+    const int64_t len = axis == 1 ? cols : rows;
+    int64_t nb = (n_out * (len / 8) + 255) / 256;
+    if (nb > 256 * 32) nb = 256 * 32;
+    if (axis == 1)
+        hipLaunchKernelGGL((dequant_kernel<FMT, DST, false>), dim3((unsigned)nb), dim3(256), 0, st, elems, scales, dst,
+                           n_out, len, ld);
+    else
+        hipLaunchKernelGGL((dequant_kernel<FMT, DST, true>), dim3((unsigned)nb), dim3(256), 0, st, elems, scales, dst,
+                           n_out, len, ld);
+    return hipGetLastError();
+}
+
+template <int DST>
+static hipError_t launch_f(int fmt, const uint8_t *elems, const uint8_t *scales, int64_t rows, int64_t cols, int axis,
+                           void *dst, int64_t ld, hipStream_t st)
+{
+    switch (fmt) {
+        case FP8_E4M3: return launch_t<FP8_E4M3, DST>(elems, scales, rows, cols, axis, dst, ld, st);
+        case FP8_E5M2: return launch_t<FP8_E5M2, DST>(elems, scales, rows, cols, axis, dst, ld, st);
+        case FP6_E3M2: return launch_t<FP6_E3M2, DST>(elems, scales, rows, cols, axis, dst, ld, st);
+        case FP6_E2M3: return launch_t<FP6_E2M3, DST>(elems, scales, rows, cols, axis, dst, ld, st);
+        case FP4_E2M1: return launch_t<FP4_E2M1, DST>(elems, scales, rows, cols, axis, dst, ld, st);
+        default:       return launch_t<INT8, DST>(elems, scales, rows, cols, axis, dst, ld, st);
+    }
+}
+
+hipError_t launch_dequant(const uint8_t *elems, const uint8_t *scales, int fmt, int64_t rows, int64_t cols, int axis,
+                          void *dst, int dst_dt, int64_t ld, hipStream_t st)
+{
+    return dst_dt == DT_F32 ? launch_f<DT_F32>(fmt, elems, scales, rows, cols, axis, dst, ld, st)
+                            : launch_f<DT_BF16>(fmt, elems, scales, rows, cols, axis, dst, ld, st);
+}
+
+}  // namespace mx

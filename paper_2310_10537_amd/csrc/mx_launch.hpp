@@ -1,0 +1,21 @@
+// Host-side launch entry points shared between the kernel files and the C ABI.
+// Each returns the hipError_t of the launch; arguments are validated by the caller.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mx {
+
+hipError_t launch_cast(const void *src, int src_dt, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,
+                       uint8_t *elems, uint8_t *scales, hipStream_t st);
+
+hipError_t launch_dequant(const uint8_t *elems, const uint8_t *scales, int fmt, int64_t rows, int64_t cols, int axis,
+                          void *dst, int dst_dt, int64_t ld, hipStream_t st);
+
+// a_bf16 != nullptr selects the quantize-on-load form (A_elems / A_scales unused).
+hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, const uint8_t *A_scales,
+                       const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
+                       const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st);
+
+}  // namespace mx

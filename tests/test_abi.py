@@ -1,0 +1,84 @@
+"""The C-ABI library loads and exports every symbol include/mx.h declares, and
+its argument validation (which runs before any HIP call) returns the documented
+status codes.  No GPU needed: nothing here launches a kernel."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2310_10537_amd import binding
+    if not os.path.exists(binding._LIB_PATH):
+        from paper_2310_10537_amd import build
+        build.build()
+    return binding.lib()
+
+
+def test_exports_match_header(L):
+    text = open(os.path.join(ROOT, "include", "mx.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(mx_[a-z_]+)\s*\(", text))
+    assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_dequantize", "mx_gemm", "mx_gemm_qa",
+                     "mx_strerror"}
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_sizes(L):
+    assert L.mx_elem_bytes(0, 1024, 1024, 1) == 1024 * 1024
+    assert L.mx_elem_bytes(2, 64, 64, 0) == 64 * 64 * 6 // 8
+    assert L.mx_elem_bytes(4, 8192, 8192, 1) == 8192 * 8192 // 2
+    assert L.mx_scale_bytes(8192, 8192, 0) == 8192 * 8192 // 32
+    assert L.mx_elem_bytes(9, 4, 32, 1) == 0
+
+
+def test_status_codes(L):
+    OK, NULL, ENUM, SHAPE, ALIGN, UNSUP = 0, 1, 2, 3, 4, 5
+    p = 0x1000  # an aligned non-null address; validation fails before it is ever used
+    q = L.mx_quantize
+    assert q(None, 1, 32, 32, 32, 1, 0, 0, p, p, None) == NULL
+    assert q(p, 1, 32, 32, 32, 1, 6, 0, p, p, None) == ENUM
+    assert q(p, 2, 32, 32, 32, 1, 0, 0, p, p, None) == ENUM
+    assert q(p, 1, 32, 32, 32, 1, 0, 2, p, p, None) == ENUM
+    assert q(p, 1, 32, 32, 32, 2, 0, 0, p, p, None) == ENUM
+    assert q(p, 1, 32, 48, 48, 1, 0, 0, p, p, None) == SHAPE     # block axis not a multiple of 32
+    assert q(p, 1, 48, 32, 32, 0, 0, 0, p, p, None) == SHAPE
+    assert q(p, 1, -1, 32, 32, 1, 0, 0, p, p, None) == SHAPE
+    assert q(p, 1, 32, 64, 32, 1, 0, 0, p, p, None) == SHAPE     # ld < cols
+    assert q(p + 2, 1, 32, 32, 32, 1, 0, 0, p, p, None) == ALIGN
+    assert q(p, 1, 32, 32, 36, 1, 0, 0, p, p, None) == ALIGN     # 36 bf16 = 72 bytes per row
+    assert q(p, 1, 32, 32, 32, 1, 0, 0, p, p + 8, None) == ALIGN
+    assert q(None, 1, 0, 32, 32, 1, 0, 0, None, None, None) == OK  # empty: nothing to do
+    assert q(None, 1, 32, 0, 0, 0, 0, 0, None, None, None) == OK
+    d = L.mx_dequantize
+    assert d(p, None, 0, 32, 32, 1, p, 0, 32, None) == NULL
+    assert d(p, p, 0, 32, 40, 1, p, 0, 40, None) == SHAPE
+    assert d(p, p, 7, 32, 32, 1, p, 0, 32, None) == ENUM
+    assert d(p, p, 0, 32, 32, 1, p + 4, 0, 32, None) == ALIGN
+    g = L.mx_gemm
+    assert g(16, 16, 32, p, p, 0, p, p, 0, None, 0, 16, None) == NULL
+    assert g(16, 16, 48, p, p, 0, p, p, 0, p, 0, 16, None) == SHAPE
+    assert g(16, 16, 32, p, p, 0, p, p, 0, p, 0, 8, None) == SHAPE   # ldc < N
+    assert g(16, 16, 32, p, p, 5, p, p, 0, p, 0, 16, None) == UNSUP  # MXINT8 operand
+    assert g(16, 16, 32, p, p, 0, p, p, 5, p, 0, 16, None) == UNSUP
+    assert g(16, 16, 32, p, p, 0, p, p, 0, p + 4, 1, 16, None) == ALIGN
+    assert g(0, 16, 32, None, None, 0, None, None, 0, None, 0, 16, None) == OK
+    ga = L.mx_gemm_qa
+    assert ga(16, 16, 32, None, 32, 0, 0, p, p, 0, p, 0, 16, None) == NULL
+    assert ga(16, 16, 32, p, 16, 0, 0, p, p, 0, p, 0, 16, None) == SHAPE  # lda < K
+    assert ga(16, 16, 32, p, 36, 0, 0, p, p, 0, p, 0, 16, None) == ALIGN
+    assert ga(16, 16, 32, p, 32, 0, 3, p, p, 0, p, 0, 16, None) == ENUM
+    for s in range(8):
+        assert isinstance(L.mx_strerror(s), bytes) and L.mx_strerror(s)
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    from paper_2310_10537_amd import binding
+    with pytest.raises(ValueError):
+        binding.mx_quantize(torch.zeros(32, 32), 1, 0)
