@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the MX hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One step = one pass of the whole hot path over seeded synthetic tensors that are
+already resident in HBM:
+  * 12 casts of an 8192 x 8192 bf16 activation tensor (Student-t(3), 0.1 % of the
+    entries x100, 0.01 % exact zeros): six element formats x {blocks along the
+    last axis, blocks along axis 0}, round-to-nearest-even;
+  * one dequantize (MXFP8 E4M3 -> bf16) of the same tensor;
+  * the transformer projection GEMM 8192 x 4096 x 4096, MXFP8 E4M3 x E4M3, bf16
+    output, once from pre-quantized operands (mx_gemm) and once with the bf16
+    activations cast on load (mx_gemm_qa).
+Inputs rotate over three copies so that no call finds its source in the 256 MB
+Infinity Cache.  Every call is bracketed by events on the stream it runs on; the
+headline value is the cast throughput (algorithmic bytes of the 12 casts divided
+by their summed durations); GEMM TFLOP/s are reported beside it.
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2310_10537_amd import binding as mx  # noqa: E402
+from paper_2310_10537_amd import inputs  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {8: 5000.0, 6: 10100.0, 4: 10100.0}
+ROWS = COLS = 8192
+GM, GK, GN = 8192, 4096, 4096
+NCOPY = 3
+
+
+def cast_bytes(fmt, n_elem):
+    """Algorithmic bytes of one cast: bf16 source + packed elements + scale bytes."""
+    return n_elem * (2.0 + mx.FORMAT_BITS[fmt] / 8.0 + 1.0 / 32.0)
+
+
+def to_dev_bf16(bits):
+    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+
+class Timed:
+    """Collects (label, start_event, end_event) on the current stream."""
+
+    def __init__(self):
+        self.recs = []
+
+    def run(self, label, fn):
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        self.recs.append((label, a, b))
+
+    def totals(self):
+        out = {}
+        for label, a, b in self.recs:
+            ms = a.elapsed_time(b)
+            t = out.setdefault(label, [0.0, 0])
+            t[0] += ms
+            t[1] += 1
+        return out
+
+
+def cpu_baseline(x_bits):
+    """The CPU reference as it stands, timed on the host cores on a bounded
+    sample: the first 4096 rows (axis-1 casts) / first 4096 columns (axis-0
+    casts) of the workload tensor, all 12 casts."""
+    import oracle
+    oracle.lib()
+    rows = np.ascontiguousarray(x_bits[:4096, :])
+    cols = np.ascontiguousarray(x_bits[:, :4096])
+    t0 = time.perf_counter()
+    nbytes = 0.0
+    for fmt in range(6):
+        oracle.quantize(rows, 1, fmt, 0)
+        oracle.quantize(cols, 0, fmt, 0)
+        nbytes += cast_bytes(fmt, rows.size) + cast_bytes(fmt, cols.size)
+    dt = time.perf_counter() - t0
+    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "12 casts (6 formats x 2 axes, RNE) of the first 4096 rows / first 4096 columns "
+                      "of the 8192x8192 bf16 workload tensor; %.1f s" % dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (no collectives exist in the MX hot path); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    mx.lib()  # fail loudly if the HIP library is missing
+
+    # ---- synthetic inputs, resident in HBM before the timed region --------------
+    x_bits = inputs.student_t_bf16((ROWS, COLS), seed=1)
+    xs = [to_dev_bf16(x_bits) for _ in range(NCOPY)]
+    a_bits = inputs.gaussian_bf16((GM, GK), seed=2)
+    As = [to_dev_bf16(a_bits) for _ in range(NCOPY)]
+    w = torch.from_numpy(inputs.gaussian_f32((GK, GN), seed=102, std=0.02)).cuda()
+    Be, Bs = mx.mx_quantize(w, 0, mx.FP8_E4M3)               # weights pre-quantized once: [N][K]
+    Aq = [mx.mx_quantize(a, 1, mx.FP8_E4M3) for a in As]
+    Cs = [torch.empty((GM, GN), dtype=torch.bfloat16, device="cuda") for _ in range(NCOPY)]
+    outs = {}
+    for fmt in range(6):
+        for axis in (1, 0):
+            outs[(fmt, axis)] = [(torch.empty((ROWS, COLS * mx.FORMAT_BITS[fmt] // 8), dtype=torch.uint8, device="cuda"),
+                                  torch.empty((ROWS, COLS // 32), dtype=torch.uint8, device="cuda")) for _ in range(2)]
+    deq_out = [torch.empty((ROWS, COLS), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    deq_in = mx.mx_quantize(xs[0], 1, mx.FP8_E4M3)
+    torch.cuda.synchronize()
+
+    rot = [0]
+
+    def step(timer):
+        for fmt in range(6):
+            for axis in (1, 0):
+                i = rot[0]
+                rot[0] += 1
+                e, s = outs[(fmt, axis)][i % 2]
+                timer.run(f"cast_{mx.FORMAT_NAMES[fmt]}_axis{axis}",
+                          lambda: mx.mx_quantize(xs[i % NCOPY], axis, fmt, mx.ROUND_RNE, e, s))
+        i = rot[0]
+        timer.run("dequantize_fp8_e4m3_bf16",
+                  lambda: mx.mx_dequantize(deq_in[0], deq_in[1], mx.FP8_E4M3, ROWS, COLS, 1, out=deq_out[i % 2]))
+        timer.run("gemm_fp8_e4m3",
+                  lambda: mx.mx_gemm(Aq[i % NCOPY][0], Aq[i % NCOPY][1], mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, GK,
+                                     out=Cs[i % NCOPY]))
+        timer.run("gemm_qa_fp8_e4m3",
+                  lambda: mx.mx_gemm_qa(As[(i + 1) % NCOPY], mx.FP8_E4M3, mx.ROUND_RNE, Be, Bs, mx.FP8_E4M3,
+                                        out=Cs[(i + 1) % NCOPY]))
+
+    warm = Timed()
+    for _ in range(args.warmup):
+        step(warm)
+    torch.cuda.synchronize()
+
+    timer = Timed()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(timer)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    tot = timer.totals()
+
+    n_elem = ROWS * COLS
+    cast_ms = 0.0
+    cast_b = 0.0
+    per_kernel = {}
+    for fmt in range(6):
+        for axis in (1, 0):
+            label = f"cast_{mx.FORMAT_NAMES[fmt]}_axis{axis}"
+            ms, n = tot[label]
+            avg = ms / n
+            cast_ms += avg
+            cast_b += cast_bytes(fmt, n_elem)
+            per_kernel[label] = {"avg_ms": round(avg, 5), "GBps": round(cast_bytes(fmt, n_elem) / avg / 1e6, 1)}
+    flop = 2.0 * GM * GN * GK
+    for label in ("gemm_fp8_e4m3", "gemm_qa_fp8_e4m3"):
+        ms, n = tot[label]
+        per_kernel[label] = {"avg_ms": round(ms / n, 5), "TFLOPs": round(flop / (ms / n) / 1e9, 1),
+                             "frac_mfma_peak": round(flop / (ms / n) / 1e9 / MFMA_PEAK_TFLOPS[8], 4)}
+    ms, n = tot["dequantize_fp8_e4m3_bf16"]
+    deq_b = n_elem * (1.0 + 1.0 / 32.0 + 2.0)
+    per_kernel["dequantize_fp8_e4m3_bf16"] = {"avg_ms": round(ms / n, 5), "GBps": round(deq_b / (ms / n) / 1e6, 1)}
+
+    # dominant kernel of the step by time: reported against its roofline
+    dom = max(tot, key=lambda k: tot[k][0])
+    dms = tot[dom][0] / tot[dom][1]
+    if dom.startswith("cast_"):
+        fmt = [i for i in range(6) if dom.startswith("cast_" + mx.FORMAT_NAMES[i])][0]
+        ach = cast_bytes(fmt, n_elem) / dms / 1e6
+        roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+    elif dom.startswith("gemm"):
+        ach = flop / dms / 1e9
+        roof = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_PEAK_TFLOPS[8],
+                "unit": "TFLOP/s", "frac": round(ach / MFMA_PEAK_TFLOPS[8], 4), "traffic": None}
+    else:
+        ach = deq_b / dms / 1e6
+        roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+
+    value = cast_b / cast_ms / 1e6   # GB/s over the 12 casts
+    line = {
+        "metric": "MX cast GB/s (% HBM peak) + MX GEMM TFLOPS (% scaled-MFMA peak)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall_ms / args.steps, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: mx_quantize of 8192x8192 bf16 Student-t(3) activations into 6 MX formats x 2 axes"
+                               " (+ dequantize, + configs[2] 8192x4096x4096 MXFP8 GEMM plain and quantize-on-load)"},
+        "cast_frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "gemm_tflops": per_kernel["gemm_fp8_e4m3"]["TFLOPs"],
+        "gemm_qa_tflops": per_kernel["gemm_qa_fp8_e4m3"]["TFLOPs"],
+        "roofline": roof,
+        "kernels": per_kernel,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(x_bits)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
