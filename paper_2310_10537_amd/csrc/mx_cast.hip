@@ -213,6 +213,10 @@ static hipError_t dispatch_fmt(int fmt, int rnd, int axis, const void *src, int6
 hipError_t launch_cast(const void *src, int src_dt, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,
                        uint8_t *elems, uint8_t *scales, hipStream_t st)
 {
+    if (src_dt == DT_BF16) {
+        hipError_t e = launch_cast_bf16_fast(src, rows, cols, ld, axis, fmt, rnd, elems, scales, st);
+        if (e != hipErrorNotSupported) return e;
+    }
     return src_dt == DT_BF16 ? dispatch_fmt<DT_BF16>(fmt, rnd, axis, src, rows, cols, ld, elems, scales, st)
                              : dispatch_fmt<DT_F32>(fmt, rnd, axis, src, rows, cols, ld, elems, scales, st);
 }

@@ -1,0 +1,294 @@
+// Bandwidth-oriented MX cast kernels for bf16 sources (Algorithm 1, Section 3 of
+// arXiv 2310.10537) on gfx950.  Both are pure streaming kernels bound by HBM:
+// per element they read 2 bytes and write bits/8 + 1/32 bytes.
+//
+//   cast_row_bf16_kernel   blocks along the contiguous axis.  A wave takes 2048
+//       consecutive elements as four fully coalesced 16-byte-per-lane loads
+//       (1 KB per instruction).  8-bit and 4-bit formats convert in place: four
+//       adjacent lanes share a block, the block maximum is a packed-u16 max
+//       finished with two DPP quad permutes.  FP6 converts 32 elements per
+//       instruction, so the wave transposes its 64 blocks through a private LDS
+//       region until each lane owns one block.  Scale bytes (and FP6 codes) are
+//       staged in LDS so that they leave as 16-byte stores.
+//   cast_col_bf16_kernel   blocks along dimension 0, output written as the cast of
+//       the transpose.  A work-group stages a [128 rows x 64 columns] tile in LDS
+//       with coalesced row loads (rows rotated by 32 bytes per 32-row block so
+//       that column reads are bank-conflict free); each lane then reads one
+//       column of one 32-row block -- the block maximum is in-lane -- and the four
+//       lanes of a column write one contiguous 128 / 96 / 64-byte output line.
+#include "mx_convert.hpp"
+#include "mx_launch.hpp"
+
+namespace mx {
+
+// Lanes of one wave exchange data through LDS without a work-group barrier: LDS
+// operations of a wave execute in order, so it is enough to keep the compiler
+// from moving accesses across this point and to wait for the wave's own writes.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+    __builtin_amdgcn_wave_barrier();
+}
+
+// ---------------------------------------------------------------------------
+// Row cast
+// ---------------------------------------------------------------------------
+constexpr int ROW_CHUNKS = 4;                 // 16-byte loads in flight per lane
+constexpr int ROW_WAVE_ELEMS = 64 * 8 * ROW_CHUNKS;   // 2048 elements = 64 blocks per wave
+
+// element offset of linear element index e in a [rows][cols] tensor with pitch ld
+template <bool FLAT>
+__device__ __forceinline__ int64_t src_offset(int64_t e, int64_t cols, int64_t ld)
+{
+    if (FLAT) return e;
+    int64_t r = e / cols;
+    return r * ld + (e - r * cols);
+}
+
+template <int FMT, int RND, bool FLAT>
+__global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__restrict__ src, int64_t cols, int64_t ld,
+                                                            uint8_t *__restrict__ elems, uint8_t *__restrict__ scales,
+                                                            int64_t n_elems)
+{
+    constexpr int w = Fmt<FMT>::bits;
+    constexpr bool SIX = (w == 6);
+    // per wave: FP6 needs 64 blocks x 80 bytes (padded) for the transpose; everyone needs 64 scale bytes
+    constexpr int LDS_PER_WAVE = SIX ? 64 * 80 : 64;
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * LDS_PER_WAVE];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint8_t *lds = lds_all + wave * LDS_PER_WAVE;
+
+    const int64_t wave_id = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t e0 = wave_id * ROW_WAVE_ELEMS;          // first element of this wave
+    if (e0 >= n_elems) return;                            // whole wave out of range
+    const int64_t blk0 = e0 / BLOCK;                      // first block of this wave
+
+    // ---- coalesced loads: chunk u, lane l -> elements e0 + u*512 + l*8 .. +7
+    uint32_t d[ROW_CHUNKS][4];
+    bool valid[ROW_CHUNKS];
+#pragma unroll
+    for (int u = 0; u < ROW_CHUNKS; u++) {
+        const int64_t e = e0 + u * 512 + lane * 8;
+        valid[u] = e < n_elems;
+        uint4 t = make_uint4(0, 0, 0, 0);
+        if (valid[u]) t = ld16(src + src_offset<FLAT>(e, cols, ld));
+        d[u][0] = t.x; d[u][1] = t.y; d[u][2] = t.z; d[u][3] = t.w;
+    }
+
+    if constexpr (!SIX) {
+        constexpr int OD = 8 * w / 32;   // output dwords per lane per chunk (2 or 1)
+#pragma unroll
+        for (int u = 0; u < ROW_CHUNKS; u++) {
+            uint32_t m = 0;
+#pragma unroll
+            for (int i = 0; i < 4; i++) m = pk_absmax(m, d[u][i]);
+            uint32_t amax16 = group_max<4>(pk_hmax(m));
+            uint32_t s = scale_from_bf16_max<FMT>(amax16);
+            uint32_t out[OD];
+            if (fast_ok(amax16, s)) {
+                convert_bf16_fast<FMT, RND, 4>(d[u], s, out);
+            } else {
+                // exact path; the condition is uniform over the four lanes of the block
+                uint32_t v[8];
+                widen_bf16<4>(d[u], v);
+                uint32_t amax = 0;
+#pragma unroll
+                for (int i = 0; i < 8; i++) {
+                    uint32_t k = amax_key<FMT>(v[i]);
+                    amax = amax > k ? amax : k;
+                }
+                amax = group_max<4>(amax);
+                s = scale_byte<FMT>(amax);
+                encode_exact<FMT, RND, 8>(v, s, out);
+            }
+            if (valid[u]) {
+                uint8_t *o = elems + (e0 + u * 512 + lane * 8) * w / 8;
+                if constexpr (OD == 2) *reinterpret_cast<uint2 *>(o) = make_uint2(out[0], out[1]);
+                else *reinterpret_cast<uint32_t *>(o) = out[0];
+            }
+            if ((lane & 3) == 0) lds[u * 16 + (lane >> 2)] = (uint8_t)s;   // block u*16 + lane/4 of this wave
+        }
+    } else {
+        // ---- FP6: transpose so that lane L owns block L of the wave (chunk L/16, quad L%16)
+#pragma unroll
+        for (int u = 0; u < ROW_CHUNKS; u++) {
+            const int b = u * 16 + (lane >> 2);
+            *reinterpret_cast<uint4 *>(lds + b * 80 + (lane & 3) * 16) = make_uint4(d[u][0], d[u][1], d[u][2], d[u][3]);
+        }
+        wave_lds_sync();
+        uint32_t blk[16];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            uint4 t = *reinterpret_cast<const uint4 *>(lds + lane * 80 + j * 16);
+            blk[4 * j] = t.x; blk[4 * j + 1] = t.y; blk[4 * j + 2] = t.z; blk[4 * j + 3] = t.w;
+        }
+        uint32_t out[6];
+        const uint32_t s = quantize_block_bf16<FMT, RND>(blk, out);
+        wave_lds_sync();
+        // codes back through LDS: 64 blocks x 24 bytes = 1536 contiguous bytes, then the scale bytes
+        uint32_t *l32 = reinterpret_cast<uint32_t *>(lds);
+#pragma unroll
+        for (int i = 0; i < 6; i++) l32[lane * 6 + i] = out[i];
+        lds[1536 + lane] = (uint8_t)s;
+        wave_lds_sync();
+        const int64_t n_blk_valid = (n_elems - e0) / BLOCK;   // blocks of this wave inside the tensor (>= 1)
+        uint8_t *o = elems + blk0 * 24;
+        const uint4 a = *reinterpret_cast<const uint4 *>(lds + lane * 16);
+        const uint2 c = *reinterpret_cast<const uint2 *>(lds + 1024 + lane * 8);
+        if (n_blk_valid >= 64) {
+            st16(o + lane * 16, a);
+            *reinterpret_cast<uint2 *>(o + 1024 + lane * 8) = c;
+        } else {
+            const int64_t nbytes = n_blk_valid * 24;           // a multiple of 8
+            if (lane * 16 + 16 <= nbytes) st16(o + lane * 16, a);
+            else if (lane * 16 + 8 <= nbytes) *reinterpret_cast<uint2 *>(o + lane * 16) = make_uint2(a.x, a.y);
+            if (1024 + lane * 8 + 8 <= nbytes) *reinterpret_cast<uint2 *>(o + 1024 + lane * 8) = c;
+        }
+    }
+
+    // ---- scale bytes: 64 per wave, stored 16 at a time
+    wave_lds_sync();
+    {
+        const uint8_t *sl = SIX ? lds + 1536 : lds;
+        const int64_t n_blk_valid = (n_elems - e0) / BLOCK;
+        if (lane < 4) {
+            if ((lane + 1) * 16 <= n_blk_valid) {
+                st16(scales + blk0 + lane * 16, *reinterpret_cast<const uint4 *>(sl + lane * 16));
+            } else {
+                for (int i = lane * 16; i < n_blk_valid && i < lane * 16 + 16; i++) scales[blk0 + i] = sl[i];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Column cast
+// ---------------------------------------------------------------------------
+constexpr int COL_TILE_R = 128, COL_TILE_C = 64;
+
+// Work-groups are dealt round-robin to the 8 XCDs, each with its own L2.  Tile
+// t = xcd * per_xcd + i with the row-tile index fastest, so the work-groups of
+// one XCD walk down the rows of a column strip: what they write (128 bytes of
+// codes and 4 scale bytes per column each) is consecutive in memory and merges
+// into full lines in that XCD's L2.
+template <int FMT, int RND>
+__global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__restrict__ src, int64_t rows, int64_t cols,
+                                                            int64_t ld, uint8_t *__restrict__ elems,
+                                                            uint8_t *__restrict__ scales, int64_t row_tiles,
+                                                            int64_t n_tiles, int64_t per_xcd)
+{
+    constexpr int w = Fmt<FMT>::bits;
+    __shared__ __attribute__((aligned(16))) uint8_t tile[COL_TILE_R * COL_TILE_C * 2];   // 16 KB, 128-byte rows
+    const int t = threadIdx.x;
+    const int64_t tile_id = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int64_t)(blockIdx.x >> 3) >= per_xcd || tile_id >= n_tiles) return;   // uniform over the work-group
+    const int64_t c0 = (tile_id / row_tiles) * COL_TILE_C;
+    const int64_t r0 = (tile_id % row_tiles) * COL_TILE_R;
+
+    // ---- coalesced loads: 8 lanes per 128-byte row segment, 32 rows per pass
+    const int lr = t >> 3, lc = t & 7;
+    const bool full_cols = c0 + COL_TILE_C <= cols;
+#pragma unroll
+    for (int p = 0; p < 4; p++) {
+        const int r = p * 32 + lr;                       // row inside the tile; its 32-row block is p
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r0 + r < rows) {
+            const uint16_t *g = src + (r0 + r) * ld + c0 + lc * 8;
+            if (full_cols || c0 + lc * 8 + 8 <= cols) {
+                v = ld16(g);
+            } else {
+                uint16_t h[8];
+#pragma unroll
+                for (int i = 0; i < 8; i++) h[i] = (c0 + lc * 8 + i < cols) ? g[i] : (uint16_t)0;
+                v = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+            }
+        }
+        // rotate the row by 32 bytes per row block: column reads of the four blocks then hit different banks
+        *reinterpret_cast<uint4 *>(tile + r * 128 + ((lc * 16 + p * 32) & 127)) = v;
+    }
+    __syncthreads();
+
+    // ---- lane (column c, row block rb): 32 values down the column, packed in pairs
+    const int c = t >> 2, rb = t & 3;
+    const int64_t col = c0 + c;
+    const int64_t row_blk = r0 / BLOCK + rb;
+    const int64_t n_rb = rows / BLOCK;
+    if (col >= cols || row_blk >= n_rb) return;
+    const uint8_t *colp = tile + rb * 32 * 128 + ((c * 2 + rb * 32) & 127);
+    uint32_t d[16];
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        uint32_t lo = *reinterpret_cast<const uint16_t *>(colp + (2 * i) * 128);
+        uint32_t hi = *reinterpret_cast<const uint16_t *>(colp + (2 * i + 1) * 128);
+        d[i] = lo | (hi << 16);
+    }
+    uint32_t out[w];
+    const uint32_t s = quantize_block_bf16<FMT, RND>(d, out);
+    uint8_t *o = elems + (col * n_rb + row_blk) * (BLOCK * w / 8);
+    if constexpr (w == 8) {
+        st16(o, make_uint4(out[0], out[1], out[2], out[3]));
+        st16(o + 16, make_uint4(out[4], out[5], out[6], out[7]));
+    } else if constexpr (w == 6) {
+        *reinterpret_cast<uint2 *>(o) = make_uint2(out[0], out[1]);
+        *reinterpret_cast<uint2 *>(o + 8) = make_uint2(out[2], out[3]);
+        *reinterpret_cast<uint2 *>(o + 16) = make_uint2(out[4], out[5]);
+    } else {
+        st16(o, make_uint4(out[0], out[1], out[2], out[3]));
+    }
+    scales[col * n_rb + row_blk] = (uint8_t)s;
+}
+
+// ---------------------------------------------------------------------------
+// Launchers.  Return hipErrorNotSupported when the fast path does not apply.
+// ---------------------------------------------------------------------------
+template <int FMT, int RND>
+static hipError_t launch_fast_t(const void *src, int64_t rows, int64_t cols, int64_t ld, int axis, uint8_t *elems,
+                                uint8_t *scales, hipStream_t st)
+{
+    const uint16_t *s16 = static_cast<const uint16_t *>(src);
+    if (axis == 1) {
+        const int64_t n = rows * cols;
+        const int64_t waves = (n + ROW_WAVE_ELEMS - 1) / ROW_WAVE_ELEMS;
+        const int64_t nb = (waves + 3) / 4;
+        if (nb > 0x7FFFFFFF) return hipErrorNotSupported;
+        if (ld == cols)
+            hipLaunchKernelGGL((cast_row_bf16_kernel<FMT, RND, true>), dim3((unsigned)nb), dim3(256), 0, st, s16, cols, ld,
+                               elems, scales, n);
+        else
+            hipLaunchKernelGGL((cast_row_bf16_kernel<FMT, RND, false>), dim3((unsigned)nb), dim3(256), 0, st, s16, cols, ld,
+                               elems, scales, n);
+        return hipGetLastError();
+    }
+    const int64_t row_tiles = (rows + COL_TILE_R - 1) / COL_TILE_R;
+    const int64_t n_tiles = row_tiles * ((cols + COL_TILE_C - 1) / COL_TILE_C);
+    const int64_t per_xcd = (n_tiles + 7) / 8;
+    if (per_xcd * 8 > 0x7FFFFFFF) return hipErrorNotSupported;
+    hipLaunchKernelGGL((cast_col_bf16_kernel<FMT, RND>), dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, s16, rows, cols,
+                       ld, elems, scales, row_tiles, n_tiles, per_xcd);
+    return hipGetLastError();
+}
+
+template <int FMT>
+static hipError_t launch_fast_r(int rnd, const void *src, int64_t rows, int64_t cols, int64_t ld, int axis, uint8_t *elems,
+                                uint8_t *scales, hipStream_t st)
+{
+    return rnd == ROUND_RNE ? launch_fast_t<FMT, ROUND_RNE>(src, rows, cols, ld, axis, elems, scales, st)
+                            : launch_fast_t<FMT, ROUND_HALF_AWAY>(src, rows, cols, ld, axis, elems, scales, st);
+}
+
+hipError_t launch_cast_bf16_fast(const void *src, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,
+                                 uint8_t *elems, uint8_t *scales, hipStream_t st)
+{
+    switch (fmt) {
+        case FP8_E4M3: return launch_fast_r<FP8_E4M3>(rnd, src, rows, cols, ld, axis, elems, scales, st);
+        case FP8_E5M2: return launch_fast_r<FP8_E5M2>(rnd, src, rows, cols, ld, axis, elems, scales, st);
+        case FP6_E3M2: return launch_fast_r<FP6_E3M2>(rnd, src, rows, cols, ld, axis, elems, scales, st);
+        case FP6_E2M3: return launch_fast_r<FP6_E2M3>(rnd, src, rows, cols, ld, axis, elems, scales, st);
+        case FP4_E2M1: return launch_fast_r<FP4_E2M1>(rnd, src, rows, cols, ld, axis, elems, scales, st);
+        default:       return launch_fast_r<INT8>(rnd, src, rows, cols, ld, axis, elems, scales, st);
+    }
+}
+
+}  // namespace mx

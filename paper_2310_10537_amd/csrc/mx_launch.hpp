@@ -10,6 +10,10 @@ namespace mx {
 hipError_t launch_cast(const void *src, int src_dt, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,
                        uint8_t *elems, uint8_t *scales, hipStream_t st);
 
+// bf16 sources only; hipErrorNotSupported when the shape is outside what the fast kernels take
+hipError_t launch_cast_bf16_fast(const void *src, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,
+                                 uint8_t *elems, uint8_t *scales, hipStream_t st);
+
 hipError_t launch_dequant(const uint8_t *elems, const uint8_t *scales, int fmt, int64_t rows, int64_t cols, int axis,
                           void *dst, int dst_dt, int64_t ld, hipStream_t st);
 
