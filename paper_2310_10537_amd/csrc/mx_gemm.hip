@@ -242,6 +242,10 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
                        const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
                        const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st)
 {
+    if (!a_bf16) {
+        hipError_t e = launch_gemm_tiled(M, N, K, A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
+        if (e != hipErrorNotSupported) return e;
+    }
     GemmArgs g{M, N, K, A_elems, A_scales, reinterpret_cast<const uint16_t *>(a_bf16), lda, B_elems, B_scales, C, ldc, st};
     switch (fmtA) {
         case FP8_E4M3: return dispatch_b<FP8_E4M3>(g, fmtB, rnd, c_dt);

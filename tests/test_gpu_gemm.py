@@ -133,6 +133,27 @@ def test_shapes(mx, oracle, shape):
     check_gemm(to_host(C), C_ref, C_abs, str(shape), hw_term_for(oracle, ea, sa, 2, eb, sb, 4, K))
 
 
+@pytest.mark.parametrize("fa,fb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("shape,dt", [((512, 256, 384), torch.float32), ((256, 768, 128), torch.bfloat16)])
+def test_tiled_kernel_full_tiles(mx, oracle, fa, fb, shape, dt):
+    """Shapes made of whole 256 x 256 x 128 tiles take the LDS-tiled kernel; blocks
+    get very different scales so that a scale byte read for the wrong row, block
+    or K step shows up."""
+    M, N, K = shape
+    rng = np.random.default_rng(M + N + fa)
+    a = inputs.student_t_f32((M, K), seed=fa + 60) * np.exp2(rng.integers(-6, 6, (M, K // 32))).repeat(32, axis=1).astype(np.float32)
+    b = inputs.gaussian_f32((N, K), seed=fb + 70, std=0.02) * np.exp2(rng.integers(-6, 6, (N, K // 32))).repeat(32, axis=1).astype(np.float32)
+    ea, sa = oracle.quantize(a, 1, fa)
+    eb, sb = oracle.quantize(b, 1, fb)
+    C_ref, C_abs = oracle.gemm(ea, sa, fa, eb, sb, fb, K, want_abs=True)
+    C = mx.mx_gemm(to_dev(ea), to_dev(sa), fa, to_dev(eb), to_dev(sb), fb, K, dtype=dt)
+    got = to_host(C)
+    if dt == torch.bfloat16:
+        got = bf16_bits_to_f64(got)
+        C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5     # half a bf16 ulp of the result on top of the bound
+    check_gemm(got, C_ref, C_abs, str(shape), hw_term_for(oracle, ea, sa, fa, eb, sb, fb, K))
+
+
 def test_exact_integer_products(mx, oracle):
     """Integer-valued FP4 operands at X = 1: every partial sum is an integer below
     2^24, so Float32 accumulation is exact and the result must equal the
