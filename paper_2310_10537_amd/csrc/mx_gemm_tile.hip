@@ -74,22 +74,33 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
 #pragma unroll
             for (int t = 0; t < 16; t++) acc[x][y][t] = 0.f;
 
-    uint4 stg[8];
-    uint32_t scA[4], scB[4], scAn[4], scBn[4];
+    // Software pipeline, prefetch distance two: while stage t is multiplied out of LDS, stage t+1
+    // (fetched during the previous iteration) moves from registers to the other LDS buffer and
+    // stage t+2 is requested from global memory, so a load has a whole iteration to arrive.
+    uint4 rA[8], rB[8];
+    uint32_t scA[4], scB[4], scA1[4], scB1[4];
 
-    // ---- prologue: stage 0
+    // ---- prologue: stage 0 to LDS, stage 1 to registers
 #pragma unroll
-    for (int j = 0; j < 8; j++) stg[j] = ld16(gA + j * g_step);
-#pragma unroll
-    for (int j = 0; j < 8; j++) *reinterpret_cast<uint4 *>(lds + st_l + j * 4096) = stg[j];
-#pragma unroll
-    for (int j = 0; j < 8; j++) stg[j] = ld16(gB + j * g_step);
-#pragma unroll
-    for (int j = 0; j < 8; j++) *reinterpret_cast<uint4 *>(lds + TILE_BYTES + st_l + j * 4096) = stg[j];
+    for (int j = 0; j < 8; j++) { rA[j] = ld16(gA + j * g_step); rB[j] = ld16(gB + j * g_step); }
 #pragma unroll
     for (int x = 0; x < 4; x++) {
         scA[x] = *reinterpret_cast<const uint32_t *>(sA + x * s_step);
         scB[x] = *reinterpret_cast<const uint32_t *>(sB + x * s_step);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        *reinterpret_cast<uint4 *>(lds + st_l + j * 4096) = rA[j];
+        *reinterpret_cast<uint4 *>(lds + TILE_BYTES + st_l + j * 4096) = rB[j];
+    }
+    if (T > 1) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) { rA[j] = ld16(gA + TK + j * g_step); rB[j] = ld16(gB + TK + j * g_step); }
+#pragma unroll
+        for (int x = 0; x < 4; x++) {
+            scA1[x] = *reinterpret_cast<const uint32_t *>(sA + x * s_step + 4);
+            scB1[x] = *reinterpret_cast<const uint32_t *>(sB + x * s_step + 4);
+        }
     }
     __syncthreads();
 
@@ -97,28 +108,34 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
         const int cur = t & 1;
         const uint8_t *bufA = lds + cur * 2 * TILE_BYTES;
         const uint8_t *bufB = bufA + TILE_BYTES;
-        uint8_t *nxt = lds + (cur ^ 1) * 2 * TILE_BYTES;
-        const bool more = t + 1 < T;
-        const int64_t kofs = (int64_t)(t + 1) * TK;
+        uint8_t *nxt = lds + (cur ^ 1) * 2 * TILE_BYTES + st_l;
         uint32_t sa[4], sb[4];
 #pragma unroll
         for (int x = 0; x < 4; x++) { sa[x] = g ? scA[x] >> 8 : scA[x]; sb[x] = g ? scB[x] >> 8 : scB[x]; }
 
+        if (t + 1 < T) {
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                *reinterpret_cast<uint4 *>(nxt + j * 4096) = rA[j];
+                *reinterpret_cast<uint4 *>(nxt + TILE_BYTES + j * 4096) = rB[j];
+            }
+#pragma unroll
+            for (int x = 0; x < 4; x++) { scA[x] = scA1[x]; scB[x] = scB1[x]; }
+        }
+        if (t + 2 < T) {
+            const int64_t kofs = (int64_t)(t + 2) * TK;
+#pragma unroll
+            for (int j = 0; j < 8; j++) { rA[j] = ld16(gA + kofs + j * g_step); rB[j] = ld16(gB + kofs + j * g_step); }
+#pragma unroll
+            for (int x = 0; x < 4; x++) {
+                scA1[x] = *reinterpret_cast<const uint32_t *>(sA + x * s_step + (t + 2) * 4);
+                scB1[x] = *reinterpret_cast<const uint32_t *>(sB + x * s_step + (t + 2) * 4);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
 #pragma unroll
         for (int sub = 0; sub < 2; sub++) {
-            // the next stage's A tile travels during sub-step 0, its B tile during sub-step 1
-            if (more) {
-                const uint8_t *gp = (sub == 0 ? gA : gB) + kofs;
-#pragma unroll
-                for (int j = 0; j < 8; j++) stg[j] = ld16(gp + j * g_step);
-                if (sub == 0) {
-#pragma unroll
-                    for (int x = 0; x < 4; x++) {
-                        scAn[x] = *reinterpret_cast<const uint32_t *>(sA + x * s_step + (t + 1) * 4);
-                        scBn[x] = *reinterpret_cast<const uint32_t *>(sB + x * s_step + (t + 1) * 4);
-                    }
-                }
-            }
             v8i_t a[4];
 #pragma unroll
             for (int x = 0; x < 4; x++) {
@@ -139,15 +156,6 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
                         acc[x][y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[x], b, acc[x][y], HA, HB, 2, (int)sa[x], 2, (int)sb[y]);
                 }
             }
-            if (more) {
-                uint8_t *np = nxt + (sub == 0 ? 0 : TILE_BYTES) + st_l;
-#pragma unroll
-                for (int j = 0; j < 8; j++) *reinterpret_cast<uint4 *>(np + j * 4096) = stg[j];
-            }
-        }
-        if (more) {
-#pragma unroll
-            for (int x = 0; x < 4; x++) { scA[x] = scAn[x]; scB[x] = scBn[x]; }
         }
         __syncthreads();
     }
