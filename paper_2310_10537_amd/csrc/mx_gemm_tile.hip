@@ -74,13 +74,36 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
 #pragma unroll
             for (int t = 0; t < 16; t++) acc[x][y][t] = 0.f;
 
-    // Software pipeline, prefetch distance two: while stage t is multiplied out of LDS, stage t+1
-    // (fetched during the previous iteration) moves from registers to the other LDS buffer and
-    // stage t+2 is requested from global memory, so a load has a whole iteration to arrive.
+    // Software pipeline (one work-group barrier per K step).
+    //   global -> registers -> LDS runs two stages ahead of the multiply: during step t the
+    //   registers holding stage t+1 are written to the other LDS buffer and immediately reloaded
+    //   with stage t+2, so a global load has a whole step to arrive;
+    //   LDS -> operand registers runs a few matrix instructions ahead, in program order
+    //   interleaved with them (the compiler is fenced group by group), so that the LDS pipe and
+    //   the matrix pipe work at the same time instead of taking turns.
+    // Step t, buffer cur = t & 1 holds stage t:
+    //   X  : 16 MFMA of sub-step 0 | read a1[0..3], b1[0..1] (sub-step 1) and b0[1..3] just in time
+    //   Y1 :  8 MFMA of sub-step 1 | write stage t+1 to the other buffer, reload registers with
+    //                                stage t+2, read b1[2..3]
+    //   barrier: every read of stage t has been issued before it, every write of stage t+1 too
+    //   Y2 :  8 MFMA of sub-step 1 | read a0[0..3], b0[0] of stage t+1
+    // Stages beyond the last are clamped to the last one: the extra loads are harmless and the
+    // loop body needs no branches.
     uint4 rA[8], rB[8];
     uint32_t scA[4], scB[4], scA1[4], scB1[4];
+    v8i_t a0[4], a1[4], b0[2], b1[4];
 
-    // ---- prologue: stage 0 to LDS, stage 1 to registers
+    auto rd = [&](const uint8_t *buf, int ofs0, int sub, int x) -> v8i_t {
+        const uint4 lo = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 6)) + x * 4096);
+        const uint4 hi = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 6) ^ 32) + x * 4096);
+        return v8i_t{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+    };
+#define MX_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define MX_MFMA4(AF, BF, Y, OPS)                                                                                      \
+    _Pragma("unroll") for (int x = 0; x < 4; x++)                                                                     \
+        acc[x][Y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(AF[x], BF, acc[x][Y], HA, HB, OPS, (int)sa[x], OPS, (int)sb[Y])
+
+    // ---- prologue: stage 0 to LDS, stage 1 to registers, first fragments
 #pragma unroll
     for (int j = 0; j < 8; j++) { rA[j] = ld16(gA + j * g_step); rB[j] = ld16(gB + j * g_step); }
 #pragma unroll
@@ -93,72 +116,87 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
         *reinterpret_cast<uint4 *>(lds + st_l + j * 4096) = rA[j];
         *reinterpret_cast<uint4 *>(lds + TILE_BYTES + st_l + j * 4096) = rB[j];
     }
-    if (T > 1) {
+    {
+        const int64_t k1 = (T > 1 ? 1 : 0) * (int64_t)TK;
+        const int s1 = (T > 1 ? 1 : 0) * 4;
 #pragma unroll
-        for (int j = 0; j < 8; j++) { rA[j] = ld16(gA + TK + j * g_step); rB[j] = ld16(gB + TK + j * g_step); }
+        for (int j = 0; j < 8; j++) { rA[j] = ld16(gA + k1 + j * g_step); rB[j] = ld16(gB + k1 + j * g_step); }
 #pragma unroll
         for (int x = 0; x < 4; x++) {
-            scA1[x] = *reinterpret_cast<const uint32_t *>(sA + x * s_step + 4);
-            scB1[x] = *reinterpret_cast<const uint32_t *>(sB + x * s_step + 4);
+            scA1[x] = *reinterpret_cast<const uint32_t *>(sA + x * s_step + s1);
+            scB1[x] = *reinterpret_cast<const uint32_t *>(sB + x * s_step + s1);
         }
     }
     __syncthreads();
+#pragma unroll
+    for (int x = 0; x < 4; x++) a0[x] = rd(lds, ra0, 0, x);
+    b0[0] = rd(lds + TILE_BYTES, rb0, 0, 0);
 
     for (int t = 0; t < T; t++) {
         const int cur = t & 1;
         const uint8_t *bufA = lds + cur * 2 * TILE_BYTES;
         const uint8_t *bufB = bufA + TILE_BYTES;
-        uint8_t *nxt = lds + (cur ^ 1) * 2 * TILE_BYTES + st_l;
+        uint8_t *nxt = lds + (cur ^ 1) * 2 * TILE_BYTES;
+        const int t2 = t + 2 < T ? t + 2 : T - 1;
+        const int64_t kofs = (int64_t)t2 * TK;
         uint32_t sa[4], sb[4];
 #pragma unroll
         for (int x = 0; x < 4; x++) { sa[x] = g ? scA[x] >> 8 : scA[x]; sb[x] = g ? scB[x] >> 8 : scB[x]; }
+        MX_FENCE();
 
-        if (t + 1 < T) {
+        // ---- X: sub-step 0 (the scale dwords of stage t+2 are requested first: they are the
+        // oldest loads in flight when they are rotated in at the end of the step)
+        uint32_t scA2[4], scB2[4];
 #pragma unroll
-            for (int j = 0; j < 8; j++) {
-                *reinterpret_cast<uint4 *>(nxt + j * 4096) = rA[j];
-                *reinterpret_cast<uint4 *>(nxt + TILE_BYTES + j * 4096) = rB[j];
-            }
-#pragma unroll
-            for (int x = 0; x < 4; x++) { scA[x] = scA1[x]; scB[x] = scB1[x]; }
+        for (int x = 0; x < 4; x++) {
+            scA2[x] = *reinterpret_cast<const uint32_t *>(sA + x * s_step + t2 * 4);
+            scB2[x] = *reinterpret_cast<const uint32_t *>(sB + x * s_step + t2 * 4);
         }
-        if (t + 2 < T) {
-            const int64_t kofs = (int64_t)(t + 2) * TK;
-#pragma unroll
-            for (int j = 0; j < 8; j++) { rA[j] = ld16(gA + kofs + j * g_step); rB[j] = ld16(gB + kofs + j * g_step); }
-#pragma unroll
-            for (int x = 0; x < 4; x++) {
-                scA1[x] = *reinterpret_cast<const uint32_t *>(sA + x * s_step + (t + 2) * 4);
-                scB1[x] = *reinterpret_cast<const uint32_t *>(sB + x * s_step + (t + 2) * 4);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
+        b0[1] = rd(bufB, rb0, 0, 1); a1[0] = rd(bufA, ra0, 1, 0); b1[0] = rd(bufB, rb0, 1, 0);
+        MX_MFMA4(a0, b0[0], 0, 0);
+        MX_FENCE();
+        b0[0] = rd(bufB, rb0, 0, 2); a1[1] = rd(bufA, ra0, 1, 1); b1[1] = rd(bufB, rb0, 1, 1);
+        MX_MFMA4(a0, b0[1], 1, 0);
+        MX_FENCE();
+        b0[1] = rd(bufB, rb0, 0, 3); a1[2] = rd(bufA, ra0, 1, 2);
+        MX_MFMA4(a0, b0[0], 2, 0);
+        MX_FENCE();
+        a1[3] = rd(bufA, ra0, 1, 3);
+        MX_MFMA4(a0, b0[1], 3, 0);
+        MX_FENCE();
 
+        // ---- Y1: sub-step 1, first half; stage t+1 registers -> LDS, reload with stage t+2
+        b1[2] = rd(bufB, rb0, 1, 2);
 #pragma unroll
-        for (int sub = 0; sub < 2; sub++) {
-            v8i_t a[4];
-#pragma unroll
-            for (int x = 0; x < 4; x++) {
-                const uint4 a0 = *reinterpret_cast<const uint4 *>(bufA + (ra0 ^ (sub << 6)) + x * 4096);
-                const uint4 a1 = *reinterpret_cast<const uint4 *>(bufA + (ra0 ^ (sub << 6) ^ 32) + x * 4096);
-                a[x] = v8i_t{(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
-            }
-#pragma unroll
-            for (int y = 0; y < 4; y++) {
-                const uint4 b0 = *reinterpret_cast<const uint4 *>(bufB + (rb0 ^ (sub << 6)) + y * 4096);
-                const uint4 b1 = *reinterpret_cast<const uint4 *>(bufB + (rb0 ^ (sub << 6) ^ 32) + y * 4096);
-                const v8i_t b = v8i_t{(int)b0.x, (int)b0.y, (int)b0.z, (int)b0.w, (int)b1.x, (int)b1.y, (int)b1.z, (int)b1.w};
-#pragma unroll
-                for (int x = 0; x < 4; x++) {
-                    if (sub == 0)
-                        acc[x][y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[x], b, acc[x][y], HA, HB, 0, (int)sa[x], 0, (int)sb[y]);
-                    else
-                        acc[x][y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[x], b, acc[x][y], HA, HB, 2, (int)sa[x], 2, (int)sb[y]);
-                }
-            }
+        for (int j = 0; j < 8; j++) {
+            *reinterpret_cast<uint4 *>(nxt + st_l + j * 4096) = rA[j];
+            rA[j] = ld16(gA + kofs + j * g_step);
         }
+        MX_MFMA4(a1, b1[0], 0, 2);
+        MX_FENCE();
+        b1[3] = rd(bufB, rb0, 1, 3);
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            *reinterpret_cast<uint4 *>(nxt + TILE_BYTES + st_l + j * 4096) = rB[j];
+            rB[j] = ld16(gB + kofs + j * g_step);
+        }
+        MX_MFMA4(a1, b1[1], 1, 2);
+        MX_FENCE();
         __syncthreads();
+        MX_FENCE();
+
+        // ---- Y2: sub-step 1, second half; first fragments of stage t+1
+        a0[0] = rd(nxt, ra0, 0, 0); a0[1] = rd(nxt, ra0, 0, 1);
+        MX_MFMA4(a1, b1[2], 2, 2);
+        MX_FENCE();
+        a0[2] = rd(nxt, ra0, 0, 2); a0[3] = rd(nxt, ra0, 0, 3); b0[0] = rd(nxt + TILE_BYTES, rb0, 0, 0);
+        MX_MFMA4(a1, b1[3], 3, 2);
+#pragma unroll
+        for (int x = 0; x < 4; x++) { scA[x] = scA1[x]; scB[x] = scB1[x]; scA1[x] = scA2[x]; scB1[x] = scB2[x]; }
+        MX_FENCE();
     }
+#undef MX_MFMA4
+#undef MX_FENCE
 
     // ---- epilogue: lane (li, g), register t of tile (x, y) -> C[8*(t/4) + 4g + t%4][li]
 #pragma unroll
