@@ -5,12 +5,18 @@
 // 256 x 256, K step 128 (four MX blocks).  Each wave owns a 128 x 128 sub-tile:
 // 4 x 4 matrix-instruction tiles of 32 x 32, i.e. 256 accumulator registers.
 // Per K step the work-group stages 256 x 128 bytes of A and of B in LDS (double
-// buffered, 128 KB in all); every 16-byte chunk c of row r sits at chunk
-// position c ^ (r & 7) of the row, so both the 16-byte stores of the staging
-// pass and the operand reads (32 rows, same chunk) are free of bank conflicts.
-// Scale bytes go from global memory straight to registers: one dword holds the
-// four scale bytes of a row for the K step; lanes 32..63 shift it by one byte so
-// that a single op_sel value addresses block 2*sub + g for every lane.
+// buffered, 128 KB in all) with direct global-to-LDS loads (no register staging,
+// no LDS store instructions: measured, the LDS pipe cannot carry the operand
+// reads of this tile shape and store instructions as well).  Every 16-byte
+// chunk c of row r sits at chunk position c ^ (r & 7) of the row, so the operand
+// reads (32 rows, same chunk) are free of bank conflicts; since a direct load
+// writes its 64 lanes to consecutive LDS addresses, the swizzle is applied on
+// the global side: the lane that fills position p of a row fetches chunk
+// p ^ (r & 7) of that row.
+// Scale bytes travel the same way: one dword holds the four scale bytes of a row
+// for the K step, 256 + 256 of them per stage sit in LDS behind the element
+// tiles; lanes 32..63 shift their dword by one byte so that a single op_sel
+// value addresses block 2*sub + g for every lane.
 #include "mx_device.hpp"
 #include "mx_launch.hpp"
 
@@ -21,7 +27,7 @@ typedef float v16f_t __attribute__((ext_vector_type(16)));
 
 constexpr int TM = 256, TN = 256, TK = 128;      // work-group tile (TK in elements = bytes for 8-bit formats)
 constexpr int TILE_BYTES = TM * TK;              // 32 KB per operand per stage
-constexpr int GEMM_LDS_BYTES = 4 * TILE_BYTES;   // A,B x 2 stages
+constexpr int SCL_BYTES = (TM + TN) * 4;         // scale dwords of one stage
 
 __host__ __device__ constexpr int hw_fmt8(int fmt) { return fmt == FP8_E4M3 ? 0 : 1; }
 
@@ -34,7 +40,8 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
                                                             const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
                                                             void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n)
 {
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    // {A tile, B tile} x two stages, then {A scale dwords, B scale dwords} x two stages
+    __shared__ __attribute__((aligned(16))) uint8_t lds[4 * TILE_BYTES + 2 * SCL_BYTES];
     constexpr int HA = hw_fmt8(FA), HB = hw_fmt8(FB);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -51,17 +58,19 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
     const int64_t nkb = K / BLOCK;
     const int T = (int)(K / TK);
 
-    // ---- staging map: thread handles chunks q = tid + 256*j, j < 8: row q/8 = tid/8 + 32*j, chunk tid%8.
-    // Rows 32 apart share (row & 7), so the LDS offset of chunk j is that of chunk 0 plus j * 4096.
-    const int st_r = tid >> 3, st_c = tid & 7;
+    // ---- staging map: one direct load of a wave fills 1 KB of LDS = 8 tile rows; wave w, load j
+    // covers rows (4j + w) * 8 .. + 7.  Lane l writes position l % 8 of row l / 8 of that group and
+    // therefore fetches chunk (l % 8) ^ (l / 8) of it.
+    const int st_r = wave * 8 + (lane >> 3), st_c = (lane & 7) ^ (lane >> 3);
     const uint8_t *gA = Ae + (m0 + st_r) * K + st_c * 16;
     const uint8_t *gB = Be + (n0 + st_r) * K + st_c * 16;
     const int64_t g_step = 32 * K;                 // 32 rows further down
-    const int st_l = swz(st_r, st_c);
-    // ---- scale pointers: one dword per row per K step; row tiles are 32 rows apart
-    const uint8_t *sA = As + (m0 + wm * 128 + li) * nkb;
-    const uint8_t *sB = Bs + (n0 + wn * 128 + li) * nkb;
-    const int64_t s_step = 32 * nkb;
+    const int st_l = wave * 1024;                  // LDS offset of this wave's 1 KB slot within a 4 KB group
+    // ---- scale staging: wave w fetches the dwords of rows 64w .. 64w+63 of A and of B
+    const uint8_t *sA = As + (m0 + wave * 64 + lane) * nkb;
+    const uint8_t *sB = Bs + (n0 + wave * 64 + lane) * nkb;
+    // ---- scale reads: dword of tile row wm*128 + 32x + li (A) / wn*128 + 32y + li (B)
+    const int rsa = (wm * 128 + li) * 4, rsb = TM * 4 + (wn * 128 + li) * 4;
     // ---- operand read offsets inside a stage's tile: row tile x adds x * 4096, the second 16-byte
     // chunk of a sub-step (chunk + 2) flips bit 5, sub-step 1 (chunk + 4) flips bit 6
     const int ra0 = swz(wm * 128 + li, g), rb0 = swz(wn * 128 + li, g);
@@ -74,23 +83,18 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
 #pragma unroll
             for (int t = 0; t < 16; t++) acc[x][y][t] = 0.f;
 
-    // Software pipeline (one work-group barrier per K step).
-    //   global -> registers -> LDS runs two stages ahead of the multiply: during step t the
-    //   registers holding stage t+1 are written to the other LDS buffer and immediately reloaded
-    //   with stage t+2, so a global load has a whole step to arrive;
-    //   LDS -> operand registers runs a few matrix instructions ahead, in program order
-    //   interleaved with them (the compiler is fenced group by group), so that the LDS pipe and
-    //   the matrix pipe work at the same time instead of taking turns.
-    // Step t, buffer cur = t & 1 holds stage t:
+    // Software pipeline (one work-group barrier per K step), buffer cur = t & 1 holds stage t:
     //   X  : 16 MFMA of sub-step 0 | read a1[0..3], b1[0..1] (sub-step 1) and b0[1..3] just in time
-    //   Y1 :  8 MFMA of sub-step 1 | write stage t+1 to the other buffer, reload registers with
-    //                                stage t+2, read b1[2..3]
-    //   barrier: every read of stage t has been issued before it, every write of stage t+1 too
-    //   Y2 :  8 MFMA of sub-step 1 | read a0[0..3], b0[0] of stage t+1
-    // Stages beyond the last are clamped to the last one: the extra loads are harmless and the
-    // loop body needs no branches.
-    uint4 rA[8], rB[8];
-    uint32_t scA[4], scB[4], scA1[4], scB1[4];
+    //   Y1 :  8 MFMA of sub-step 1 | read b1[2..3]
+    //   wait for the direct loads of stage t+1, barrier: every read of stage t was issued before it
+    //   Y2 :  8 MFMA of sub-step 1 | request stage t+2 into the buffer stage t just vacated,
+    //                                read a0[0..3], b0[0] of stage t+1
+    // LDS reads are written in program order between the matrix instructions and the compiler is
+    // fenced group by group, so the LDS pipe and the matrix pipe work at the same time.
+    // Stages beyond the last are clamped to the last one (harmless extra loads, no branches).
+    typedef __attribute__((address_space(3))) void lds_ptr_t;
+    typedef __attribute__((address_space(1))) const void glb_ptr_t;
+    uint32_t sa[4], sb[4];   // scale dwords of the current stage, already shifted for this lane
     v8i_t a0[4], a1[4], b0[2], b1[4];
 
     auto rd = [&](const uint8_t *buf, int ofs0, int sub, int x) -> v8i_t {
@@ -98,60 +102,69 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
         const uint4 hi = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 6) ^ 32) + x * 4096);
         return v8i_t{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
     };
+    // Direct loads of one operand tile for K offset kofs into LDS tile dst.  Written as inline
+    // assembly on purpose: the compiler makes every later LDS read wait for a direct load it knows
+    // about (it cannot tell that the two stage buffers never overlap), which serialises the whole
+    // pipeline.  Here the only consumer-side wait is the explicit vmcnt(0) before the barrier.
+    // M0 carries the wave-uniform LDS destination; lane l lands at destination + 16 * l.
+    auto stage = [&](const uint8_t *gsrc, int64_t kofs, uint8_t *dst) {
+        const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const uint8_t *gp = gsrc + kofs + j * g_step;
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
+        }
+    };
+    // scale dwords of K step ts into scale buffer dst (A rows then B rows)
+    auto stage_scales = [&](int ts, uint8_t *dst) {
+        const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + wave * 256));
+        const uint8_t *pa = sA + ts * 4, *pb = sB + ts * 4;
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" : : "v"(pa), "s"(l0) : "m0");
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" : : "v"(pb), "s"(l0 + TM * 4) : "m0");
+    };
+    auto read_scales = [&](const uint8_t *src) {
+#pragma unroll
+        for (int x = 0; x < 4; x++) {
+            const uint32_t da = *reinterpret_cast<const uint32_t *>(src + rsa + x * 128);
+            const uint32_t db = *reinterpret_cast<const uint32_t *>(src + rsb + x * 128);
+            sa[x] = g ? da >> 8 : da;
+            sb[x] = g ? db >> 8 : db;
+        }
+    };
+    uint8_t *const scl = lds + 4 * TILE_BYTES;
 #define MX_FENCE() __builtin_amdgcn_sched_barrier(0)
 #define MX_MFMA4(AF, BF, Y, OPS)                                                                                      \
     _Pragma("unroll") for (int x = 0; x < 4; x++)                                                                     \
         acc[x][Y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(AF[x], BF, acc[x][Y], HA, HB, OPS, (int)sa[x], OPS, (int)sb[Y])
 
-    // ---- prologue: stage 0 to LDS, stage 1 to registers, first fragments
-#pragma unroll
-    for (int j = 0; j < 8; j++) { rA[j] = ld16(gA + j * g_step); rB[j] = ld16(gB + j * g_step); }
-#pragma unroll
-    for (int x = 0; x < 4; x++) {
-        scA[x] = *reinterpret_cast<const uint32_t *>(sA + x * s_step);
-        scB[x] = *reinterpret_cast<const uint32_t *>(sB + x * s_step);
-    }
-#pragma unroll
-    for (int j = 0; j < 8; j++) {
-        *reinterpret_cast<uint4 *>(lds + st_l + j * 4096) = rA[j];
-        *reinterpret_cast<uint4 *>(lds + TILE_BYTES + st_l + j * 4096) = rB[j];
-    }
+    // ---- prologue: stage 0 and stage 1 on their way to LDS
+    stage(gA, 0, lds);
+    stage(gB, 0, lds + TILE_BYTES);
+    stage_scales(0, scl);
     {
-        const int64_t k1 = (T > 1 ? 1 : 0) * (int64_t)TK;
-        const int s1 = (T > 1 ? 1 : 0) * 4;
-#pragma unroll
-        for (int j = 0; j < 8; j++) { rA[j] = ld16(gA + k1 + j * g_step); rB[j] = ld16(gB + k1 + j * g_step); }
-#pragma unroll
-        for (int x = 0; x < 4; x++) {
-            scA1[x] = *reinterpret_cast<const uint32_t *>(sA + x * s_step + s1);
-            scB1[x] = *reinterpret_cast<const uint32_t *>(sB + x * s_step + s1);
-        }
+        const int t1 = T > 1 ? 1 : 0;
+        stage(gA, (int64_t)t1 * TK, lds + 2 * TILE_BYTES);
+        stage(gB, (int64_t)t1 * TK, lds + 3 * TILE_BYTES);
+        stage_scales(t1, scl + SCL_BYTES);
     }
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): both stages have landed in LDS
     __syncthreads();
 #pragma unroll
     for (int x = 0; x < 4; x++) a0[x] = rd(lds, ra0, 0, x);
     b0[0] = rd(lds + TILE_BYTES, rb0, 0, 0);
+    read_scales(scl);
 
     for (int t = 0; t < T; t++) {
-        const int cur = t & 1;
-        const uint8_t *bufA = lds + cur * 2 * TILE_BYTES;
-        const uint8_t *bufB = bufA + TILE_BYTES;
-        uint8_t *nxt = lds + (cur ^ 1) * 2 * TILE_BYTES;
+        uint8_t *bufA = lds + (t & 1) * 2 * TILE_BYTES;
+        uint8_t *nxt = lds + ((t & 1) ^ 1) * 2 * TILE_BYTES;
+        uint8_t *bufB = bufA + TILE_BYTES;
+        uint8_t *sclc = scl + (t & 1) * SCL_BYTES;
+        const uint8_t *scln = scl + ((t & 1) ^ 1) * SCL_BYTES;
         const int t2 = t + 2 < T ? t + 2 : T - 1;
         const int64_t kofs = (int64_t)t2 * TK;
-        uint32_t sa[4], sb[4];
-#pragma unroll
-        for (int x = 0; x < 4; x++) { sa[x] = g ? scA[x] >> 8 : scA[x]; sb[x] = g ? scB[x] >> 8 : scB[x]; }
         MX_FENCE();
 
-        // ---- X: sub-step 0 (the scale dwords of stage t+2 are requested first: they are the
-        // oldest loads in flight when they are rotated in at the end of the step)
-        uint32_t scA2[4], scB2[4];
-#pragma unroll
-        for (int x = 0; x < 4; x++) {
-            scA2[x] = *reinterpret_cast<const uint32_t *>(sA + x * s_step + t2 * 4);
-            scB2[x] = *reinterpret_cast<const uint32_t *>(sB + x * s_step + t2 * 4);
-        }
+        // ---- X: sub-step 0
         b0[1] = rd(bufB, rb0, 0, 1); a1[0] = rd(bufA, ra0, 1, 0); b1[0] = rd(bufB, rb0, 1, 0);
         MX_MFMA4(a0, b0[0], 0, 0);
         MX_FENCE();
@@ -165,34 +178,30 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
         MX_MFMA4(a0, b0[1], 3, 0);
         MX_FENCE();
 
-        // ---- Y1: sub-step 1, first half; stage t+1 registers -> LDS, reload with stage t+2
+        // ---- Y1: sub-step 1, first half
         b1[2] = rd(bufB, rb0, 1, 2);
-#pragma unroll
-        for (int j = 0; j < 8; j++) {
-            *reinterpret_cast<uint4 *>(nxt + st_l + j * 4096) = rA[j];
-            rA[j] = ld16(gA + kofs + j * g_step);
-        }
         MX_MFMA4(a1, b1[0], 0, 2);
         MX_FENCE();
         b1[3] = rd(bufB, rb0, 1, 3);
-#pragma unroll
-        for (int j = 0; j < 8; j++) {
-            *reinterpret_cast<uint4 *>(nxt + TILE_BYTES + st_l + j * 4096) = rB[j];
-            rB[j] = ld16(gB + kofs + j * g_step);
-        }
         MX_MFMA4(a1, b1[1], 1, 2);
         MX_FENCE();
+        // stage t+1 (requested during the previous step) must be in LDS, and every wave must be
+        // done reading stage t, before the buffers change roles
+        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
         __syncthreads();
         MX_FENCE();
 
-        // ---- Y2: sub-step 1, second half; first fragments of stage t+1
+        // ---- Y2: sub-step 1, second half; request stage t+2, first fragments of stage t+1
+        stage(gA, kofs, bufA);
         a0[0] = rd(nxt, ra0, 0, 0); a0[1] = rd(nxt, ra0, 0, 1);
         MX_MFMA4(a1, b1[2], 2, 2);
         MX_FENCE();
+        stage(gB, kofs, bufB);
+        stage_scales(t2, sclc);
         a0[2] = rd(nxt, ra0, 0, 2); a0[3] = rd(nxt, ra0, 0, 3); b0[0] = rd(nxt + TILE_BYTES, rb0, 0, 0);
         MX_MFMA4(a1, b1[3], 3, 2);
-#pragma unroll
-        for (int x = 0; x < 4; x++) { scA[x] = scA1[x]; scB[x] = scB1[x]; scA1[x] = scA2[x]; scB1[x] = scB2[x]; }
+        MX_FENCE();
+        read_scales(scln);   // for the next step; the matrix instructions above already hold theirs
         MX_FENCE();
     }
 #undef MX_MFMA4
@@ -216,17 +225,10 @@ template <int FA, int FB, int CDT>
 static hipError_t launch_t(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint8_t *Be,
                            const uint8_t *Bs, void *C, int64_t ldc, hipStream_t st)
 {
-    static bool attr_set = false;   // raising the dynamic LDS limit is a per-function, per-process setting
     auto kern = gemm8_tile_kernel<FA, FB, CDT>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           GEMM_LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
     const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), GEMM_LDS_BYTES, st, M, N, K, Ae, As, Be, Bs, C, ldc,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc,
                        tiles_m, tiles_n);
     return hipGetLastError();
 }
