@@ -13,10 +13,14 @@
 // writes its 64 lanes to consecutive LDS addresses, the swizzle is applied on
 // the global side: the lane that fills position p of a row fetches chunk
 // p ^ (r & 7) of that row.
-// Scale bytes travel the same way: one dword holds the four scale bytes of a row
-// for the K step, 256 + 256 of them per stage sit in LDS behind the element
-// tiles; lanes 32..63 shift their dword by one byte so that a single op_sel
-// value addresses block 2*sub + g for every lane.
+// Scale bytes travel the same way, four K steps at a time: a row's scale bytes
+// for 512 elements are 16 consecutive bytes, so one 16-byte direct load per row
+// brings four steps' worth and touches its cache line once instead of four
+// times (a row's scales and its neighbours' are 128 bytes apart -- per-step
+// dword loads doubled the number of L2 requests of the whole kernel).  Two such
+// groups (256 + 256 rows x 16 bytes each) sit in LDS behind the element tiles.
+// Lanes 32..63 shift their dword by one byte so that a single op_sel value
+// addresses block 2*sub + g for every lane.
 #include "mx_device.hpp"
 #include "mx_launch.hpp"
 
@@ -27,7 +31,8 @@ typedef float v16f_t __attribute__((ext_vector_type(16)));
 
 constexpr int TM = 256, TN = 256, TK = 128;      // work-group tile (TK in elements = bytes for 8-bit formats)
 constexpr int TILE_BYTES = TM * TK;              // 32 KB per operand per stage
-constexpr int SCL_BYTES = (TM + TN) * 4;         // scale dwords of one stage
+constexpr int SCL_GROUP = 4;                     // K steps per scale group
+constexpr int SCL_BYTES = (TM + TN) * 4 * SCL_GROUP;   // one group: 16 scale bytes per row
 
 __host__ __device__ constexpr int hw_fmt8(int fmt) { return fmt == FP8_E4M3 ? 0 : 1; }
 
@@ -70,7 +75,7 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
     const uint8_t *sA = As + (m0 + wave * 64 + lane) * nkb;
     const uint8_t *sB = Bs + (n0 + wave * 64 + lane) * nkb;
     // ---- scale reads: dword of tile row wm*128 + 32x + li (A) / wn*128 + 32y + li (B)
-    const int rsa = (wm * 128 + li) * 4, rsb = TM * 4 + (wn * 128 + li) * 4;
+    const int rsa = (wm * 128 + li) * 16, rsb = TM * 16 + (wn * 128 + li) * 16;
     // ---- operand read offsets inside a stage's tile: row tile x adds x * 4096, the second 16-byte
     // chunk of a sub-step (chunk + 2) flips bit 5, sub-step 1 (chunk + 4) flips bit 6
     const int ra0 = swz(wm * 128 + li, g), rb0 = swz(wn * 128 + li, g);
@@ -115,23 +120,28 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
             asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
         }
     };
-    // scale dwords of K step ts into scale buffer dst (A rows then B rows)
-    auto stage_scales = [&](int ts, uint8_t *dst) {
-        const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + wave * 256));
-        const uint8_t *pa = sA + ts * 4, *pb = sB + ts * 4;
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" : : "v"(pa), "s"(l0) : "m0");
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" : : "v"(pb), "s"(l0 + TM * 4) : "m0");
+    uint8_t *const scl = lds + 4 * TILE_BYTES;
+    const int n_groups = T / SCL_GROUP;
+    // scale bytes of K steps 4G .. 4G+3 (group G, clamped to the last) into slot G & 1: A rows, then B rows
+    auto stage_scales = [&](int G) {
+        G = G < n_groups ? G : n_groups - 1;
+        uint8_t *dst = scl + (G & 1) * SCL_BYTES;
+        const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + wave * 1024));
+        const uint8_t *pa = sA + G * 16, *pb = sB + G * 16;
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pa), "s"(l0) : "m0");
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pb), "s"(l0 + TM * 16) : "m0");
     };
-    auto read_scales = [&](const uint8_t *src) {
+    // scale dwords of K step ts for this lane's rows
+    auto read_scales = [&](int ts) {
+        const uint8_t *src = scl + ((ts / SCL_GROUP) & 1) * SCL_BYTES + (ts & (SCL_GROUP - 1)) * 4;
 #pragma unroll
         for (int x = 0; x < 4; x++) {
-            const uint32_t da = *reinterpret_cast<const uint32_t *>(src + rsa + x * 128);
-            const uint32_t db = *reinterpret_cast<const uint32_t *>(src + rsb + x * 128);
+            const uint32_t da = *reinterpret_cast<const uint32_t *>(src + rsa + x * 512);
+            const uint32_t db = *reinterpret_cast<const uint32_t *>(src + rsb + x * 512);
             sa[x] = g ? da >> 8 : da;
             sb[x] = g ? db >> 8 : db;
         }
     };
-    uint8_t *const scl = lds + 4 * TILE_BYTES;
 #define MX_FENCE() __builtin_amdgcn_sched_barrier(0)
 #define MX_MFMA4(AF, BF, Y, OPS)                                                                                      \
     _Pragma("unroll") for (int x = 0; x < 4; x++)                                                                     \
@@ -140,26 +150,28 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
     // ---- prologue: stage 0 and stage 1 on their way to LDS
     stage(gA, 0, lds);
     stage(gB, 0, lds + TILE_BYTES);
-    stage_scales(0, scl);
+    stage_scales(0);
     {
         const int t1 = T > 1 ? 1 : 0;
         stage(gA, (int64_t)t1 * TK, lds + 2 * TILE_BYTES);
         stage(gB, (int64_t)t1 * TK, lds + 3 * TILE_BYTES);
-        stage_scales(t1, scl + SCL_BYTES);
     }
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): both stages have landed in LDS
     __syncthreads();
 #pragma unroll
     for (int x = 0; x < 4; x++) a0[x] = rd(lds, ra0, 0, x);
     b0[0] = rd(lds + TILE_BYTES, rb0, 0, 0);
-    read_scales(scl);
+    read_scales(0);
 
-    for (int t = 0; t < T; t++) {
-        uint8_t *bufA = lds + (t & 1) * 2 * TILE_BYTES;
-        uint8_t *nxt = lds + ((t & 1) ^ 1) * 2 * TILE_BYTES;
+    // four K steps (one scale group) per trip, so that the scale request sits in a fixed place of
+    // straight-line code (a branch inside the step would undo the interleaving)
+    for (int tt = 0; tt < T; tt += SCL_GROUP) {
+#pragma unroll
+      for (int h = 0; h < SCL_GROUP; h++) {
+        const int t = tt + h;
+        uint8_t *bufA = lds + (h & 1) * 2 * TILE_BYTES;
+        uint8_t *nxt = lds + ((h & 1) ^ 1) * 2 * TILE_BYTES;
         uint8_t *bufB = bufA + TILE_BYTES;
-        uint8_t *sclc = scl + (t & 1) * SCL_BYTES;
-        const uint8_t *scln = scl + ((t & 1) ^ 1) * SCL_BYTES;
         const int t2 = t + 2 < T ? t + 2 : T - 1;
         const int64_t kofs = (int64_t)t2 * TK;
         MX_FENCE();
@@ -197,12 +209,13 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
         MX_MFMA4(a1, b1[2], 2, 2);
         MX_FENCE();
         stage(gB, kofs, bufB);
-        stage_scales(t2, sclc);
+        if (h == 0) stage_scales(tt / SCL_GROUP + 1);   // next group, once every four steps
         a0[2] = rd(nxt, ra0, 0, 2); a0[3] = rd(nxt, ra0, 0, 3); b0[0] = rd(nxt + TILE_BYTES, rb0, 0, 0);
         MX_MFMA4(a1, b1[3], 3, 2);
         MX_FENCE();
-        read_scales(scln);   // for the next step; the matrix instructions above already hold theirs
+        read_scales(t + 1);   // for the next step; the matrix instructions above already hold theirs
         MX_FENCE();
+      }
     }
 #undef MX_MFMA4
 #undef MX_FENCE
@@ -239,7 +252,7 @@ hipError_t launch_gemm_tiled(int64_t M, int64_t N, int64_t K, const uint8_t *Ae,
                              hipStream_t st)
 {
     const bool a8 = fmtA == FP8_E4M3 || fmtA == FP8_E5M2, b8 = fmtB == FP8_E4M3 || fmtB == FP8_E5M2;
-    if (!a8 || !b8 || M % TM || N % TN || K % TK || K == 0 || (M / TM) * (N / TN) > (1 << 24)) return hipErrorNotSupported;
+    if (!a8 || !b8 || M % TM || N % TN || K % (TK * SCL_GROUP) || K == 0 || (M / TM) * (N / TN) > (1 << 24)) return hipErrorNotSupported;
 #define MX_CASE(FA_, FB_)                                                                                          \
     if (fmtA == FA_ && fmtB == FB_)                                                                                \
         return c_dt == DT_F32 ? launch_t<FA_, FB_, DT_F32>(M, N, K, Ae, As, Be, Bs, C, ldc, st)                    \
