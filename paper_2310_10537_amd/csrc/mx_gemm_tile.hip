@@ -89,18 +89,18 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
             for (int t = 0; t < 16; t++) acc[x][y][t] = 0.f;
 
     // Software pipeline (one work-group barrier per K step), buffer cur = t & 1 holds stage t:
-    //   X  : 16 MFMA of sub-step 0 | read a1[0..3], b1[0..1] (sub-step 1) and b0[1..3] just in time
-    //   Y1 :  8 MFMA of sub-step 1 | read b1[2..3]
+    //   X : 16 MFMA of sub-step 0 | read a1[0..3], b1[0..3] (sub-step 1 of stage t)
     //   wait for the direct loads of stage t+1, barrier: every read of stage t was issued before it
-    //   Y2 :  8 MFMA of sub-step 1 | request stage t+2 into the buffer stage t just vacated,
-    //                                read a0[0..3], b0[0] of stage t+1
+    //   Y : 16 MFMA of sub-step 1 | request stage t+2 into the buffer stage t just vacated,
+    //                               read a0[0..3], b0[0..3] (sub-step 0 of stage t+1)
+    // Four LDS reads per four matrix instructions throughout, so the LDS pipe is loaded evenly.
     // LDS reads are written in program order between the matrix instructions and the compiler is
     // fenced group by group, so the LDS pipe and the matrix pipe work at the same time.
     // Stages beyond the last are clamped to the last one (harmless extra loads, no branches).
     typedef __attribute__((address_space(3))) void lds_ptr_t;
     typedef __attribute__((address_space(1))) const void glb_ptr_t;
     uint32_t sa[4], sb[4];   // scale dwords of the current stage, already shifted for this lane
-    v8i_t a0[4], a1[4], b0[2], b1[4];
+    v8i_t a0[4], a1[4], b0[4], b1[4];   // operand fragments of sub-step 0 / 1, double-buffered in time
 
     auto rd = [&](const uint8_t *buf, int ofs0, int sub, int x) -> v8i_t {
         const uint4 lo = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 6)) + x * 4096);
@@ -159,8 +159,7 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): both stages have landed in LDS
     __syncthreads();
 #pragma unroll
-    for (int x = 0; x < 4; x++) a0[x] = rd(lds, ra0, 0, x);
-    b0[0] = rd(lds + TILE_BYTES, rb0, 0, 0);
+    for (int x = 0; x < 4; x++) { a0[x] = rd(lds, ra0, 0, x); b0[x] = rd(lds + TILE_BYTES, rb0, 0, x); }
     read_scales(0);
 
     // four K steps (one scale group) per trip, so that the scale request sits in a fixed place of
@@ -176,41 +175,41 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
         const int64_t kofs = (int64_t)t2 * TK;
         MX_FENCE();
 
-        // ---- X: sub-step 0
-        b0[1] = rd(bufB, rb0, 0, 1); a1[0] = rd(bufA, ra0, 1, 0); b1[0] = rd(bufB, rb0, 1, 0);
+        // ---- X: the 16 matrix instructions of sub-step 0; meanwhile all fragments of sub-step 1
+        // are read, two fragments (four LDS reads) per group of four matrix instructions
+        a1[0] = rd(bufA, ra0, 1, 0); b1[0] = rd(bufB, rb0, 1, 0);
         MX_MFMA4(a0, b0[0], 0, 0);
         MX_FENCE();
-        b0[0] = rd(bufB, rb0, 0, 2); a1[1] = rd(bufA, ra0, 1, 1); b1[1] = rd(bufB, rb0, 1, 1);
+        a1[1] = rd(bufA, ra0, 1, 1); a1[2] = rd(bufA, ra0, 1, 2);
         MX_MFMA4(a0, b0[1], 1, 0);
         MX_FENCE();
-        b0[1] = rd(bufB, rb0, 0, 3); a1[2] = rd(bufA, ra0, 1, 2);
-        MX_MFMA4(a0, b0[0], 2, 0);
+        a1[3] = rd(bufA, ra0, 1, 3); b1[1] = rd(bufB, rb0, 1, 1);
+        MX_MFMA4(a0, b0[2], 2, 0);
         MX_FENCE();
-        a1[3] = rd(bufA, ra0, 1, 3);
-        MX_MFMA4(a0, b0[1], 3, 0);
+        b1[2] = rd(bufB, rb0, 1, 2); b1[3] = rd(bufB, rb0, 1, 3);
+        MX_MFMA4(a0, b0[3], 3, 0);
         MX_FENCE();
-
-        // ---- Y1: sub-step 1, first half
-        b1[2] = rd(bufB, rb0, 1, 2);
-        MX_MFMA4(a1, b1[0], 0, 2);
-        MX_FENCE();
-        b1[3] = rd(bufB, rb0, 1, 3);
-        MX_MFMA4(a1, b1[1], 1, 2);
-        MX_FENCE();
-        // stage t+1 (requested during the previous step) must be in LDS, and every wave must be
-        // done reading stage t, before the buffers change roles
+        // Stage t+1 (requested one step ago) must be in LDS, and every wave must have issued its
+        // last read of stage t, before the buffers change roles.
         __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
         __syncthreads();
         MX_FENCE();
 
-        // ---- Y2: sub-step 1, second half; request stage t+2, first fragments of stage t+1
+        // ---- Y: the 16 matrix instructions of sub-step 1; meanwhile stage t+2 is requested into
+        // the buffer stage t just vacated and the sub-step-0 fragments of stage t+1 are read
         stage(gA, kofs, bufA);
-        a0[0] = rd(nxt, ra0, 0, 0); a0[1] = rd(nxt, ra0, 0, 1);
-        MX_MFMA4(a1, b1[2], 2, 2);
+        a0[0] = rd(nxt, ra0, 0, 0); b0[0] = rd(nxt + TILE_BYTES, rb0, 0, 0);
+        MX_MFMA4(a1, b1[0], 0, 2);
         MX_FENCE();
         stage(gB, kofs, bufB);
+        a0[1] = rd(nxt, ra0, 0, 1); a0[2] = rd(nxt, ra0, 0, 2);
+        MX_MFMA4(a1, b1[1], 1, 2);
+        MX_FENCE();
         if (h == 0) stage_scales(tt / SCL_GROUP + 1);   // next group, once every four steps
-        a0[2] = rd(nxt, ra0, 0, 2); a0[3] = rd(nxt, ra0, 0, 3); b0[0] = rd(nxt + TILE_BYTES, rb0, 0, 0);
+        a0[3] = rd(nxt, ra0, 0, 3); b0[1] = rd(nxt + TILE_BYTES, rb0, 0, 1);
+        MX_MFMA4(a1, b1[2], 2, 2);
+        MX_FENCE();
+        b0[2] = rd(nxt + TILE_BYTES, rb0, 0, 2); b0[3] = rd(nxt + TILE_BYTES, rb0, 0, 3);
         MX_MFMA4(a1, b1[3], 3, 2);
         MX_FENCE();
         read_scales(t + 1);   // for the next step; the matrix instructions above already hold theirs
