@@ -21,13 +21,27 @@
 // groups (256 + 256 rows x 16 bytes each) sit in LDS behind the element tiles.
 // Lanes 32..63 shift their dword by one byte so that a single op_sel value
 // addresses block 2*sub + g for every lane.
-#include "mx_device.hpp"
+//
+// Quantize-on-load (QA = true): the A operand arrives as raw bf16.  Each thread
+// owns four MX blocks of a stage (lane l of wave w: tile row 16w + l/4 + 64p for
+// p < 4, block l % 4 of the row's four), fetches them into registers during the
+// second half of a step, casts them with the hardware converts of the stand-alone
+// cast kernels during the first half of the next step and writes elements and
+// scale bytes into the LDS stage that the B operand reaches by direct load.  The
+// hot loop has no exact path: a block the converts cannot take (non-finite value,
+// or a scale byte so small that Float32 subnormals matter) only raises a flag, and
+// a work-group that saw one recomputes its whole tile afterwards, 32 x 32 tile by
+// tile, with the exact cast of the direct kernel and in the same K order -- so the
+// result is bit-identical to mx_quantize followed by mx_gemm either way.
+#include "mx_convert.hpp"
+#include "mx_gemm_frag.hpp"
 #include "mx_launch.hpp"
 
 namespace mx {
 
 typedef int v8i_t __attribute__((ext_vector_type(8)));
 typedef float v16f_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int TM = 256, TN = 256, TK = 128;      // work-group tile (TK in elements = bytes for 8-bit formats)
 constexpr int TILE_BYTES = TM * TK;              // 32 KB per operand per stage
@@ -39,9 +53,10 @@ __host__ __device__ constexpr int hw_fmt8(int fmt) { return fmt == FP8_E4M3 ? 0 
 // LDS byte offset of 16-byte chunk c (0..7) of tile row r
 __device__ __forceinline__ int swz(int r, int c) { return r * TK + ((c ^ (r & 7)) << 4); }
 
-template <int FA, int FB, int CDT>
+template <int FA, int FB, int CDT, bool QA, int RND>
 __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N, int64_t K,
                                                             const uint8_t *__restrict__ Ae, const uint8_t *__restrict__ As,
+                                                            const uint16_t *__restrict__ Abf, int64_t lda,
                                                             const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
                                                             void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n)
 {
@@ -128,8 +143,42 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
         uint8_t *dst = scl + (G & 1) * SCL_BYTES;
         const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + wave * 1024));
         const uint8_t *pa = sA + G * 16, *pb = sB + G * 16;
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pa), "s"(l0) : "m0");
+        if (!QA) asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pa), "s"(l0) : "m0");
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pb), "s"(l0 + TM * 16) : "m0");
+    };
+
+    // ---- quantize-on-load of A: registers for the thread's four blocks of one stage
+    u32x4_t qa[4][4];
+    uint32_t bad = 0;   // set when a block of this thread cannot take the hardware converts
+    const int q_row = wave * 16 + (lane >> 2), q_kb = lane & 3;
+    const uint16_t *gQ = QA ? Abf + (m0 + q_row) * lda + q_kb * BLOCK : nullptr;
+    // request the four blocks of pass p (tile row q_row + 64p) of K step ts.  Ordinary loads: the
+    // compiler places their waits itself (the direct loads it cannot see only make them stricter).
+    auto qa_request = [&](int ts, int p) {
+        ts = ts < T ? ts : T - 1;
+        const u32x4_t *gp = reinterpret_cast<const u32x4_t *>(gQ + (int64_t)ts * TK + (int64_t)p * 64 * lda);
+#pragma unroll
+        for (int i = 0; i < 4; i++) qa[p][i] = gp[i];
+    };
+    // cast pass p (already in registers) as K step ts and write it into the A tile `dst`
+    auto qa_commit = [&](int ts, int p, uint8_t *dst) {
+        uint32_t d[16], out[8];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            d[4 * i] = qa[p][i][0]; d[4 * i + 1] = qa[p][i][1]; d[4 * i + 2] = qa[p][i][2]; d[4 * i + 3] = qa[p][i][3];
+        }
+        uint32_t m = 0;
+#pragma unroll
+        for (int i = 0; i < 16; i++) m = pk_absmax(m, d[i]);
+        const uint32_t amax16 = pk_hmax(m);
+        const uint32_t sbyte = scale_from_bf16_max<FA>(amax16);
+        // an all-zero block is safe with any scale: the converts keep (signed) zero
+        bad |= (uint32_t)(amax16 != 0 && !fast_ok(amax16, sbyte));
+        convert_bf16_fast<FA, RND, 16>(d, sbyte, out);
+        const int r = q_row + 64 * p;
+        *reinterpret_cast<uint4 *>(dst + swz(r, 2 * q_kb)) = make_uint4(out[0], out[1], out[2], out[3]);
+        *reinterpret_cast<uint4 *>(dst + swz(r, 2 * q_kb + 1)) = make_uint4(out[4], out[5], out[6], out[7]);
+        scl[((ts / SCL_GROUP) & 1) * SCL_BYTES + r * 16 + (ts & (SCL_GROUP - 1)) * 4 + q_kb] = (uint8_t)sbyte;
     };
     // scale dwords of K step ts for this lane's rows
     auto read_scales = [&](int ts) {
@@ -148,15 +197,24 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
         acc[x][Y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(AF[x], BF, acc[x][Y], HA, HB, OPS, (int)sa[x], OPS, (int)sb[Y])
 
     // ---- prologue: stage 0 and stage 1 on their way to LDS
-    stage(gA, 0, lds);
     stage(gB, 0, lds + TILE_BYTES);
     stage_scales(0);
     {
         const int t1 = T > 1 ? 1 : 0;
-        stage(gA, (int64_t)t1 * TK, lds + 2 * TILE_BYTES);
         stage(gB, (int64_t)t1 * TK, lds + 3 * TILE_BYTES);
+        if (!QA) {
+            stage(gA, 0, lds);
+            stage(gA, (int64_t)t1 * TK, lds + 2 * TILE_BYTES);
+        } else {
+#pragma unroll
+            for (int p = 0; p < 4; p++) qa_request(0, p);
+#pragma unroll
+            for (int p = 0; p < 4; p++) qa_commit(0, p, lds);
+#pragma unroll
+            for (int p = 0; p < 4; p++) qa_request(1, p);   // committed during the first step
+        }
     }
-    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): both stages have landed in LDS
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // both stages have landed in LDS
     __syncthreads();
 #pragma unroll
     for (int x = 0; x < 4; x++) { a0[x] = rd(lds, ra0, 0, x); b0[x] = rd(lds + TILE_BYTES, rb0, 0, x); }
@@ -177,30 +235,39 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
 
         // ---- X: the 16 matrix instructions of sub-step 0; meanwhile all fragments of sub-step 1
         // are read, two fragments (four LDS reads) per group of four matrix instructions
+        // Quantize-on-load: the registers hold stage t+1 of A (requested half a step ago); one
+        // pass per group is cast and written to the other buffer, whose last readers passed the
+        // previous barrier.
         a1[0] = rd(bufA, ra0, 1, 0); b1[0] = rd(bufB, rb0, 1, 0);
         MX_MFMA4(a0, b0[0], 0, 0);
+        if (QA) qa_commit(t + 1, 0, nxt);
         MX_FENCE();
         a1[1] = rd(bufA, ra0, 1, 1); a1[2] = rd(bufA, ra0, 1, 2);
         MX_MFMA4(a0, b0[1], 1, 0);
+        if (QA) qa_commit(t + 1, 1, nxt);
         MX_FENCE();
         a1[3] = rd(bufA, ra0, 1, 3); b1[1] = rd(bufB, rb0, 1, 1);
         MX_MFMA4(a0, b0[2], 2, 0);
+        if (QA) qa_commit(t + 1, 2, nxt);
         MX_FENCE();
         b1[2] = rd(bufB, rb0, 1, 2); b1[3] = rd(bufB, rb0, 1, 3);
         MX_MFMA4(a0, b0[3], 3, 0);
+        if (QA) qa_commit(t + 1, 3, nxt);
         MX_FENCE();
         // Stage t+1 (requested one step ago) must be in LDS, and every wave must have issued its
         // last read of stage t, before the buffers change roles.
-        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         MX_FENCE();
 
         // ---- Y: the 16 matrix instructions of sub-step 1; meanwhile stage t+2 is requested into
         // the buffer stage t just vacated and the sub-step-0 fragments of stage t+1 are read
-        stage(gA, kofs, bufA);
+        if (!QA) stage(gA, kofs, bufA);
+        else { qa_request(t + 2, 0); qa_request(t + 2, 1); }
         a0[0] = rd(nxt, ra0, 0, 0); b0[0] = rd(nxt + TILE_BYTES, rb0, 0, 0);
         MX_MFMA4(a1, b1[0], 0, 2);
         MX_FENCE();
+        if (QA) { qa_request(t + 2, 2); qa_request(t + 2, 3); }
         stage(gB, kofs, bufB);
         a0[1] = rd(nxt, ra0, 0, 1); a0[2] = rd(nxt, ra0, 0, 2);
         MX_MFMA4(a1, b1[1], 1, 2);
@@ -219,6 +286,17 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
 #undef MX_MFMA4
 #undef MX_FENCE
 
+    // ---- quantize-on-load: exact recomputation of the tile if any block needed the exact cast
+    if constexpr (QA) {
+        if (__syncthreads_or((int)bad)) {
+#pragma unroll 1
+            for (int sub = 0; sub < 16; sub++)
+                direct_tile<FA, FB, true, RND, CDT>(M, N, K, nullptr, nullptr, Abf, lda, Be, Bs, C, ldc,
+                                                    m0 + wm * 128 + (sub >> 2) * 32, n0 + wn * 128 + (sub & 3) * 32, lane);
+            return;
+        }
+    }
+
     // ---- epilogue: lane (li, g), register t of tile (x, y) -> C[8*(t/4) + 4g + t%4][li]
 #pragma unroll
     for (int x = 0; x < 4; x++)
@@ -233,29 +311,42 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
             }
 }
 
-template <int FA, int FB, int CDT>
-static hipError_t launch_t(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint8_t *Be,
-                           const uint8_t *Bs, void *C, int64_t ldc, hipStream_t st)
+template <int FA, int FB, int CDT, bool QA, int RND>
+static hipError_t launch_t(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint16_t *Abf,
+                           int64_t lda, const uint8_t *Be, const uint8_t *Bs, void *C, int64_t ldc, hipStream_t st)
 {
-    auto kern = gemm8_tile_kernel<FA, FB, CDT>;
+    auto kern = gemm8_tile_kernel<FA, FB, CDT, QA, RND>;
     const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
     const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, M, N, K, Ae, As, Abf, lda, Be, Bs, C, ldc,
                        tiles_m, tiles_n);
     return hipGetLastError();
 }
 
-// Tiled path for 8-bit x 8-bit operands on full tiles; hipErrorNotSupported otherwise.
-hipError_t launch_gemm_tiled(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, int fmtA,
-                             const uint8_t *Be, const uint8_t *Bs, int fmtB, void *C, int c_dt, int64_t ldc,
-                             hipStream_t st)
+template <int FA, int FB>
+static hipError_t launch_mode(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint16_t *Abf,
+                              int64_t lda, int rnd, const uint8_t *Be, const uint8_t *Bs, void *C, int c_dt, int64_t ldc,
+                              hipStream_t st)
+{
+#define MX_GO(QA_, RND_)                                                                                           \
+    (c_dt == DT_F32 ? launch_t<FA, FB, DT_F32, QA_, RND_>(M, N, K, Ae, As, Abf, lda, Be, Bs, C, ldc, st)            \
+                    : launch_t<FA, FB, DT_BF16, QA_, RND_>(M, N, K, Ae, As, Abf, lda, Be, Bs, C, ldc, st))
+    if (!Abf) return MX_GO(false, ROUND_RNE);
+    return rnd == ROUND_RNE ? MX_GO(true, ROUND_RNE) : MX_GO(true, ROUND_HALF_AWAY);
+#undef MX_GO
+}
+
+// Tiled path for 8-bit x 8-bit operands on full tiles (a_bf16 != nullptr: A cast on load);
+// hipErrorNotSupported otherwise.
+hipError_t launch_gemm_tiled(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const void *a_bf16,
+                             int64_t lda, int rnd, int fmtA, const uint8_t *Be, const uint8_t *Bs, int fmtB, void *C,
+                             int c_dt, int64_t ldc, hipStream_t st)
 {
     const bool a8 = fmtA == FP8_E4M3 || fmtA == FP8_E5M2, b8 = fmtB == FP8_E4M3 || fmtB == FP8_E5M2;
     if (!a8 || !b8 || M % TM || N % TN || K % (TK * SCL_GROUP) || K == 0 || (M / TM) * (N / TN) > (1 << 24)) return hipErrorNotSupported;
+    const uint16_t *Abf = static_cast<const uint16_t *>(a_bf16);
 #define MX_CASE(FA_, FB_)                                                                                          \
-    if (fmtA == FA_ && fmtB == FB_)                                                                                \
-        return c_dt == DT_F32 ? launch_t<FA_, FB_, DT_F32>(M, N, K, Ae, As, Be, Bs, C, ldc, st)                    \
-                              : launch_t<FA_, FB_, DT_BF16>(M, N, K, Ae, As, Be, Bs, C, ldc, st);
+    if (fmtA == FA_ && fmtB == FB_) return launch_mode<FA_, FB_>(M, N, K, Ae, As, Abf, lda, rnd, Be, Bs, C, c_dt, ldc, st);
     MX_CASE(FP8_E4M3, FP8_E4M3)
     MX_CASE(FP8_E4M3, FP8_E5M2)
     MX_CASE(FP8_E5M2, FP8_E4M3)

@@ -28,7 +28,7 @@ NAMES = ("fp8_e4m3", "fp8_e5m2", "fp6_e3m2", "fp6_e2m3", "fp4_e2m1")
 RNE, AWAY = 0, 1
 TOL = 1e-5
 
-from gpu_util import to_dev, to_host  # noqa: E402
+from gpu_util import same_floats, to_dev, to_host  # noqa: E402
 
 
 @pytest.fixture(scope="module")
@@ -238,6 +238,48 @@ def test_gemm_qa_equals_quantize_then_gemm(mx, oracle, fa, rnd):
     eb, sb = oracle.quantize(b, 1, 0)
     C_ref, C_abs = oracle.gemm(ea, sa, fa, eb, sb, 0, K, want_abs=True)
     check_gemm(to_host(C1), C_ref, C_abs, "qa", hw_term_for(oracle, ea, sa, fa, eb, sb, 0, K))
+
+
+@pytest.mark.parametrize("fa", [0, 1], ids=["e4m3", "e5m2"])
+@pytest.mark.parametrize("rnd", [RNE, AWAY], ids=["rne", "away"])
+@pytest.mark.parametrize("special", ["none", "zeros", "exact_path"])
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_gemm_qa_tiled_equals_quantize_then_gemm(mx, oracle, fa, rnd, special, dt):
+    """Whole 256 x 256 tiles with K a multiple of 512 take the LDS-tiled kernel, which casts A
+    with the hardware converts inside the K loop.  It must stay bit-identical to the two-step
+    path: on ordinary data, on all-zero blocks (signed zeros included), and when blocks with
+    Inf / NaN / near-subnormal magnitudes force a work-group to recompute its tile exactly."""
+    M, N, K = 512, 256, 1024
+    a = inputs.student_t_bf16((M, K), seed=70 + fa).copy()
+    if special == "zeros":
+        a[3, 0:64] = 0
+        a[300, 512:544] = 0x8000            # a block of -0.0
+        a[255, 992:1024] = 0
+        a[17, 32:64] = np.where(np.arange(32) % 2 == 0, 0, 0x8000).astype(np.uint16)
+    elif special == "exact_path":
+        a[5, 40] = 0x7F80                   # +Inf         (tile row 0)
+        a[6, 100] = 0xFFC1                  # a NaN
+        a[7, 160:192] = np.arange(32, dtype=np.uint16) + 1        # bf16 subnormals only
+        a[8, 192:224] = (np.arange(32, dtype=np.uint16) * 5) + 0x0080   # around 2^-126
+        # tile row 1 (rows 256..511) stays ordinary: its work-group keeps the fast result
+    b = inputs.gaussian_f32((N, K), seed=71, std=0.02)
+    ad = to_dev(a)
+    gb = mx.mx_quantize(to_dev(b), 1, 0)
+    ga = mx.mx_quantize(ad, 1, fa, rnd)
+    C2 = mx.mx_gemm(ga[0], ga[1], fa, gb[0], gb[1], 0, K, dtype=dt)
+    C1 = mx.mx_gemm_qa(ad, fa, rnd, gb[0], gb[1], 0, dtype=dt)
+    h1, h2 = to_host(C1), to_host(C2)
+    assert same_floats(h1, h2)
+    if special == "exact_path":
+        # row 5 holds an Inf (E4M3: NaN code, E5M2: Inf code), row 6 a NaN: those rows and no others are non-finite
+        bad = ~np.isfinite(h1) if dt == torch.float32 else (h1 & 0x7FFF) >= 0x7F80
+        assert bad[5].all() and bad[6].all() and bad.sum() == 2 * N
+    if dt == torch.float32 and special != "exact_path":
+        ea, sa = oracle.quantize(a, 1, fa, rnd)
+        eb, sb = oracle.quantize(b, 1, 0)
+        assert np.array_equal(to_host(ga[0]), ea) and np.array_equal(to_host(ga[1]), sa)
+        C_ref, C_abs = oracle.gemm(ea, sa, fa, eb, sb, 0, K, want_abs=True)
+        check_gemm(to_host(C1), C_ref, C_abs, "qa-tiled", hw_term_for(oracle, ea, sa, fa, eb, sb, 0, K))
 
 
 def sampled_check(mx, oracle, C, A, fa, B, fb, K, seed, n=2048):
