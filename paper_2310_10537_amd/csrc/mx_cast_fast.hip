@@ -52,6 +52,7 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
                                                             uint8_t *__restrict__ elems, uint8_t *__restrict__ scales,
                                                             int64_t n_elems)
 {
+    if constexpr (FMT == FP8_E4M3 || FMT == FP8_E5M2) fp8_saturate_mode();
     constexpr int w = Fmt<FMT>::bits;
     constexpr bool SIX = (w == 6);
     // per wave: FP6 needs 64 blocks x 80 bytes (padded) for the transpose; everyone needs 64 scale bytes
@@ -179,6 +180,7 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
                                                             uint8_t *__restrict__ scales, int64_t row_tiles,
                                                             int64_t n_tiles, int64_t per_xcd)
 {
+    if constexpr (FMT == FP8_E4M3 || FMT == FP8_E5M2) fp8_saturate_mode();
     constexpr int w = Fmt<FMT>::bits;
     __shared__ __attribute__((aligned(16))) uint8_t tile[COL_TILE_R * COL_TILE_C * 2];   // 16 KB, 128-byte rows
     const int t = threadIdx.x;

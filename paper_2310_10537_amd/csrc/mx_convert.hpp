@@ -8,9 +8,11 @@
 //     the Float32 scale operand (mantissa ignored, E = 0 means 2^-127);
 //     subnormal results and all 24 source bits are honoured;
 //   * FP6 / FP4 saturate to the largest normal -- what Algorithm 1 asks for;
-//   * FP8 does not saturate: anything above the largest normal becomes NaN
-//     (E4M3, code 0x7F) or Inf (E5M2, code 0x7C), so those codes are patched
-//     back to the largest normal (0x7E / 0x7B) here;
+//   * FP8 does not saturate by default: anything above the largest normal becomes
+//     NaN (E4M3, code 0x7F) or Inf (E5M2, code 0x7C).  With the wave's
+//     MODE.FP16_OVFL bit set the same converts clamp a finite overflow to the
+//     largest normal (0x7E / 0x7B) -- what Algorithm 1 asks for -- so every
+//     kernel that converts to FP8 sets that bit first (fp8_saturate_mode);
 //   * NaN / Inf inputs and Float32-subnormal inputs are not treated the way
 //     Algorithm 1 needs.  Blocks that contain a non-finite value, or whose scale
 //     byte is below 18 (only then can a Float32 subnormal reach half of the
@@ -59,7 +61,8 @@ __device__ __forceinline__ uint32_t scale_from_bf16_max(uint32_t amax16)
 // true when the block can use the hardware converts
 __device__ __forceinline__ bool fast_ok(uint32_t amax16, uint32_t s) { return amax16 < 0x7F80u && s >= FAST_MIN_SCALE; }
 
-// FP8: NaN / Inf codes produced by finite overflow -> largest normal, sign kept
+// FP8 codes converted with MODE.FP16_OVFL clear: NaN / Inf codes produced by finite
+// overflow -> largest normal, sign kept
 template <int FMT>
 __device__ __forceinline__ uint32_t fp8_unoverflow(uint32_t codes)
 {
@@ -69,10 +72,18 @@ __device__ __forceinline__ uint32_t fp8_unoverflow(uint32_t codes)
     return codes - (ov >> 7);
 }
 
+// Make the FP8 converts of this wave clamp instead of overflowing (on = true) or restore the
+// default: MODE (hardware register 1) bit 23, FP16_OVFL.  Per-wave state.  The bit also makes
+// the matrix instructions clamp NaN / Inf operands and results, so it must be clear whenever a
+// matrix instruction whose result is kept can issue.
+__device__ __forceinline__ void fp8_saturate_mode(bool on = true) { __builtin_amdgcn_s_setreg(1 | (23 << 6) | (0 << 11), on ? 1 : 0); }
+
 // Convert ND packed bf16 dwords (2*ND consecutive elements of one block) with
 // scale byte s (>= FAST_MIN_SCALE, finite inputs only) into packed codes.
 // out receives 2*ND*bits/32 dwords.  FP6 needs the whole block (ND = 16).
-template <int FMT, int RND, int ND>
+// FP8 formats: with PATCH = false the caller has set fp8_saturate_mode(); with PATCH = true
+// the wave runs in the default mode and overflowed codes are patched afterwards.
+template <int FMT, int RND, int ND, bool PATCH = false>
 __device__ __forceinline__ void convert_bf16_fast(const uint32_t (&d)[ND], uint32_t s, uint32_t *out)
 {
     const float sf = __uint_as_float(s << 23);
@@ -100,7 +111,7 @@ __device__ __forceinline__ void convert_bf16_fast(const uint32_t (&d)[ND], uint3
                     r = __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(r, b0, b1, sf, true);
                 }
             }
-            out[j] = fp8_unoverflow<FMT>(__builtin_bit_cast(uint32_t, r));
+            out[j] = PATCH ? fp8_unoverflow<FMT>(__builtin_bit_cast(uint32_t, r)) : __builtin_bit_cast(uint32_t, r);
         }
     } else if constexpr (FMT == FP4_E2M1) {
 #pragma unroll

@@ -86,10 +86,32 @@ static hipError_t dispatch_b(const GemmArgs &g, int fmtB, int rnd, int c_dt)
     }
 }
 
+// whether the fused quantize-on-load tiled kernel beats cast + plain tiled kernel (256 x 256 tiles)
+static bool qa_fused_pays(int64_t M, int64_t N) { return N / 256 <= 2 && (M / 256) * (N / 256) >= 256; }
+
 hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, const uint8_t *A_scales,
                        const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
                        const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st)
 {
+    // Quantize-on-load on whole tiles.  The fused kernel casts each A tile once per column of
+    // output tiles and reads it as bf16 that often, so it pays only for narrow outputs (measured:
+    // up to two tile columns), and only when there are enough tiles to fill the chip, since the
+    // stand-alone cast always runs on every compute unit.  Every other problem casts A once into
+    // a stream-ordered workspace (the same cast kernel, hence the same bytes, as mx_quantize)
+    // and runs the plain tiled kernel on it.
+    if (a_bf16 && gemm_tiled_applies(M, N, K, fmtA, fmtB) && !qa_fused_pays(M, N)) {
+        const size_t eb = (size_t)M * (size_t)K, sb = eb / BLOCK;
+        uint8_t *ws = nullptr;
+        hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), eb + sb, st);
+        if (e == hipSuccess) {
+            e = launch_cast_bf16_fast(a_bf16, M, K, lda, 1, fmtA, rnd, ws, ws + eb, st);
+            if (e == hipSuccess)
+                e = launch_gemm_tiled(M, N, K, ws, ws + eb, nullptr, 0, rnd, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
+            const hipError_t f = hipFreeAsync(ws, st);
+            return e != hipSuccess ? e : f;
+        }
+        (void)hipGetLastError();   // no workspace: the fused kernel needs none
+    }
     {
         hipError_t e = launch_gemm_tiled(M, N, K, A_elems, A_scales, a_bf16, lda, rnd, fmtA, B_elems, B_scales, fmtB, C,
                                          c_dt, ldc, st);

@@ -174,7 +174,11 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
         const uint32_t sbyte = scale_from_bf16_max<FA>(amax16);
         // an all-zero block is safe with any scale: the converts keep (signed) zero
         bad |= (uint32_t)(amax16 != 0 && !fast_ok(amax16, sbyte));
+        // the converts clamp finite overflow to the largest normal only in saturate mode, and the
+        // matrix instructions must not run in it (they would clamp NaN / Inf operands of B too)
+        fp8_saturate_mode(true);
         convert_bf16_fast<FA, RND, 16>(d, sbyte, out);
+        fp8_saturate_mode(false);
         const int r = q_row + 64 * p;
         *reinterpret_cast<uint4 *>(dst + swz(r, 2 * q_kb)) = make_uint4(out[0], out[1], out[2], out[3]);
         *reinterpret_cast<uint4 *>(dst + swz(r, 2 * q_kb + 1)) = make_uint4(out[4], out[5], out[6], out[7]);
@@ -336,14 +340,20 @@ static hipError_t launch_mode(int64_t M, int64_t N, int64_t K, const uint8_t *Ae
 #undef MX_GO
 }
 
+bool gemm_tiled_applies(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB)
+{
+    const bool a8 = fmtA == FP8_E4M3 || fmtA == FP8_E5M2, b8 = fmtB == FP8_E4M3 || fmtB == FP8_E5M2;
+    return a8 && b8 && M % TM == 0 && N % TN == 0 && K % (TK * SCL_GROUP) == 0 && K > 0 && M > 0 && N > 0 &&
+           (M / TM) * (N / TN) <= (1 << 24);
+}
+
 // Tiled path for 8-bit x 8-bit operands on full tiles (a_bf16 != nullptr: A cast on load);
 // hipErrorNotSupported otherwise.
 hipError_t launch_gemm_tiled(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const void *a_bf16,
                              int64_t lda, int rnd, int fmtA, const uint8_t *Be, const uint8_t *Bs, int fmtB, void *C,
                              int c_dt, int64_t ldc, hipStream_t st)
 {
-    const bool a8 = fmtA == FP8_E4M3 || fmtA == FP8_E5M2, b8 = fmtB == FP8_E4M3 || fmtB == FP8_E5M2;
-    if (!a8 || !b8 || M % TM || N % TN || K % (TK * SCL_GROUP) || K == 0 || (M / TM) * (N / TN) > (1 << 24)) return hipErrorNotSupported;
+    if (!gemm_tiled_applies(M, N, K, fmtA, fmtB)) return hipErrorNotSupported;
     const uint16_t *Abf = static_cast<const uint16_t *>(a_bf16);
 #define MX_CASE(FA_, FB_)                                                                                          \
     if (fmtA == FA_ && fmtB == FB_) return launch_mode<FA_, FB_>(M, N, K, Ae, As, Abf, lda, rnd, Be, Bs, C, c_dt, ldc, st);

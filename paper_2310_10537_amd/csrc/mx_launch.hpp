@@ -22,6 +22,9 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
                        const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
                        const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st);
 
+// true when launch_gemm_tiled takes the problem
+bool gemm_tiled_applies(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
+
 // LDS-tiled kernel for 8-bit operands on whole 256 x 256 tiles with K a multiple of 512
 // (a_bf16 != nullptr: A is raw bf16 and cast on load); hipErrorNotSupported when the problem
 // does not qualify.
