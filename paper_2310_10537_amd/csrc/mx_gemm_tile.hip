@@ -67,14 +67,31 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
     const int wm = wave >> 1, wn = wave & 1;
     const int li = lane & 31, g = lane >> 5;
 
-    // XCD-aware rasterisation: work-groups are dealt round-robin to 8 XCDs; give each XCD
-    // a contiguous band of M tiles so that its L2 sees few distinct A panels.
+    // XCD-aware rasterisation.  Work-groups are dealt round-robin to the 8 XCDs, each with its
+    // own L2, and the first 32 an XCD receives run at the same time (one per compute unit), in
+    // step over K.  What that group misses in L2 per K step is one slab per distinct tile row
+    // plus one per distinct tile column, so it should be as square as possible: each XCD gets a
+    // band of M tiles and walks it in sub-bands of 4 tile rows, column by column (4 x 8 tiles at a
+    // time instead of 2 x 16: a third fewer L2 misses, measured with the fetch counters).
     const int n_tiles = tiles_m * tiles_n;
     const int per_xcd = (n_tiles + 7) >> 3;
-    const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd || tile_id >= n_tiles) return;
-    const int64_t m0 = (int64_t)(tile_id / tiles_n) * TM;
-    const int64_t n0 = (int64_t)(tile_id % tiles_n) * TN;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    if (idx >= per_xcd) return;
+    int tm, tn;
+    if ((tiles_m & 7) == 0) {
+        const int band = tiles_m >> 3;                       // tile rows per XCD
+        const int H = (band & 3) == 0 ? 4 : (band & 1) == 0 ? 2 : 1;
+        const int sub = idx / (H * tiles_n), r = idx - sub * (H * tiles_n);
+        tm = xcd * band + sub * H + r % H;
+        tn = r / H;
+    } else {
+        const int tile_id = xcd * per_xcd + idx;
+        if (tile_id >= n_tiles) return;
+        tm = tile_id / tiles_n;
+        tn = tile_id % tiles_n;
+    }
+    const int64_t m0 = (int64_t)tm * TM;
+    const int64_t n0 = (int64_t)tn * TN;
     const int64_t nkb = K / BLOCK;
     const int T = (int)(K / TK);
 

@@ -135,7 +135,10 @@ def test_shapes(mx, oracle, shape):
 
 @pytest.mark.parametrize("fa,fb", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("shape,dt", [((512, 256, 384), torch.float32), ((256, 768, 128), torch.bfloat16),
-                                      ((256, 512, 1536), torch.float32), ((512, 256, 512), torch.bfloat16)])
+                                      ((256, 512, 1536), torch.float32), ((512, 256, 512), torch.bfloat16),
+                                      # 8, 16 and 32 tile rows: the XCD-banded tile orders (sub-bands of 1, 2, 4 rows)
+                                      ((2048, 768, 512), torch.float32), ((4096, 512, 512), torch.bfloat16),
+                                      ((8192, 256, 512), torch.float32)])
 def test_tiled_kernel_full_tiles(mx, oracle, fa, fb, shape, dt):
     """Shapes made of whole 256 x 256 x 128 tiles take the LDS-tiled kernel; blocks
     get very different scales so that a scale byte read for the wrong row, block
