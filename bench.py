@@ -13,9 +13,11 @@ already resident in HBM:
     output, once from pre-quantized operands (mx_gemm) and once with the bf16
     activations cast on load (mx_gemm_qa).
 Inputs rotate over three copies so that no call finds its source in the 256 MB
-Infinity Cache.  Every call is bracketed by events on the stream it runs on; the
-headline value is the cast throughput (algorithmic bytes of the 12 casts divided
-by their summed durations); GEMM TFLOP/s are reported beside it.
+Infinity Cache.  K steps are timed as a whole (ms_per_step).  Each call's own
+average duration is then measured the same way: K launches of that call back to
+back on the stream it runs on, between two events, with the same buffer rotation.
+The headline value is the cast throughput (algorithmic bytes of the 12 casts
+divided by their summed average durations); GEMM TFLOP/s are reported beside it.
 
 Prints ONE JSON line.
 """
@@ -41,8 +43,23 @@ GM, GK, GN = 8192, 4096, 4096
 NCOPY = 3
 # HBM bytes per launch (read + write) from hardware counters of a profiled run of this file,
 # scaled by what the same counters read for the 128 MiB copy above; the profiles directory holds
-# the summaries these come from.  Labels without a measurement report null.
-MEASURED_TRAFFIC_BYTES = {}
+# the summaries these come from (bench_hot_path_hbm_traffic.txt).  Labels without a measurement
+# report null (the E4M3 row cast shares its kernel with launches of another size in that run).
+MEASURED_TRAFFIC_BYTES = {
+    "cast_fp4_e2m1_axis0": 170478334,
+    "cast_fp4_e2m1_axis1": 169936739,
+    "cast_fp6_e2m3_axis0": 187849283,
+    "cast_fp6_e2m3_axis1": 186675680,
+    "cast_fp6_e3m2_axis0": 187828848,
+    "cast_fp6_e3m2_axis1": 186679442,
+    "cast_fp8_e4m3_axis0": 203895506,
+    "cast_fp8_e5m2_axis0": 203857445,
+    "cast_fp8_e5m2_axis1": 203513169,
+    "cast_int8_axis0": 203723596,
+    "cast_int8_axis1": 203527655,
+    "dequantize_fp8_e4m3_bf16": 205567236,
+    "gemm_fp8_e4m3": 275387187,
+}
 
 
 def cast_bytes(fmt, n_elem):
@@ -55,26 +72,29 @@ def to_dev_bf16(bits):
 
 
 class Timed:
-    """Collects (label, start_event, end_event) on the current stream."""
+    """Average duration per label: run(label, fn, n) launches fn n times between
+    two events on the current stream."""
 
-    def __init__(self):
+    def __init__(self, n):
+        self.n = n
         self.recs = []
 
     def run(self, label, fn):
         a = torch.cuda.Event(enable_timing=True)
         b = torch.cuda.Event(enable_timing=True)
         a.record()
-        fn()
+        for _ in range(self.n):
+            fn()
         b.record()
         self.recs.append((label, a, b))
 
     def totals(self):
+        """label -> [summed ms, launches]"""
         out = {}
         for label, a, b in self.recs:
-            ms = a.elapsed_time(b)
             t = out.setdefault(label, [0.0, 0])
-            t[0] += ms
-            t[1] += 1
+            t[0] += a.elapsed_time(b)
+            t[1] += self.n
         return out
 
 
@@ -134,38 +154,53 @@ def main():
 
     rot = [0]
 
-    def step(timer):
-        for fmt in range(6):
-            for axis in (1, 0):
-                i = rot[0]
-                rot[0] += 1
-                e, s = outs[(fmt, axis)][i % 2]
-                timer.run(f"cast_{mx.FORMAT_NAMES[fmt]}_axis{axis}",
-                          lambda: mx.mx_quantize(xs[i % NCOPY], axis, fmt, mx.ROUND_RNE, e, s))
-        i = rot[0]
-        timer.run("dequantize_fp8_e4m3_bf16",
-                  lambda: mx.mx_dequantize(deq_in[0], deq_in[1], mx.FP8_E4M3, ROWS, COLS, 1, out=deq_out[i % 2]))
-        timer.run("gemm_fp8_e4m3",
-                  lambda: mx.mx_gemm(Aq[i % NCOPY][0], Aq[i % NCOPY][1], mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, GK,
-                                     out=Cs[i % NCOPY]))
-        timer.run("gemm_qa_fp8_e4m3",
-                  lambda: mx.mx_gemm_qa(As[(i + 1) % NCOPY], mx.FP8_E4M3, mx.ROUND_RNE, Be, Bs, mx.FP8_E4M3,
-                                        out=Cs[(i + 1) % NCOPY]))
+    def nxt():
+        rot[0] += 1
+        return rot[0]
 
-    warm = Timed()
+    def cast_call(fmt, axis):
+        def f():
+            i = nxt()
+            e, s = outs[(fmt, axis)][i % 2]
+            mx.mx_quantize(xs[i % NCOPY], axis, fmt, mx.ROUND_RNE, e, s)
+        return f
+
+    def deq_call():
+        mx.mx_dequantize(deq_in[0], deq_in[1], mx.FP8_E4M3, ROWS, COLS, 1, out=deq_out[nxt() % 2])
+
+    def gemm_call():
+        i = nxt()
+        mx.mx_gemm(Aq[i % NCOPY][0], Aq[i % NCOPY][1], mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, GK, out=Cs[i % NCOPY])
+
+    def gemm_qa_call():
+        i = nxt()
+        mx.mx_gemm_qa(As[i % NCOPY], mx.FP8_E4M3, mx.ROUND_RNE, Be, Bs, mx.FP8_E4M3, out=Cs[i % NCOPY])
+
+    calls = [(f"cast_{mx.FORMAT_NAMES[fmt]}_axis{axis}", cast_call(fmt, axis)) for fmt in range(6) for axis in (1, 0)]
+    calls += [("dequantize_fp8_e4m3_bf16", deq_call), ("gemm_fp8_e4m3", gemm_call), ("gemm_qa_fp8_e4m3", gemm_qa_call)]
+
+    def step(_timer=None):
+        for _label, fn in calls:
+            fn()
+
     for _ in range(args.warmup):
-        step(warm)
+        step()
     # One plain 128 MiB -> 128 MiB device copy outside the timed region: the kernel of known
     # traffic against which hardware byte counters of a profiled run are scaled.
     deq_out[0].copy_(xs[0])
     torch.cuda.synchronize()
 
-    timer = Timed()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(timer)
+        step()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
+
+    # per-call average durations over the same number of launches
+    timer = Timed(args.steps)
+    for label, fn in calls:
+        timer.run(label, fn)
+    torch.cuda.synchronize()
     tot = timer.totals()
 
     n_elem = ROWS * COLS

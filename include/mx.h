@@ -12,7 +12,8 @@
  *
  * Conventions common to all entry points
  *   - Every tensor pointer is DEVICE memory owned by the caller; the library
- *     never allocates, frees, or keeps a pointer after the call returns.
+ *     keeps no pointer after the call returns.  No entry point allocates,
+ *     with one exception stated at mx_gemm_qa (a stream-ordered workspace).
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default
  *     stream).  Work is enqueued on it asynchronously; no call synchronises.
  *   - The return value is an mx_status_t.  On any value other than MX_OK
@@ -133,6 +134,15 @@ int mx_gemm(int64_t M, int64_t N, int64_t K,
  * elements, a multiple of 8) and cast to fmtA with rounding rnd while it is
  * loaded.  The result is bit-identical to mx_quantize(A, axis 1) followed by
  * mx_gemm.
+ * Three kernels serve it, chosen by shape.  Problems made of whole 256 x 256
+ * output tiles with 8-bit formats and K a multiple of 512 run the LDS-tiled
+ * kernel: with at most two tile columns and at least 256 tiles the cast happens
+ * inside its K loop (one launch, no workspace); otherwise A is first cast into
+ * a workspace of M*K*(1 + 1/32) bytes taken from and returned to the device's
+ * default memory pool in stream order (hipMallocAsync / hipFreeAsync on
+ * hip_stream) -- the only allocation the library makes; if the pool refuses, the
+ * fused kernel runs instead.  Every other problem casts in registers in the
+ * direct kernel.
  */
 int mx_gemm_qa(int64_t M, int64_t N, int64_t K,
                const void *A_bf16, int64_t lda, mx_format_t fmtA, mx_round_t rnd,
