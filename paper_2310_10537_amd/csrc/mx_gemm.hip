@@ -99,8 +99,9 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
     // stand-alone cast always runs on every compute unit.  Every other problem casts A once into
     // a stream-ordered workspace (the same cast kernel, hence the same bytes, as mx_quantize)
     // and runs the plain tiled kernel on it.
-    if (a_bf16 && gemm_tiled_applies(M, N, K, fmtA, fmtB) && !qa_fused_pays(M, N)) {
-        const size_t eb = (size_t)M * (size_t)K, sb = eb / BLOCK;
+    if (a_bf16 && gemm_tiled_applies(M, N, K, fmtA, fmtB) && !(gemm_tiled_fuses_cast(fmtA, fmtB) && qa_fused_pays(M, N))) {
+        const size_t bits = fmtA <= FP8_E5M2 ? 8 : fmtA <= FP6_E2M3 ? 6 : 4;
+        const size_t eb = (size_t)M * (size_t)K * bits / 8, sb = (size_t)M * (size_t)K / BLOCK;
         uint8_t *ws = nullptr;
         hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), eb + sb, st);
         if (e == hipSuccess) {
@@ -110,7 +111,7 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
             const hipError_t f = hipFreeAsync(ws, st);
             return e != hipSuccess ? e : f;
         }
-        (void)hipGetLastError();   // no workspace: the fused kernel needs none
+        (void)hipGetLastError();   // no workspace: the kernels below need none
     }
     {
         hipError_t e = launch_gemm_tiled(M, N, K, A_elems, A_scales, a_bf16, lda, rnd, fmtA, B_elems, B_scales, fmtB, C,

@@ -1,18 +1,24 @@
-// LDS-tiled MX GEMM for 8-bit operands (Section 4.1 of arXiv 2310.10537) on
-// gfx950's block-scaled 32x32x64 f8f6f4 matrix instruction.
+// LDS-tiled MX GEMM (Section 4.1 of arXiv 2310.10537) on gfx950's block-scaled
+// 32x32x64 f8f6f4 matrix instruction, for every pair of FP8 / FP6 / FP4 formats.
 //
 // Work-group: 256 threads = 4 waves in a 2 x 2 arrangement, output tile
 // 256 x 256, K step 128 (four MX blocks).  Each wave owns a 128 x 128 sub-tile:
 // 4 x 4 matrix-instruction tiles of 32 x 32, i.e. 256 accumulator registers.
-// Per K step the work-group stages 256 x 128 bytes of A and of B in LDS (double
-// buffered, 128 KB in all) with direct global-to-LDS loads (no register staging,
-// no LDS store instructions: measured, the LDS pipe cannot carry the operand
-// reads of this tile shape and store instructions as well).  Every 16-byte
-// chunk c of row r sits at chunk position c ^ (r & 7) of the row, so the operand
-// reads (32 rows, same chunk) are free of bank conflicts; since a direct load
-// writes its 64 lanes to consecutive LDS addresses, the swizzle is applied on
-// the global side: the lane that fills position p of a row fetches chunk
-// p ^ (r & 7) of that row.
+// Per K step the work-group stages 256 rows x 128 elements of A and of B in LDS
+// (double buffered) with direct global-to-LDS loads (no register staging, no LDS
+// store instructions: measured, the LDS pipe cannot carry the operand reads of
+// this tile shape and store instructions as well).  A direct load writes its 64
+// lanes to consecutive 16-byte LDS slots, so any layout that permutes 16-byte
+// slots is free: the permutation is applied on the global side.
+//   8-bit: a row is 128 bytes = 8 slots; chunk c of row r sits in slot
+//          c ^ (r & 7), so the operand reads (32 rows, same chunk) are free of
+//          bank conflicts.  A lane's operand is chunks {4s+g, 4s+g+2} of sub-step s.
+//   6-bit: a row is 96 bytes = 8 units of 12 bytes, fetched with 12-byte direct
+//          loads, which still land in 16-byte slots (4 bytes of each stay
+//          unused): same slot arithmetic as 8-bit, a lane's operand (one MX
+//          block, 24 bytes) is units {4s+2g, 4s+2g+1}, read as two 12-byte reads.
+//   4-bit: a row is 64 bytes = 4 slots, slot c ^ ((r >> 1) & 3); a lane's
+//          operand is the single chunk 2s+g.
 // Scale bytes travel the same way, four K steps at a time: a row's scale bytes
 // for 512 elements are 16 consecutive bytes, so one 16-byte direct load per row
 // brings four steps' worth and touches its cache line once instead of four
@@ -33,6 +39,8 @@
 // a work-group that saw one recomputes its whole tile afterwards, 32 x 32 tile by
 // tile, with the exact cast of the direct kernel and in the same K order -- so the
 // result is bit-identical to mx_quantize followed by mx_gemm either way.
+#pragma once
+
 #include "mx_convert.hpp"
 #include "mx_gemm_frag.hpp"
 #include "mx_launch.hpp"
@@ -43,26 +51,64 @@ typedef int v8i_t __attribute__((ext_vector_type(8)));
 typedef float v16f_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int TM = 256, TN = 256, TK = 128;      // work-group tile (TK in elements = bytes for 8-bit formats)
-constexpr int TILE_BYTES = TM * TK;              // 32 KB per operand per stage
+typedef uint32_t u32x3_t __attribute__((ext_vector_type(3)));
+
+constexpr int TM = 256, TN = 256, TK = 128;      // work-group tile (TK in elements)
 constexpr int SCL_GROUP = 4;                     // K steps per scale group
 constexpr int SCL_BYTES = (TM + TN) * 4 * SCL_GROUP;   // one group: 16 scale bytes per row
 
-__host__ __device__ constexpr int hw_fmt8(int fmt) { return fmt == FP8_E4M3 ? 0 : 1; }
+// How an operand of element width W travels through LDS.
+template <int W> struct TileFmt;
+template <> struct TileFmt<8> { static constexpr int ROW = 128, UNIT = 16, RPI = 8; };   // LDS bytes per row, global bytes per
+template <> struct TileFmt<6> { static constexpr int ROW = 128, UNIT = 12, RPI = 8; };   // lane of a direct load, tile rows per
+template <> struct TileFmt<4> { static constexpr int ROW = 64, UNIT = 16, RPI = 16; };   // wave-wide direct load (1 KB of LDS)
 
-// LDS byte offset of 16-byte chunk c (0..7) of tile row r
-__device__ __forceinline__ int swz(int r, int c) { return r * TK + ((c ^ (r & 7)) << 4); }
+// LDS byte offset of 16-byte chunk c (0..7) of tile row r, 8-bit operand
+__device__ __forceinline__ int swz(int r, int c) { return r * 128 + ((c ^ (r & 7)) << 4); }
+
+// Byte offset, inside a tile of width W, of the first LDS slot lane (li, g) reads for sub-step 0 of
+// tile row r (a multiple of 32 rows further down only adds to it).
+template <int W>
+__device__ __forceinline__ int frag_ofs(int r, int g)
+{
+    if (W == 8) return r * 128 + ((g ^ (r & 7)) << 4);
+    if (W == 6) return r * 128 + (((2 * g) ^ (r & 7)) << 4);
+    return r * 64 + ((g ^ ((r >> 1) & 3)) << 4);
+}
+
+// One operand fragment: tile row block x (32 rows each), sub-step sub, from the tile at buf.
+template <int W>
+__device__ __forceinline__ v8i_t read_frag(const uint8_t *buf, int ofs0, int sub, int x)
+{
+    if constexpr (W == 8) {
+        const uint4 lo = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 6)) + x * 4096);
+        const uint4 hi = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 6) ^ 32) + x * 4096);
+        return v8i_t{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+    } else if constexpr (W == 6) {
+        const u32x3_t lo = *reinterpret_cast<const u32x3_t *>(buf + (ofs0 ^ (sub << 6)) + x * 4096);
+        const u32x3_t hi = *reinterpret_cast<const u32x3_t *>(buf + (ofs0 ^ (sub << 6) ^ 16) + x * 4096);
+        return v8i_t{(int)lo[0], (int)lo[1], (int)lo[2], (int)hi[0], (int)hi[1], (int)hi[2], 0, 0};
+    } else {
+        const uint4 lo = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 5)) + x * 2048);
+        return v8i_t{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, 0, 0, 0, 0};
+    }
+}
 
 template <int FA, int FB, int CDT, bool QA, int RND>
-__global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N, int64_t K,
+__global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N, int64_t K,
                                                             const uint8_t *__restrict__ Ae, const uint8_t *__restrict__ As,
                                                             const uint16_t *__restrict__ Abf, int64_t lda,
                                                             const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
                                                             void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n)
 {
+    constexpr int WA = Fmt<FA>::bits, WB = Fmt<FB>::bits;
+    static_assert(!QA || WA == 8, "the fused cast is written for 8-bit A operands");
+    typedef TileFmt<WA> TA;
+    typedef TileFmt<WB> TB;
+    constexpr int A_BYTES = TM * TA::ROW, B_BYTES = TN * TB::ROW, STAGE_BYTES = A_BYTES + B_BYTES;
     // {A tile, B tile} x two stages, then {A scale dwords, B scale dwords} x two stages
-    __shared__ __attribute__((aligned(16))) uint8_t lds[4 * TILE_BYTES + 2 * SCL_BYTES];
-    constexpr int HA = hw_fmt8(FA), HB = hw_fmt8(FB);
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * STAGE_BYTES + 2 * SCL_BYTES];
+    constexpr int HA = hw_fmt(FA), HB = hw_fmt(FB);   // must reach the builtin as literal constants
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int li = lane & 31, g = lane >> 5;
@@ -95,22 +141,22 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
     const int64_t nkb = K / BLOCK;
     const int T = (int)(K / TK);
 
-    // ---- staging map: one direct load of a wave fills 1 KB of LDS = 8 tile rows; wave w, load j
-    // covers rows (4j + w) * 8 .. + 7.  Lane l writes position l % 8 of row l / 8 of that group and
-    // therefore fetches chunk (l % 8) ^ (l / 8) of it.
-    const int st_r = wave * 8 + (lane >> 3), st_c = (lane & 7) ^ (lane >> 3);
-    const uint8_t *gA = Ae + (m0 + st_r) * K + st_c * 16;
-    const uint8_t *gB = Be + (n0 + st_r) * K + st_c * 16;
-    const int64_t g_step = 32 * K;                 // 32 rows further down
+    // ---- staging map: one direct load of a wave fills 1 KB of LDS = RPI tile rows; wave w, load j
+    // covers rows (4j + w) * RPI .. + RPI-1.  Lane l writes slot l % S of row l / S of that group
+    // (S slots per row) and therefore fetches the unit that the layout keeps in that slot.
+    const int a_r = WA == 4 ? lane >> 2 : lane >> 3, a_u = WA == 4 ? (lane & 3) ^ ((a_r >> 1) & 3) : (lane & 7) ^ a_r;
+    const int b_r = WB == 4 ? lane >> 2 : lane >> 3, b_u = WB == 4 ? (lane & 3) ^ ((b_r >> 1) & 3) : (lane & 7) ^ b_r;
+    const int64_t a_row_bytes = K * WA / 8, b_row_bytes = K * WB / 8;
+    const uint8_t *gA = QA ? nullptr : Ae + (m0 + wave * TA::RPI + a_r) * a_row_bytes + a_u * TA::UNIT;
+    const uint8_t *gB = Be + (n0 + wave * TB::RPI + b_r) * b_row_bytes + b_u * TB::UNIT;
     const int st_l = wave * 1024;                  // LDS offset of this wave's 1 KB slot within a 4 KB group
     // ---- scale staging: wave w fetches the dwords of rows 64w .. 64w+63 of A and of B
     const uint8_t *sA = As + (m0 + wave * 64 + lane) * nkb;
     const uint8_t *sB = Bs + (n0 + wave * 64 + lane) * nkb;
     // ---- scale reads: dword of tile row wm*128 + 32x + li (A) / wn*128 + 32y + li (B)
     const int rsa = (wm * 128 + li) * 16, rsb = TM * 16 + (wn * 128 + li) * 16;
-    // ---- operand read offsets inside a stage's tile: row tile x adds x * 4096, the second 16-byte
-    // chunk of a sub-step (chunk + 2) flips bit 5, sub-step 1 (chunk + 4) flips bit 6
-    const int ra0 = swz(wm * 128 + li, g), rb0 = swz(wn * 128 + li, g);
+    // ---- operand read offsets inside a stage's tile (sub-step 0, row block 0)
+    const int ra0 = frag_ofs<WA>(wm * 128 + li, g), rb0 = frag_ofs<WB>(wn * 128 + li, g);
 
     v16f_t acc[4][4];
 #pragma unroll
@@ -134,25 +180,32 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
     uint32_t sa[4], sb[4];   // scale dwords of the current stage, already shifted for this lane
     v8i_t a0[4], a1[4], b0[4], b1[4];   // operand fragments of sub-step 0 / 1, double-buffered in time
 
-    auto rd = [&](const uint8_t *buf, int ofs0, int sub, int x) -> v8i_t {
-        const uint4 lo = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 6)) + x * 4096);
-        const uint4 hi = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 6) ^ 32) + x * 4096);
-        return v8i_t{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-    };
     // Direct loads of one operand tile for K offset kofs into LDS tile dst.  Written as inline
     // assembly on purpose: the compiler makes every later LDS read wait for a direct load it knows
     // about (it cannot tell that the two stage buffers never overlap), which serialises the whole
     // pipeline.  Here the only consumer-side wait is the explicit vmcnt(0) before the barrier.
     // M0 carries the wave-uniform LDS destination; lane l lands at destination + 16 * l.
-    auto stage = [&](const uint8_t *gsrc, int64_t kofs, uint8_t *dst) {
+    auto stage_a = [&](int ts, uint8_t *dst) {
         const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
+        const uint8_t *gp0 = gA + (int64_t)ts * (TK * WA / 8);
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-            const uint8_t *gp = gsrc + kofs + j * g_step;
-            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
+        for (int j = 0; j < TM / (4 * TA::RPI); j++) {
+            const uint8_t *gp = gp0 + j * (4 * TA::RPI) * a_row_bytes;
+            if (WA == 6) asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx3 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
+            else asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
         }
     };
-    uint8_t *const scl = lds + 4 * TILE_BYTES;
+    auto stage_b = [&](int ts, uint8_t *dst) {
+        const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
+        const uint8_t *gp0 = gB + (int64_t)ts * (TK * WB / 8);
+#pragma unroll
+        for (int j = 0; j < TN / (4 * TB::RPI); j++) {
+            const uint8_t *gp = gp0 + j * (4 * TB::RPI) * b_row_bytes;
+            if (WB == 6) asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx3 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
+            else asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
+        }
+    };
+    uint8_t *const scl = lds + 2 * STAGE_BYTES;
     const int n_groups = T / SCL_GROUP;
     // scale bytes of K steps 4G .. 4G+3 (group G, clamped to the last) into slot G & 1: A rows, then B rows
     auto stage_scales = [&](int G) {
@@ -218,14 +271,14 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
         acc[x][Y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(AF[x], BF, acc[x][Y], HA, HB, OPS, (int)sa[x], OPS, (int)sb[Y])
 
     // ---- prologue: stage 0 and stage 1 on their way to LDS
-    stage(gB, 0, lds + TILE_BYTES);
+    stage_b(0, lds + A_BYTES);
     stage_scales(0);
     {
         const int t1 = T > 1 ? 1 : 0;
-        stage(gB, (int64_t)t1 * TK, lds + 3 * TILE_BYTES);
+        stage_b(t1, lds + STAGE_BYTES + A_BYTES);
         if (!QA) {
-            stage(gA, 0, lds);
-            stage(gA, (int64_t)t1 * TK, lds + 2 * TILE_BYTES);
+            stage_a(0, lds);
+            stage_a(t1, lds + STAGE_BYTES);
         } else {
 #pragma unroll
             for (int p = 0; p < 4; p++) qa_request(0, p);
@@ -238,7 +291,7 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // both stages have landed in LDS
     __syncthreads();
 #pragma unroll
-    for (int x = 0; x < 4; x++) { a0[x] = rd(lds, ra0, 0, x); b0[x] = rd(lds + TILE_BYTES, rb0, 0, x); }
+    for (int x = 0; x < 4; x++) { a0[x] = read_frag<WA>(lds, ra0, 0, x); b0[x] = read_frag<WB>(lds + A_BYTES, rb0, 0, x); }
     read_scales(0);
 
     // four K steps (one scale group) per trip, so that the scale request sits in a fixed place of
@@ -247,11 +300,10 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
 #pragma unroll
       for (int h = 0; h < SCL_GROUP; h++) {
         const int t = tt + h;
-        uint8_t *bufA = lds + (h & 1) * 2 * TILE_BYTES;
-        uint8_t *nxt = lds + ((h & 1) ^ 1) * 2 * TILE_BYTES;
-        uint8_t *bufB = bufA + TILE_BYTES;
+        uint8_t *bufA = lds + (h & 1) * STAGE_BYTES;
+        uint8_t *nxt = lds + ((h & 1) ^ 1) * STAGE_BYTES;
+        uint8_t *bufB = bufA + A_BYTES;
         const int t2 = t + 2 < T ? t + 2 : T - 1;
-        const int64_t kofs = (int64_t)t2 * TK;
         MX_FENCE();
 
         // ---- X: the 16 matrix instructions of sub-step 0; meanwhile all fragments of sub-step 1
@@ -259,19 +311,19 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
         // Quantize-on-load: the registers hold stage t+1 of A (requested half a step ago); one
         // pass per group is cast and written to the other buffer, whose last readers passed the
         // previous barrier.
-        a1[0] = rd(bufA, ra0, 1, 0); b1[0] = rd(bufB, rb0, 1, 0);
+        a1[0] = read_frag<WA>(bufA, ra0, 1, 0); b1[0] = read_frag<WB>(bufB, rb0, 1, 0);
         MX_MFMA4(a0, b0[0], 0, 0);
         if (QA) qa_commit(t + 1, 0, nxt);
         MX_FENCE();
-        a1[1] = rd(bufA, ra0, 1, 1); a1[2] = rd(bufA, ra0, 1, 2);
+        a1[1] = read_frag<WA>(bufA, ra0, 1, 1); a1[2] = read_frag<WA>(bufA, ra0, 1, 2);
         MX_MFMA4(a0, b0[1], 1, 0);
         if (QA) qa_commit(t + 1, 1, nxt);
         MX_FENCE();
-        a1[3] = rd(bufA, ra0, 1, 3); b1[1] = rd(bufB, rb0, 1, 1);
+        a1[3] = read_frag<WA>(bufA, ra0, 1, 3); b1[1] = read_frag<WB>(bufB, rb0, 1, 1);
         MX_MFMA4(a0, b0[2], 2, 0);
         if (QA) qa_commit(t + 1, 2, nxt);
         MX_FENCE();
-        b1[2] = rd(bufB, rb0, 1, 2); b1[3] = rd(bufB, rb0, 1, 3);
+        b1[2] = read_frag<WB>(bufB, rb0, 1, 2); b1[3] = read_frag<WB>(bufB, rb0, 1, 3);
         MX_MFMA4(a0, b0[3], 3, 0);
         if (QA) qa_commit(t + 1, 3, nxt);
         MX_FENCE();
@@ -283,21 +335,21 @@ __global__ __launch_bounds__(256, 1) void gemm8_tile_kernel(int64_t M, int64_t N
 
         // ---- Y: the 16 matrix instructions of sub-step 1; meanwhile stage t+2 is requested into
         // the buffer stage t just vacated and the sub-step-0 fragments of stage t+1 are read
-        if (!QA) stage(gA, kofs, bufA);
+        if (!QA) stage_a(t2, bufA);
         else { qa_request(t + 2, 0); qa_request(t + 2, 1); }
-        a0[0] = rd(nxt, ra0, 0, 0); b0[0] = rd(nxt + TILE_BYTES, rb0, 0, 0);
+        a0[0] = read_frag<WA>(nxt, ra0, 0, 0); b0[0] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 0);
         MX_MFMA4(a1, b1[0], 0, 2);
         MX_FENCE();
         if (QA) { qa_request(t + 2, 2); qa_request(t + 2, 3); }
-        stage(gB, kofs, bufB);
-        a0[1] = rd(nxt, ra0, 0, 1); a0[2] = rd(nxt, ra0, 0, 2);
+        stage_b(t2, bufB);
+        a0[1] = read_frag<WA>(nxt, ra0, 0, 1); a0[2] = read_frag<WA>(nxt, ra0, 0, 2);
         MX_MFMA4(a1, b1[1], 1, 2);
         MX_FENCE();
         if (h == 0) stage_scales(tt / SCL_GROUP + 1);   // next group, once every four steps
-        a0[3] = rd(nxt, ra0, 0, 3); b0[1] = rd(nxt + TILE_BYTES, rb0, 0, 1);
+        a0[3] = read_frag<WA>(nxt, ra0, 0, 3); b0[1] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 1);
         MX_MFMA4(a1, b1[2], 2, 2);
         MX_FENCE();
-        b0[2] = rd(nxt + TILE_BYTES, rb0, 0, 2); b0[3] = rd(nxt + TILE_BYTES, rb0, 0, 3);
+        b0[2] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 2); b0[3] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 3);
         MX_MFMA4(a1, b1[3], 3, 2);
         MX_FENCE();
         read_scales(t + 1);   // for the next step; the matrix instructions above already hold theirs
@@ -336,7 +388,7 @@ template <int FA, int FB, int CDT, bool QA, int RND>
 static hipError_t launch_t(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint16_t *Abf,
                            int64_t lda, const uint8_t *Be, const uint8_t *Bs, void *C, int64_t ldc, hipStream_t st)
 {
-    auto kern = gemm8_tile_kernel<FA, FB, CDT, QA, RND>;
+    auto kern = gemm_tile_kernel<FA, FB, CDT, QA, RND>;
     const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
     const int per_xcd = (tiles_m * tiles_n + 7) / 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, M, N, K, Ae, As, Abf, lda, Be, Bs, C, ldc,
@@ -344,42 +396,52 @@ static hipError_t launch_t(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, c
     return hipGetLastError();
 }
 
+// Arguments of a tiled launch (Abf != nullptr: A is raw bf16, cast inside the kernel).
+struct TileArgs {
+    int64_t M, N, K;
+    const uint8_t *Ae, *As;
+    const uint16_t *Abf;
+    int64_t lda;
+    int rnd;
+    const uint8_t *Be, *Bs;
+    void *C;
+    int c_dt;
+    int64_t ldc;
+    hipStream_t st;
+};
+
 template <int FA, int FB>
-static hipError_t launch_mode(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint16_t *Abf,
-                              int64_t lda, int rnd, const uint8_t *Be, const uint8_t *Bs, void *C, int c_dt, int64_t ldc,
-                              hipStream_t st)
+static hipError_t launch_pair(const TileArgs &a)
 {
-#define MX_GO(QA_, RND_)                                                                                           \
-    (c_dt == DT_F32 ? launch_t<FA, FB, DT_F32, QA_, RND_>(M, N, K, Ae, As, Abf, lda, Be, Bs, C, ldc, st)            \
-                    : launch_t<FA, FB, DT_BF16, QA_, RND_>(M, N, K, Ae, As, Abf, lda, Be, Bs, C, ldc, st))
-    if (!Abf) return MX_GO(false, ROUND_RNE);
-    return rnd == ROUND_RNE ? MX_GO(true, ROUND_RNE) : MX_GO(true, ROUND_HALF_AWAY);
+#define MX_GO(QA_, RND_)                                                                                                  \
+    (a.c_dt == DT_F32 ? launch_t<FA, FB, DT_F32, QA_, RND_>(a.M, a.N, a.K, a.Ae, a.As, a.Abf, a.lda, a.Be, a.Bs, a.C, a.ldc, a.st) \
+                      : launch_t<FA, FB, DT_BF16, QA_, RND_>(a.M, a.N, a.K, a.Ae, a.As, a.Abf, a.lda, a.Be, a.Bs, a.C, a.ldc, a.st))
+    if (!a.Abf) return MX_GO(false, ROUND_RNE);
+    // the fused cast exists for 8-bit pairs only
+    if constexpr (Fmt<FA>::bits == 8 && Fmt<FB>::bits == 8)
+        return a.rnd == ROUND_RNE ? MX_GO(true, ROUND_RNE) : MX_GO(true, ROUND_HALF_AWAY);
+    else
+        return hipErrorNotSupported;
 #undef MX_GO
 }
 
-bool gemm_tiled_applies(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB)
+// all B formats for one A format
+template <int FA>
+static hipError_t launch_a(const TileArgs &a, int fmtB)
 {
-    const bool a8 = fmtA == FP8_E4M3 || fmtA == FP8_E5M2, b8 = fmtB == FP8_E4M3 || fmtB == FP8_E5M2;
-    return a8 && b8 && M % TM == 0 && N % TN == 0 && K % (TK * SCL_GROUP) == 0 && K > 0 && M > 0 && N > 0 &&
-           (M / TM) * (N / TN) <= (1 << 24);
+    switch (fmtB) {
+        case FP8_E4M3: return launch_pair<FA, FP8_E4M3>(a);
+        case FP8_E5M2: return launch_pair<FA, FP8_E5M2>(a);
+        case FP6_E3M2: return launch_pair<FA, FP6_E3M2>(a);
+        case FP6_E2M3: return launch_pair<FA, FP6_E2M3>(a);
+        case FP4_E2M1: return launch_pair<FA, FP4_E2M1>(a);
+        default:       return hipErrorNotSupported;
+    }
 }
 
-// Tiled path for 8-bit x 8-bit operands on full tiles (a_bf16 != nullptr: A cast on load);
-// hipErrorNotSupported otherwise.
-hipError_t launch_gemm_tiled(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const void *a_bf16,
-                             int64_t lda, int rnd, int fmtA, const uint8_t *Be, const uint8_t *Bs, int fmtB, void *C,
-                             int c_dt, int64_t ldc, hipStream_t st)
-{
-    if (!gemm_tiled_applies(M, N, K, fmtA, fmtB)) return hipErrorNotSupported;
-    const uint16_t *Abf = static_cast<const uint16_t *>(a_bf16);
-#define MX_CASE(FA_, FB_)                                                                                          \
-    if (fmtA == FA_ && fmtB == FB_) return launch_mode<FA_, FB_>(M, N, K, Ae, As, Abf, lda, rnd, Be, Bs, C, c_dt, ldc, st);
-    MX_CASE(FP8_E4M3, FP8_E4M3)
-    MX_CASE(FP8_E4M3, FP8_E5M2)
-    MX_CASE(FP8_E5M2, FP8_E4M3)
-    MX_CASE(FP8_E5M2, FP8_E5M2)
-#undef MX_CASE
-    return hipErrorNotSupported;
-}
+// one translation unit per A element width (the instantiations are many and compile in parallel)
+hipError_t launch_gemm_tiled_a8(const TileArgs &a, int fmtA, int fmtB);
+hipError_t launch_gemm_tiled_a6(const TileArgs &a, int fmtA, int fmtB);
+hipError_t launch_gemm_tiled_a4(const TileArgs &a, int fmtA, int fmtB);
 
 }  // namespace mx

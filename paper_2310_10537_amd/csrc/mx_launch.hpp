@@ -22,12 +22,14 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
                        const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
                        const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st);
 
-// true when launch_gemm_tiled takes the problem
+// true when the LDS-tiled kernel takes the problem: FP8 / FP6 / FP4 operands, whole 256 x 256
+// tiles, K a multiple of 512
 bool gemm_tiled_applies(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
+// true when the tiled kernel can cast a bf16 A operand inside its K loop (8-bit pairs)
+bool gemm_tiled_fuses_cast(int fmtA, int fmtB);
 
-// LDS-tiled kernel for 8-bit operands on whole 256 x 256 tiles with K a multiple of 512
-// (a_bf16 != nullptr: A is raw bf16 and cast on load); hipErrorNotSupported when the problem
-// does not qualify.
+// LDS-tiled kernel (a_bf16 != nullptr: A is raw bf16 and cast on load); hipErrorNotSupported
+// when the problem does not qualify.
 hipError_t launch_gemm_tiled(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const void *a_bf16,
                              int64_t lda, int rnd, int fmtA, const uint8_t *Be, const uint8_t *Bs, int fmtB, void *C,
                              int c_dt, int64_t ldc, hipStream_t st);

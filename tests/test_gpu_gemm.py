@@ -158,6 +158,45 @@ def test_tiled_kernel_full_tiles(mx, oracle, fa, fb, shape, dt):
     check_gemm(got, C_ref, C_abs, str(shape), hw_term_for(oracle, ea, sa, fa, eb, sb, fb, K))
 
 
+@pytest.mark.parametrize("fa", range(5), ids=NAMES)
+@pytest.mark.parametrize("fb", range(5), ids=NAMES)
+@pytest.mark.parametrize("shape,dt", [((256, 512, 1536), torch.float32), ((512, 256, 512), torch.bfloat16)])
+def test_tiled_kernel_all_format_pairs(mx, oracle, fa, fb, shape, dt):
+    """Every FP8 / FP6 / FP4 pair on whole tiles: each element width has its own LDS layout and
+    direct-load shape, so every (row, K block) must come back from the right slot.  Per-block
+    scales differ widely, and the exactly representable pairs are held to the plain 1e-5 bound."""
+    M, N, K = shape
+    rng = np.random.default_rng(M + N + 5 * fa + fb)
+    a = inputs.student_t_f32((M, K), seed=fa + 80) * np.exp2(rng.integers(-6, 6, (M, K // 32))).repeat(32, axis=1).astype(np.float32)
+    b = inputs.gaussian_f32((N, K), seed=fb + 90, std=0.02) * np.exp2(rng.integers(-6, 6, (N, K // 32))).repeat(32, axis=1).astype(np.float32)
+    ea, sa = oracle.quantize(a, 1, fa)
+    eb, sb = oracle.quantize(b, 1, fb)
+    C_ref, C_abs = oracle.gemm(ea, sa, fa, eb, sb, fb, K, want_abs=True)
+    C = mx.mx_gemm(to_dev(ea), to_dev(sa), fa, to_dev(eb), to_dev(sb), fb, K, dtype=dt)
+    got = to_host(C)
+    if dt == torch.bfloat16:
+        got = bf16_bits_to_f64(got)
+        C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5     # half a bf16 ulp of the result on top of the bound
+    check_gemm(got, C_ref, C_abs, f"{NAMES[fa]}x{NAMES[fb]} {shape}", hw_term_for(oracle, ea, sa, fa, eb, sb, fb, K))
+
+
+@pytest.mark.parametrize("fa,fb", [(2, 2), (3, 4), (4, 0), (1, 3)], ids=["e3m2xe3m2", "e2m3xe2m1", "e2m1xe4m3", "e5m2xe2m3"])
+def test_tiled_kernel_one_hot_rows(mx, oracle, fa, fb):
+    """A is one-hot per row (element k = m mod K is 1.0, scale byte 127): C[m][n] must reproduce
+    B[n][m mod K] exactly, which pins the K position of every element of every LDS slot."""
+    M, N, K = 512, 256, 512
+    a = np.zeros((M, K), np.float32)
+    a[np.arange(M), np.arange(M) % K] = 1.0
+    b = inputs.gaussian_f32((N, K), seed=95, std=1.0)
+    ea, sa = oracle.quantize(a, 1, fa)
+    eb, sb = oracle.quantize(b, 1, fb)
+    Bd = oracle.dequantize(eb, sb, fb, N, K, 1)
+    C = to_host(mx.mx_gemm(to_dev(ea), to_dev(sa), fa, to_dev(eb), to_dev(sb), fb, K))
+    Ad = oracle.dequantize(ea, sa, fa, M, K, 1)
+    expect = (Ad[np.arange(M), np.arange(M) % K][:, None] * Bd[:, np.arange(M) % K].T).astype(np.float32)
+    assert np.array_equal(C, expect)
+
+
 def test_exact_integer_products(mx, oracle):
     """Integer-valued FP4 operands at X = 1: every partial sum is an integer below
     2^24, so Float32 accumulation is exact and the result must equal the
