@@ -185,25 +185,33 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     // about (it cannot tell that the two stage buffers never overlap), which serialises the whole
     // pipeline.  Here the only consumer-side wait is the explicit vmcnt(0) before the barrier.
     // M0 carries the wave-uniform LDS destination; lane l lands at destination + 16 * l.
-    auto stage_a = [&](int ts, uint8_t *dst) {
+    constexpr int NJA = QA ? 0 : TM / (4 * TA::RPI), NJB = TN / (4 * TB::RPI);   // direct loads per wave per stage
+    auto stage_a1 = [&](int ts, uint8_t *dst, int j) {
         const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
-        const uint8_t *gp0 = gA + (int64_t)ts * (TK * WA / 8);
+        const uint8_t *gp = gA + (int64_t)ts * (TK * WA / 8) + j * (4 * TA::RPI) * a_row_bytes;
+        if (WA == 6) asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx3 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
+        else asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
+    };
+    auto stage_b1 = [&](int ts, uint8_t *dst, int j) {
+        const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
+        const uint8_t *gp = gB + (int64_t)ts * (TK * WB / 8) + j * (4 * TB::RPI) * b_row_bytes;
+        if (WB == 6) asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx3 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
+        else asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
+    };
+    auto stage_a = [&](int ts, uint8_t *dst) {
 #pragma unroll
-        for (int j = 0; j < TM / (4 * TA::RPI); j++) {
-            const uint8_t *gp = gp0 + j * (4 * TA::RPI) * a_row_bytes;
-            if (WA == 6) asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx3 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
-            else asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
-        }
+        for (int j = 0; j < NJA; j++) stage_a1(ts, dst, j);
     };
     auto stage_b = [&](int ts, uint8_t *dst) {
-        const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
-        const uint8_t *gp0 = gB + (int64_t)ts * (TK * WB / 8);
 #pragma unroll
-        for (int j = 0; j < TN / (4 * TB::RPI); j++) {
-            const uint8_t *gp = gp0 + j * (4 * TB::RPI) * b_row_bytes;
-            if (WB == 6) asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx3 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
-            else asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
-        }
+        for (int j = 0; j < NJB; j++) stage_b1(ts, dst, j);
+    };
+    // direct load number k of a stage (A's first, then B's), one per matrix instruction of the
+    // second half of a step: a burst of them would fill the memory pipeline's queue and stall the
+    // wave -- in-order issue -- in front of its next matrix instruction
+    auto stage_one = [&](int k, int ts, uint8_t *dstA, uint8_t *dstB) {
+        if (k < NJA) stage_a1(ts, dstA, k);
+        else if (k - NJA < NJB) stage_b1(ts, dstB, k - NJA);
     };
     uint8_t *const scl = lds + 2 * STAGE_BYTES;
     const int n_groups = T / SCL_GROUP;
@@ -266,6 +274,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
         }
     };
 #define MX_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define MX_MFMA1(AF, BF, X, Y, OPS)                                                                                   \
+    acc[X][Y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(AF[X], BF, acc[X][Y], HA, HB, OPS, (int)sa[X], OPS, (int)sb[Y])
 #define MX_MFMA4(AF, BF, Y, OPS)                                                                                      \
     _Pragma("unroll") for (int x = 0; x < 4; x++)                                                                     \
         acc[x][Y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(AF[x], BF, acc[x][Y], HA, HB, OPS, (int)sa[x], OPS, (int)sb[Y])
@@ -335,28 +345,28 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
 
         // ---- Y: the 16 matrix instructions of sub-step 1; meanwhile stage t+2 is requested into
         // the buffer stage t just vacated and the sub-step-0 fragments of stage t+1 are read
-        if (!QA) stage_a(t2, bufA);
-        else { qa_request(t + 2, 0); qa_request(t + 2, 1); }
-        a0[0] = read_frag<WA>(nxt, ra0, 0, 0); b0[0] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 0);
-        MX_MFMA4(a1, b1[0], 0, 2);
-        MX_FENCE();
+#define MX_Y_GROUP(GRP, READ0, READ1, BF, Y)                                                                             \
+    stage_one(4 * GRP + 0, t2, bufA, bufB); READ0; MX_MFMA1(a1, BF, 0, Y, 2); MX_FENCE();                                   \
+    stage_one(4 * GRP + 1, t2, bufA, bufB);        MX_MFMA1(a1, BF, 1, Y, 2); MX_FENCE();                                   \
+    stage_one(4 * GRP + 2, t2, bufA, bufB); READ1; MX_MFMA1(a1, BF, 2, Y, 2); MX_FENCE();                                   \
+    stage_one(4 * GRP + 3, t2, bufA, bufB);        MX_MFMA1(a1, BF, 3, Y, 2); MX_FENCE()
+        if (QA) { qa_request(t + 2, 0); qa_request(t + 2, 1); }
+        MX_Y_GROUP(0, a0[0] = read_frag<WA>(nxt, ra0, 0, 0), b0[0] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 0), b1[0], 0);
         if (QA) { qa_request(t + 2, 2); qa_request(t + 2, 3); }
-        stage_b(t2, bufB);
-        a0[1] = read_frag<WA>(nxt, ra0, 0, 1); a0[2] = read_frag<WA>(nxt, ra0, 0, 2);
-        MX_MFMA4(a1, b1[1], 1, 2);
-        MX_FENCE();
+        MX_Y_GROUP(1, a0[1] = read_frag<WA>(nxt, ra0, 0, 1), a0[2] = read_frag<WA>(nxt, ra0, 0, 2), b1[1], 1);
         if (h == 0) stage_scales(tt / SCL_GROUP + 1);   // next group, once every four steps
-        a0[3] = read_frag<WA>(nxt, ra0, 0, 3); b0[1] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 1);
-        MX_MFMA4(a1, b1[2], 2, 2);
-        MX_FENCE();
-        b0[2] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 2); b0[3] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 3);
-        MX_MFMA4(a1, b1[3], 3, 2);
-        MX_FENCE();
+        MX_Y_GROUP(2, a0[3] = read_frag<WA>(nxt, ra0, 0, 3), b0[1] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 1), b1[2], 2);
+        MX_Y_GROUP(3, b0[2] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 2), b0[3] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 3), b1[3], 3);
+#undef MX_Y_GROUP
         read_scales(t + 1);   // for the next step; the matrix instructions above already hold theirs
         MX_FENCE();
       }
     }
 #undef MX_MFMA4
+#undef MX_MFMA1
+    // every direct load (the last, clamped, stages included) must have landed before this
+    // work-group's LDS can be handed to another one
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #undef MX_FENCE
 
     // ---- quantize-on-load: exact recomputation of the tile if any block needed the exact cast

@@ -362,3 +362,69 @@ def test_config3_sampled(mx, oracle):
     B = (to_host(gb[0]), to_host(gb[1]))
     got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, (ea, sa), 0, B, 0, K, seed=3)
     check_gemm(got, C_ref, C_abs, "config3", hw)
+
+
+def test_config3_wide_sampled(mx, oracle):
+    """The second projection of the transformer workload: N = 11008 (43 tile columns), cast on load."""
+    M, K, N = 8192, 4096, 11008
+    a = inputs.gaussian_bf16((M, K), seed=2)
+    w = inputs.gaussian_f32((K, N), seed=112, std=0.02)
+    gb = mx.mx_quantize(to_dev(w), 0, 0)
+    C = mx.mx_gemm_qa(to_dev(a), 0, RNE, gb[0], gb[1], 0, dtype=torch.bfloat16)
+    ea, sa = oracle.quantize(a, 1, 0)
+    B = (to_host(gb[0]), to_host(gb[1]))
+    got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, (ea, sa), 0, B, 0, K, seed=5)
+    C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5     # bf16 output: half an ulp of the result on top
+    check_gemm(got, C_ref, C_abs, "config3 N=11008", hw)
+
+
+def cast_sample_matches(oracle, src, axis, fmt, rnd, gpu, lo, hi):
+    """GPU cast of a whole tensor against the reference on rows (axis 1) or columns (axis 0) lo..hi."""
+    part = np.ascontiguousarray(src[lo:hi] if axis == 1 else src[:, lo:hi])
+    e, s = oracle.quantize(part, axis, fmt, rnd)
+    return np.array_equal(to_host(gpu[0][lo:hi]), e) and np.array_equal(to_host(gpu[1][lo:hi]), s)
+
+
+def test_config4_sampled(mx, oracle):
+    """Mixed-format inference GEMM: MXFP6 E3M2 Student-t activations [4096, 8192] x MXFP4 E2M1
+    N(0, 0.02) weights of logical shape 8192 x 28672 (cast along dim 0, stored [28672][8192]),
+    bf16 output.  Casts checked on slices, the product on sampled entries."""
+    M, K, N = 4096, 8192, 28672
+    act = inputs.student_t_bf16((M, K), seed=3)
+    w = inputs.gaussian_f32((K, N), seed=103, std=0.02)
+    ga = mx.mx_quantize(to_dev(act), 1, 2)
+    gb = mx.mx_quantize(to_dev(w), 0, 4)
+    assert cast_sample_matches(oracle, act, 1, 2, RNE, ga, 1000, 1256)
+    assert cast_sample_matches(oracle, w, 0, 4, RNE, gb, 28672 - 256, 28672)
+    C = mx.mx_gemm(ga[0], ga[1], 2, gb[0], gb[1], 4, K, dtype=torch.bfloat16)
+    del w
+    A = (to_host(ga[0]), to_host(ga[1]))
+    B = (to_host(gb[0]), to_host(gb[1]))
+    got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, A, 2, B, 4, K, seed=6)
+    C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5
+    check_gemm(got, C_ref, C_abs, "config4", hw)
+
+
+@pytest.mark.parametrize("rnd", [RNE, AWAY], ids=["rne", "away"])
+def test_config5_sampled(mx, oracle, rnd):
+    """MXFP6 E3M2 training-step triple of a GPT-style MLP layer (hidden 2048, ffn 8192, 16384
+    tokens): forward X.W, dgrad dY.W^T, wgrad X^T.dY, every operand cast with its blocks along
+    that GEMM's K axis (axis-0 casts for the transposed uses)."""
+    T, H, F = 16384, 2048, 8192
+    X = inputs.gaussian_bf16((T, H), seed=4)
+    W = inputs.gaussian_bf16((H, F), seed=104, std=0.02)
+    dY = inputs.gaussian_bf16((T, F), seed=204)
+    Xd, Wd, dYd = to_dev(X), to_dev(W), to_dev(dY)
+    fmt = 2
+    X1, X0 = mx.mx_quantize(Xd, 1, fmt, rnd), mx.mx_quantize(Xd, 0, fmt, rnd)        # [T][H], [H][T]
+    W1, W0 = mx.mx_quantize(Wd, 1, fmt, rnd), mx.mx_quantize(Wd, 0, fmt, rnd)        # [H][F], [F][H]
+    Y1, Y0 = mx.mx_quantize(dYd, 1, fmt, rnd), mx.mx_quantize(dYd, 0, fmt, rnd)      # [T][F], [F][T]
+    assert cast_sample_matches(oracle, X, 1, fmt, rnd, X1, 0, 512) and cast_sample_matches(oracle, X, 0, fmt, rnd, X0, 1024, 1536)
+    assert cast_sample_matches(oracle, W, 1, fmt, rnd, W1, 0, 2048) and cast_sample_matches(oracle, W, 0, fmt, rnd, W0, 0, 8192)
+    assert cast_sample_matches(oracle, dY, 1, fmt, rnd, Y1, 16000, 16384) and cast_sample_matches(oracle, dY, 0, fmt, rnd, Y0, 4096, 4352)
+    h = lambda g: (to_host(g[0]), to_host(g[1]))
+    for name, A, B, K in (("fwd", X1, W0, H), ("dgrad", Y1, W1, F), ("wgrad", X0, Y0, T)):
+        C = mx.mx_gemm(A[0], A[1], fmt, B[0], B[1], fmt, K, dtype=torch.float32)
+        got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, h(A), fmt, h(B), fmt, K, seed=7, n=1024)
+        check_gemm(got, C_ref, C_abs, f"config5 {name}", hw)
+        del C
