@@ -19,6 +19,11 @@ back on the stream it runs on, between two events, with the same buffer rotation
 The headline value is the cast throughput (algorithmic bytes of the 12 casts
 divided by their summed average durations); GEMM TFLOP/s are reported beside it.
 
+With --all-configs the other full-size workloads are timed as well (per call, same protocol)
+and reported under "other_configs": the 4096 x 11008 projection of config 3, the mixed-format
+inference GEMM of config 4 with its two casts, and the MXFP6 training triple of config 5 (six
+casts, three GEMMs).  They are not part of the step or of the headline value.
+
 Prints ONE JSON line.
 """
 import argparse
@@ -118,12 +123,91 @@ def cpu_baseline(x_bits):
                       "of the 8192x8192 bf16 workload tensor; %.1f s" % dt}
 
 
+def time_call(fn, n):
+    """Average duration in ms of n back-to-back launches of fn (after 2 warm-up launches)."""
+    fn()
+    fn()
+    a = torch.cuda.Event(enable_timing=True)
+    b = torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(n):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / n
+
+
+def other_configs(n):
+    """Configs 3 (wide projection), 4 and 5 at full size; returns a dict of per-call results."""
+    out = {}
+
+    def gemm_entry(label, M, N, K, ms, bits):
+        tf = 2.0 * M * N * K / ms / 1e9
+        out[label] = {"avg_ms": round(ms, 5), "TFLOPs": round(tf, 1), "frac_mfma_peak": round(tf / MFMA_PEAK_TFLOPS[bits], 4)}
+
+    def cast_entry(label, n_elem, src_bytes, fmt, ms):
+        b = n_elem * (src_bytes + mx.FORMAT_BITS[fmt] / 8.0 + 1.0 / 32.0)
+        out[label] = {"avg_ms": round(ms, 5), "GBps": round(b / ms / 1e6, 1)}
+
+    # config 3, second projection: 8192 x 11008 x 4096, E4M3, A cast on load
+    M, K, N = 8192, 4096, 11008
+    a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=2))
+    w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=112, std=0.02)).cuda()
+    Be, Bs = mx.mx_quantize(w, 0, mx.FP8_E4M3)
+    Ae, As = mx.mx_quantize(a, 1, mx.FP8_E4M3)
+    C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    gemm_entry("cfg3_gemm_8192x11008x4096_e4m3", M, N, K,
+               time_call(lambda: mx.mx_gemm(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, out=C), n), 8)
+    gemm_entry("cfg3_gemm_qa_8192x11008x4096_e4m3", M, N, K,
+               time_call(lambda: mx.mx_gemm_qa(a, mx.FP8_E4M3, mx.ROUND_RNE, Be, Bs, mx.FP8_E4M3, out=C), n), 8)
+    del a, w, Be, Bs, Ae, As, C
+
+    # config 4: E3M2 activations [4096, 8192] x E2M1 weights (logical 8192 x 28672)
+    M, K, N = 4096, 8192, 28672
+    act = to_dev_bf16(inputs.student_t_bf16((M, K), seed=3))
+    w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=103, std=0.02)).cuda()
+    ga = mx.mx_quantize(act, 1, mx.FP6_E3M2)
+    gb = mx.mx_quantize(w, 0, mx.FP4_E2M1)
+    cast_entry("cfg4_cast_act_e3m2_axis1", M * K, 2, mx.FP6_E3M2,
+               time_call(lambda: mx.mx_quantize(act, 1, mx.FP6_E3M2, mx.ROUND_RNE, ga[0], ga[1]), n))
+    cast_entry("cfg4_cast_w_f32_e2m1_axis0", K * N, 4, mx.FP4_E2M1,
+               time_call(lambda: mx.mx_quantize(w, 0, mx.FP4_E2M1, mx.ROUND_RNE, gb[0], gb[1]), n))
+    C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    gemm_entry("cfg4_gemm_4096x28672x8192_e3m2_e2m1", M, N, K,
+               time_call(lambda: mx.mx_gemm(ga[0], ga[1], mx.FP6_E3M2, gb[0], gb[1], mx.FP4_E2M1, K, out=C), n), 6)
+    del act, w, ga, gb, C
+
+    # config 5: E3M2 training triple, half-away rounding; T tokens, hidden H, ffn F
+    T, H, F = 16384, 2048, 8192
+    fmt, rnd = mx.FP6_E3M2, mx.ROUND_HALF_AWAY
+    X = to_dev_bf16(inputs.gaussian_bf16((T, H), seed=4))
+    W = to_dev_bf16(inputs.gaussian_bf16((H, F), seed=104, std=0.02))
+    dY = to_dev_bf16(inputs.gaussian_bf16((T, F), seed=204))
+    q = {}
+    for name, t, axis in (("X_axis1", X, 1), ("W_axis0", W, 0), ("dY_axis1", dY, 1), ("W_axis1", W, 1),
+                          ("X_axis0", X, 0), ("dY_axis0", dY, 0)):
+        q[name] = mx.mx_quantize(t, axis, fmt, rnd)
+        e, s = q[name]
+        cast_entry("cfg5_cast_" + name, t.numel(), 2, fmt, time_call(lambda: mx.mx_quantize(t, axis, fmt, rnd, e, s), n))
+    total = sum(out[k]["avg_ms"] for k in out if k.startswith("cfg5_cast_"))
+    for name, A, B, (M, N, K) in (("fwd", q["X_axis1"], q["W_axis0"], (T, F, H)), ("dgrad", q["dY_axis1"], q["W_axis1"], (T, H, F)),
+                                  ("wgrad", q["X_axis0"], q["dY_axis0"], (H, F, T))):
+        C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        ms = time_call(lambda: mx.mx_gemm(A[0], A[1], fmt, B[0], B[1], fmt, K, out=C), n)
+        gemm_entry(f"cfg5_gemm_{name}_{M}x{N}x{K}_e3m2", M, N, K, ms, 6)
+        total += ms
+        del C
+    out["cfg5_triple_total_ms"] = round(total, 5)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-configs", action="store_true", help="also time configs 3 (wide), 4 and 5 per call")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (no collectives exist in the MX hot path); "
@@ -265,6 +349,10 @@ def main():
         "roofline_slowest_cast": cast_roof(slowest_cast),
         "kernels": per_kernel,
     }
+    if args.all_configs:
+        del xs, As, Aq, Cs, outs, deq_out, deq_in
+        torch.cuda.empty_cache()
+        line["other_configs"] = other_configs(args.steps)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(x_bits)
     print(json.dumps(line))
