@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
     const int64_t col = c0 + c;
     const int64_t row_blk = r0 / BLOCK + rb;
     const int64_t n_rb = rows / BLOCK;
-    if (col >= cols || row_blk >= n_rb) return;
+    const bool valid = col < cols && row_blk < n_rb;
     const uint8_t *colp = tile + rb * 32 * 128 + ((c * 2 + rb * 32) & 127);
     uint32_t d[16];
 #pragma unroll
@@ -228,6 +228,11 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
     }
     uint32_t out[w];
     const uint32_t s = quantize_block_bf16<FMT, RND>(d, out);
+    // the four lanes of a column hold its four consecutive scale bytes: one dword store when
+    // the whole quad is valid and the address is aligned, else byte stores
+    const uint32_t s4 = s | ((uint32_t)__shfl_down((int)s, 1) << 8) | ((uint32_t)__shfl_down((int)s, 2) << 16) |
+                        ((uint32_t)__shfl_down((int)s, 3) << 24);
+    if (!valid) return;
     uint8_t *o = elems + (col * n_rb + row_blk) * (BLOCK * w / 8);
     if constexpr (w == 8) {
         st16(o, make_uint4(out[0], out[1], out[2], out[3]));
@@ -239,7 +244,12 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
     } else {
         st16(o, make_uint4(out[0], out[1], out[2], out[3]));
     }
-    scales[col * n_rb + row_blk] = (uint8_t)s;
+    const bool quad = (n_rb & 3) == 0 && r0 / BLOCK + 4 <= n_rb;   // uniform over the work-group
+    if (quad) {
+        if (rb == 0) *reinterpret_cast<uint32_t *>(scales + col * n_rb + row_blk) = s4;
+    } else {
+        scales[col * n_rb + row_blk] = (uint8_t)s;
+    }
 }
 
 // ---------------------------------------------------------------------------

@@ -206,6 +206,47 @@ __device__ __forceinline__ void widen_bf16(const uint32_t (&d)[ND], uint32_t (&v
     }
 }
 
+// Exact integer path for a whole block held by one lane as 16 packed bf16 dwords, written to
+// need few registers (it sits in kernels whose occupancy matters and runs for rare blocks only):
+// the encode loop is rolled, always works on dword 0 and rotates the 16 source registers by one
+// place per trip, and shifts each pair of codes into the top of a w-dword shift register, so no
+// register is ever indexed by the loop counter.
+template <int FMT, int RND>
+__device__ __forceinline__ uint32_t quantize_block_bf16_exact(const uint32_t (&d)[16], uint32_t *packed)
+{
+    constexpr int w = Fmt<FMT>::bits;
+    uint32_t amax = 0;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        const uint32_t k0 = amax_key<FMT>(d[i] << 16), k1 = amax_key<FMT>(d[i] & 0xFFFF0000u);
+        amax = amax > k0 ? amax : k0;
+        amax = amax > k1 ? amax : k1;
+    }
+    const uint32_t s = scale_byte<FMT>(amax);
+    const bool nan_block = !Fmt<FMT>::elem_nan && s == SCALE_NAN;
+    uint32_t r[16], o[w];
+#pragma unroll
+    for (int i = 0; i < 16; i++) r[i] = d[i];
+#pragma unroll
+    for (int i = 0; i < w; i++) o[i] = 0;
+#pragma unroll 1
+    for (int it = 0; it < 16; it++) {
+        const uint32_t c0 = nan_block ? 0u : encode_elem<FMT, RND>(r[0] << 16, s);
+        const uint32_t c1 = nan_block ? 0u : encode_elem<FMT, RND>(r[0] & 0xFFFF0000u, s);
+        const uint32_t pair = c0 | (c1 << w);                       // 2w bits
+#pragma unroll
+        for (int j = 0; j < w - 1; j++) o[j] = (o[j] >> (2 * w)) | (o[j + 1] << (32 - 2 * w));
+        o[w - 1] = (o[w - 1] >> (2 * w)) | (pair << (32 - 2 * w));
+        const uint32_t first = r[0];
+#pragma unroll
+        for (int j = 0; j < 15; j++) r[j] = r[j + 1];
+        r[15] = first;
+    }
+#pragma unroll
+    for (int i = 0; i < w; i++) packed[i] = o[i];
+    return s;
+}
+
 // A whole block held by one lane: 16 packed bf16 dwords -> scale byte + packed codes.
 template <int FMT, int RND>
 __device__ __forceinline__ uint32_t quantize_block_bf16(const uint32_t (&d)[16], uint32_t *packed)
@@ -218,16 +259,7 @@ __device__ __forceinline__ uint32_t quantize_block_bf16(const uint32_t (&d)[16],
     if (fast_ok(amax16, s)) {
         convert_bf16_fast<FMT, RND, 16>(d, s, packed);
     } else {
-        uint32_t v[32];
-        widen_bf16<16>(d, v);
-        uint32_t amax = 0;
-#pragma unroll
-        for (int i = 0; i < 32; i++) {
-            uint32_t k = amax_key<FMT>(v[i]);
-            amax = amax > k ? amax : k;
-        }
-        s = scale_byte<FMT>(amax);
-        encode_exact<FMT, RND, 32>(v, s, packed);
+        s = quantize_block_bf16_exact<FMT, RND>(d, packed);
     }
     return s;
 }
