@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
 // ---------------------------------------------------------------------------
 // Column cast
 // ---------------------------------------------------------------------------
-constexpr int COL_TILE_R = 128, COL_TILE_C = 64;
+constexpr int COL_TILE_R = 128, COL_TILE_C = 64;   // rows a multiple of 128 (256 measured slower)
 
 // Work-groups are dealt round-robin to the 8 XCDs, each with its own L2.  Tile
 // t = xcd * per_xcd + i with the row-tile index fastest, so the work-groups of
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
 {
     if constexpr (FMT == FP8_E4M3 || FMT == FP8_E5M2) fp8_saturate_mode();
     constexpr int w = Fmt<FMT>::bits;
-    __shared__ __attribute__((aligned(16))) uint8_t tile[COL_TILE_R * COL_TILE_C * 2];   // 16 KB, 128-byte rows
+    __shared__ __attribute__((aligned(16))) uint8_t tile[COL_TILE_R * COL_TILE_C * 2];   // 128-byte rows
     const int t = threadIdx.x;
     const int64_t tile_id = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int64_t)(blockIdx.x >> 3) >= per_xcd || tile_id >= n_tiles) return;   // uniform over the work-group
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
     const int lr = t >> 3, lc = t & 7;
     const bool full_cols = c0 + COL_TILE_C <= cols;
 #pragma unroll
-    for (int p = 0; p < 4; p++) {
+    for (int p = 0; p < COL_TILE_R / 32; p++) {
         const int r = p * 32 + lr;                       // row inside the tile; its 32-row block is p
         uint4 v = make_uint4(0, 0, 0, 0);
         if (r0 + r < rows) {
@@ -207,48 +207,53 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
                 v = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
             }
         }
-        // rotate the row by 32 bytes per row block: column reads of the four blocks then hit different banks
+        // rotate the row by 32 bytes per row block: column reads of four adjacent blocks then hit different banks
         *reinterpret_cast<uint4 *>(tile + r * 128 + ((lc * 16 + p * 32) & 127)) = v;
     }
     __syncthreads();
 
-    // ---- lane (column c, row block rb): 32 values down the column, packed in pairs
-    const int c = t >> 2, rb = t & 3;
+    // ---- lane (column c, row block rb + 4q): 32 values down the column, packed in pairs
+    const int c = t >> 2;
     const int64_t col = c0 + c;
-    const int64_t row_blk = r0 / BLOCK + rb;
     const int64_t n_rb = rows / BLOCK;
-    const bool valid = col < cols && row_blk < n_rb;
-    const uint8_t *colp = tile + rb * 32 * 128 + ((c * 2 + rb * 32) & 127);
-    uint32_t d[16];
+    const bool quad = (n_rb & 3) == 0;                   // scale dwords are aligned
 #pragma unroll
-    for (int i = 0; i < 16; i++) {
-        uint32_t lo = *reinterpret_cast<const uint16_t *>(colp + (2 * i) * 128);
-        uint32_t hi = *reinterpret_cast<const uint16_t *>(colp + (2 * i + 1) * 128);
-        d[i] = lo | (hi << 16);
-    }
-    uint32_t out[w];
-    const uint32_t s = quantize_block_bf16<FMT, RND>(d, out);
-    // the four lanes of a column hold its four consecutive scale bytes: one dword store when
-    // the whole quad is valid and the address is aligned, else byte stores
-    const uint32_t s4 = s | ((uint32_t)__shfl_down((int)s, 1) << 8) | ((uint32_t)__shfl_down((int)s, 2) << 16) |
-                        ((uint32_t)__shfl_down((int)s, 3) << 24);
-    if (!valid) return;
-    uint8_t *o = elems + (col * n_rb + row_blk) * (BLOCK * w / 8);
-    if constexpr (w == 8) {
-        st16(o, make_uint4(out[0], out[1], out[2], out[3]));
-        st16(o + 16, make_uint4(out[4], out[5], out[6], out[7]));
-    } else if constexpr (w == 6) {
-        *reinterpret_cast<uint2 *>(o) = make_uint2(out[0], out[1]);
-        *reinterpret_cast<uint2 *>(o + 8) = make_uint2(out[2], out[3]);
-        *reinterpret_cast<uint2 *>(o + 16) = make_uint2(out[4], out[5]);
-    } else {
-        st16(o, make_uint4(out[0], out[1], out[2], out[3]));
-    }
-    const bool quad = (n_rb & 3) == 0 && r0 / BLOCK + 4 <= n_rb;   // uniform over the work-group
-    if (quad) {
-        if (rb == 0) *reinterpret_cast<uint32_t *>(scales + col * n_rb + row_blk) = s4;
-    } else {
-        scales[col * n_rb + row_blk] = (uint8_t)s;
+    for (int q = 0; q < COL_TILE_R / 128; q++) {
+        const int rb = (t & 3) + 4 * q;
+        const int64_t row_blk = r0 / BLOCK + rb;
+        const bool valid = col < cols && row_blk < n_rb;
+        const uint8_t *colp = tile + rb * 32 * 128 + ((c * 2 + rb * 32) & 127);
+        uint32_t d[16];
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            uint32_t lo = *reinterpret_cast<const uint16_t *>(colp + (2 * i) * 128);
+            uint32_t hi = *reinterpret_cast<const uint16_t *>(colp + (2 * i + 1) * 128);
+            d[i] = lo | (hi << 16);
+        }
+        uint32_t out[w];
+        const uint32_t s = quantize_block_bf16<FMT, RND>(d, out);
+        // the four lanes of a column hold four consecutive scale bytes: one dword store when the
+        // whole quad is valid and the address is aligned, else byte stores
+        const uint32_t s4 = s | ((uint32_t)__shfl_down((int)s, 1) << 8) | ((uint32_t)__shfl_down((int)s, 2) << 16) |
+                            ((uint32_t)__shfl_down((int)s, 3) << 24);
+        if (valid) {
+            uint8_t *o = elems + (col * n_rb + row_blk) * (BLOCK * w / 8);
+            if constexpr (w == 8) {
+                st16(o, make_uint4(out[0], out[1], out[2], out[3]));
+                st16(o + 16, make_uint4(out[4], out[5], out[6], out[7]));
+            } else if constexpr (w == 6) {
+                *reinterpret_cast<uint2 *>(o) = make_uint2(out[0], out[1]);
+                *reinterpret_cast<uint2 *>(o + 8) = make_uint2(out[2], out[3]);
+                *reinterpret_cast<uint2 *>(o + 16) = make_uint2(out[4], out[5]);
+            } else {
+                st16(o, make_uint4(out[0], out[1], out[2], out[3]));
+            }
+            if (quad && r0 / BLOCK + 4 * q + 4 <= n_rb) {   // uniform over the work-group
+                if ((t & 3) == 0) *reinterpret_cast<uint32_t *>(scales + col * n_rb + row_blk) = s4;
+            } else {
+                scales[col * n_rb + row_blk] = (uint8_t)s;
+            }
+        }
     }
 }
 
