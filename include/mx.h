@@ -4,6 +4,8 @@
  * Operations (arXiv 2310.10537):
  *   mx_quantize    Algorithm 1 (Section 3): float tensor -> MX blocks of 32
  *                  elements sharing one E8M0 power-of-two scale (Table 1).
+ *   mx_quantize_dual  the same cast along both axes in one pass (Section 4.1:
+ *                  a tensor and its transpose are quantized separately).
  *   mx_dequantize  v_i = X * P_i (Section 2).
  *   mx_gemm        the dot-product operation of the compute flow (Section 4.1):
  *                  both operands MX, scalar-float output.
@@ -98,6 +100,22 @@ size_t mx_scale_bytes(int64_t rows, int64_t cols, int axis);
 int mx_quantize(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols,
                 int64_t ld, int axis, mx_format_t fmt, mx_round_t rnd,
                 void *elems_out, uint8_t *scales_out, void *hip_stream);
+
+/*
+ * Both casts of one tensor in a single call: (elems_axis1, scales_axis1) receive
+ * exactly what mx_quantize writes with axis = 1 and (elems_axis0, scales_axis0)
+ * what it writes with axis = 0.  A training step needs each tensor with its
+ * blocks along the reduction axis of every GEMM that uses it (X and X^T, W and
+ * W^T, dY and dY^T -- Section 4.1, Figure 2 -- and the two casts differ), so the
+ * source is read once instead of twice.  rows and cols must both be multiples
+ * of 32.  bf16 sources made of whole 128 x 64 tiles take the one-pass kernel;
+ * anything else runs the two casts one after the other.  Arguments, alignment
+ * and error behaviour as for mx_quantize.
+ */
+int mx_quantize_dual(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols,
+                     int64_t ld, mx_format_t fmt, mx_round_t rnd,
+                     void *elems_axis1, uint8_t *scales_axis1,
+                     void *elems_axis0, uint8_t *scales_axis0, void *hip_stream);
 
 /*
  * v = X * P (Section 2) for an MX tensor produced by mx_quantize with the same

@@ -42,6 +42,7 @@ def lib() -> ctypes.CDLL:
         L.mx_scale_bytes.argtypes = [i64, i64, ci]
         L.mx_scale_bytes.restype = ctypes.c_size_t
         L.mx_quantize.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp]
+        L.mx_quantize_dual.argtypes = [vp, ci, i64, i64, i64, ci, ci, vp, vp, vp, vp, vp]
         L.mx_dequantize.argtypes = [vp, vp, ci, i64, i64, ci, vp, ci, i64, vp]
         L.mx_gemm.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, ci, i64, vp]
         L.mx_gemm_qa.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
@@ -103,6 +104,25 @@ def mx_quantize(src, axis, fmt, rnd=ROUND_RNE, elems_out=None, scales_out=None, 
     _check(lib().mx_quantize(src.data_ptr(), _dt(src), rows, cols, ld, axis, fmt, rnd,
                              elems_out.data_ptr(), scales_out.data_ptr(), _stream(stream)))
     return elems_out, scales_out
+
+
+def mx_quantize_dual(src, fmt, rnd=ROUND_RNE, out_axis1=None, out_axis0=None, stream=None):
+    """Both casts of src in one call.  Returns ((elems, scales) for axis 1, (elems, scales) for axis 0)."""
+    _dev(src, "src")
+    assert src.dim() == 2 and (src.shape[1] == 0 or src.stride(1) == 1)
+    rows, cols = src.shape
+    ld = src.stride(0) if rows > 1 else cols
+    w = FORMAT_BITS[fmt] if 0 <= fmt < 6 else 8
+    if out_axis1 is None:
+        out_axis1 = (torch.empty((rows, cols * w // 8), dtype=torch.uint8, device=src.device),
+                     torch.empty((rows, cols // BLOCK), dtype=torch.uint8, device=src.device))
+    if out_axis0 is None:
+        out_axis0 = (torch.empty((cols, rows * w // 8), dtype=torch.uint8, device=src.device),
+                     torch.empty((cols, rows // BLOCK), dtype=torch.uint8, device=src.device))
+    _check(lib().mx_quantize_dual(src.data_ptr(), _dt(src), rows, cols, ld, fmt, rnd,
+                                  out_axis1[0].data_ptr(), out_axis1[1].data_ptr(),
+                                  out_axis0[0].data_ptr(), out_axis0[1].data_ptr(), _stream(stream)))
+    return out_axis1, out_axis0
 
 
 def mx_dequantize(elems, scales, fmt, rows, cols, axis, dtype=torch.float32, out=None, stream=None):

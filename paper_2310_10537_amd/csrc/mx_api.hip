@@ -53,6 +53,23 @@ int mx_quantize(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols, 
     return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
 }
 
+int mx_quantize_dual(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols, int64_t ld, mx_format_t fmt,
+                     mx_round_t rnd, void *elems_axis1, uint8_t *scales_axis1, void *elems_axis0, uint8_t *scales_axis0,
+                     void *hip_stream)
+{
+    if (!fmt_ok(fmt) || !dt_ok(src_dt) || (rnd != MX_ROUND_RNE && rnd != MX_ROUND_HALF_AWAY)) return MX_ERR_ENUM;
+    if (int st = tensor_shape_status(rows, cols, 1, ld)) return st;
+    if (int st = tensor_shape_status(rows, cols, 0, ld)) return st;
+    if (rows == 0 || cols == 0) return MX_OK;
+    if (!src || !elems_axis1 || !scales_axis1 || !elems_axis0 || !scales_axis0) return MX_ERR_NULL;
+    if (!aligned16(src) || !aligned16(elems_axis1) || !aligned16(scales_axis1) || !aligned16(elems_axis0) ||
+        !aligned16(scales_axis0) || (ld * esize(src_dt)) % 16)
+        return MX_ERR_ALIGN;
+    hipError_t e = mx::launch_cast_dual(src, src_dt, rows, cols, ld, fmt, rnd, static_cast<uint8_t *>(elems_axis1), scales_axis1,
+                                        static_cast<uint8_t *>(elems_axis0), scales_axis0, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+}
+
 int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt, int64_t rows, int64_t cols, int axis,
                   void *dst, mx_dtype_t dst_dt, int64_t ld, void *hip_stream)
 {

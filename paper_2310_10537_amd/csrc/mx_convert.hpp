@@ -78,6 +78,30 @@ __device__ __forceinline__ uint32_t fp8_unoverflow(uint32_t codes)
 // matrix instruction whose result is kept can issue.
 __device__ __forceinline__ void fp8_saturate_mode(bool on = true) { __builtin_amdgcn_s_setreg(1 | (23 << 6) | (0 << 11), on ? 1 : 0); }
 
+// The 32-element FP6 converts, as inline assembly with an early-clobber result.  They read 16 or
+// 32 source registers and write 6, over several passes; the compiler's builtins let the register
+// allocator overlap the result with the sources at any offset, and when the result starts part
+// way into a source the first result dword lands on a source element that has not been read yet
+// (seen on the hardware: element 4 of every block wrong, nothing else).  A result that shares no
+// register with the sources is always safe.  The trailing s_nop stands in for whatever wait
+// states the compiler would place after the instruction: it does not look inside assembly text.
+template <bool E2M3>
+__device__ __forceinline__ u32x6_t cvt_pk32_fp6_from_bf16(bf16x32_t v, float sf)
+{
+    u32x6_t r;
+    if (E2M3) asm("v_cvt_scalef32_pk32_fp6_bf16 %0, %1, %2\n\ts_nop 1" : "=&v"(r) : "v"(v), "v"(sf));
+    else asm("v_cvt_scalef32_pk32_bf6_bf16 %0, %1, %2\n\ts_nop 1" : "=&v"(r) : "v"(v), "v"(sf));
+    return r;
+}
+template <bool E2M3>
+__device__ __forceinline__ u32x6_t cvt_2xpk16_fp6_from_f32(f32x16_t a, f32x16_t b, float sf)
+{
+    u32x6_t r;
+    if (E2M3) asm("v_cvt_scalef32_2xpk16_fp6_f32 %0, %1, %2, %3\n\ts_nop 1" : "=&v"(r) : "v"(a), "v"(b), "v"(sf));
+    else asm("v_cvt_scalef32_2xpk16_bf6_f32 %0, %1, %2, %3\n\ts_nop 1" : "=&v"(r) : "v"(a), "v"(b), "v"(sf));
+    return r;
+}
+
 // Convert ND packed bf16 dwords (2*ND consecutive elements of one block) with
 // scale byte s (>= FAST_MIN_SCALE, finite inputs only) into packed codes.
 // out receives 2*ND*bits/32 dwords.  FP6 needs the whole block (ND = 16).
@@ -143,8 +167,7 @@ __device__ __forceinline__ void convert_bf16_fast(const uint32_t (&d)[ND], uint3
             for (int i = 0; i < 16; i++) tmp[i] = d[i];
             bf16x32_t v;
             __builtin_memcpy(&v, tmp, 64);
-            r = FMT == FP6_E2M3 ? __builtin_amdgcn_cvt_scalef32_pk32_fp6_bf16(v, sf)
-                                : __builtin_amdgcn_cvt_scalef32_pk32_bf6_bf16(v, sf);
+            r = cvt_pk32_fp6_from_bf16<FMT == FP6_E2M3>(v, sf);
         } else {
             // the Float32 form interleaves its two sources: out[2i] = a[i], out[2i+1] = b[i],
             // which is exactly the low / high halves of the packed bf16 dwords
@@ -154,8 +177,7 @@ __device__ __forceinline__ void convert_bf16_fast(const uint32_t (&d)[ND], uint3
                 a[i] = __uint_as_float((d[i] << 16) | 1u);
                 b[i] = __uint_as_float((d[i] & 0xFFFF0000u) | 1u);
             }
-            r = FMT == FP6_E2M3 ? __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(a, b, sf)
-                                : __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(a, b, sf);
+            r = cvt_2xpk16_fp6_from_f32<FMT == FP6_E2M3>(a, b, sf);
         }
 #pragma unroll
         for (int i = 0; i < 6; i++) out[i] = r[i];

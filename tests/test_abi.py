@@ -23,8 +23,8 @@ def test_exports_match_header(L):
     text = open(os.path.join(ROOT, "include", "mx.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(mx_[a-z_]+)\s*\(", text))
-    assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_dequantize", "mx_gemm", "mx_gemm_qa",
-                     "mx_strerror"}
+    assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_dual", "mx_dequantize", "mx_gemm",
+                     "mx_gemm_qa", "mx_strerror"}
     for n in names:
         assert hasattr(L, n), n
 
@@ -55,6 +55,13 @@ def test_status_codes(L):
     assert q(p, 1, 32, 32, 32, 1, 0, 0, p, p + 8, None) == ALIGN
     assert q(None, 1, 0, 32, 32, 1, 0, 0, None, None, None) == OK  # empty: nothing to do
     assert q(None, 1, 32, 0, 0, 0, 0, 0, None, None, None) == OK
+    qd = L.mx_quantize_dual
+    assert qd(p, 1, 32, 32, 32, 0, 0, p, p, p, None, None) == NULL
+    assert qd(p, 1, 32, 32, 32, 6, 0, p, p, p, p, None) == ENUM
+    assert qd(p, 1, 48, 32, 32, 0, 0, p, p, p, p, None) == SHAPE    # both axes must be multiples of 32
+    assert qd(p, 1, 32, 48, 48, 0, 0, p, p, p, p, None) == SHAPE
+    assert qd(p, 1, 32, 32, 32, 0, 0, p, p, p + 4, p, None) == ALIGN
+    assert qd(None, 1, 0, 32, 32, 0, 0, None, None, None, None, None) == OK
     d = L.mx_dequantize
     assert d(p, None, 0, 32, 32, 1, p, 0, 32, None) == NULL
     assert d(p, p, 0, 32, 40, 1, p, 0, 40, None) == SHAPE

@@ -201,3 +201,51 @@ def test_full_size_config2_sampled(mx, oracle):
             assert np.array_equal(to_host(s[pk]), s_ref), (fmt, axis)
             # whole-tensor property: no NaN scale and every scale within the data's exponent range
             assert int(s.max()) < 255
+
+
+@pytest.mark.parametrize("fmt", range(6), ids=NAMES)
+@pytest.mark.parametrize("rnd", [RNE, AWAY], ids=["rne", "away"])
+@pytest.mark.parametrize("shape,kind", [((512, 256), "student"), ((256, 448), "adversarial"), ((128, 64), "student"),
+                                        ((96, 160), "student")])
+def test_quantize_dual_matches_reference_on_both_axes(mx, oracle, fmt, rnd, shape, kind):
+    """One pass, two MX tensors: each must be byte-identical to the reference cast along its axis.
+    Whole 128 x 64 tiles take the one-pass kernel (degenerate blocks included), the last shape the
+    two-launch fallback."""
+    rows, cols = shape
+    if kind == "adversarial":
+        x = inputs.f32_to_bf16_bits(inputs.adversarial_f32(rows, cols, seed=31 + fmt))
+    else:
+        x = inputs.student_t_bf16((rows, cols), seed=30 + fmt)
+    (e1, s1), (e0, s0) = mx.mx_quantize_dual(to_dev(x), fmt, rnd)
+    for axis, e, s in ((1, e1, s1), (0, e0, s0)):
+        re_, rs = oracle.quantize(x, axis, fmt, rnd)
+        assert np.array_equal(to_host(s), rs), f"scales axis {axis}"
+        assert np.array_equal(to_host(e), re_), f"elements axis {axis}"
+
+
+def test_quantize_dual_fp32_source_and_leading_dimension(mx, oracle):
+    """fp32 sources and padded rows go through the two ordinary casts; a bf16 view with a leading
+    dimension still takes the one-pass kernel."""
+    x = inputs.gaussian_f32((128, 192), seed=33)
+    (e1, s1), (e0, s0) = mx.mx_quantize_dual(to_dev(x), 2)
+    for axis, e, s in ((1, e1, s1), (0, e0, s0)):
+        re_, rs = oracle.quantize(x, axis, 2, 0)
+        assert np.array_equal(to_host(s), rs) and np.array_equal(to_host(e), re_)
+    big = inputs.student_t_bf16((256, 256), seed=34)
+    view = to_dev(big)[:, 64:192]
+    (e1, s1), (e0, s0) = mx.mx_quantize_dual(view, 0)
+    sub = np.ascontiguousarray(big[:, 64:192])
+    for axis, e, s in ((1, e1, s1), (0, e0, s0)):
+        re_, rs = oracle.quantize(sub, axis, 0, 0)
+        assert np.array_equal(to_host(s), rs) and np.array_equal(to_host(e), re_)
+
+
+def test_quantize_dual_full_size_sampled(mx, oracle):
+    """The 8192 x 8192 workload tensor: slices of both outputs against the reference."""
+    x = inputs.student_t_bf16((8192, 8192), seed=1)
+    (e1, s1), (e0, s0) = mx.mx_quantize_dual(to_dev(x), 0)
+    for lo in (0, 4000, 8192 - 128):
+        re_, rs = oracle.quantize(np.ascontiguousarray(x[lo:lo + 128]), 1, 0, 0)
+        assert np.array_equal(to_host(e1[lo:lo + 128]), re_) and np.array_equal(to_host(s1[lo:lo + 128]), rs)
+        re_, rs = oracle.quantize(np.ascontiguousarray(x[:, lo:lo + 128]), 0, 0, 0)
+        assert np.array_equal(to_host(e0[lo:lo + 128]), re_) and np.array_equal(to_host(s0[lo:lo + 128]), rs)
