@@ -428,3 +428,26 @@ def test_config5_sampled(mx, oracle, rnd):
         got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, h(A), fmt, h(B), fmt, K, seed=7, n=1024)
         check_gemm(got, C_ref, C_abs, f"config5 {name}", hw)
         del C
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("pad", [2, 8])
+def test_tiled_kernel_output_leading_dimension(mx, oracle, dt, pad):
+    """C as a view with a leading dimension (the header allows any ldc >= N): the padding columns
+    must stay untouched."""
+    M, N, K = 256, 512, 512
+    a = inputs.gaussian_f32((M, K), seed=120)
+    b = inputs.gaussian_f32((N, K), seed=121, std=0.02)
+    ea, sa = oracle.quantize(a, 1, 0)
+    eb, sb = oracle.quantize(b, 1, 0)
+    full = torch.full((M, N + pad), 7.0, dtype=dt, device="cuda")
+    mx.mx_gemm(to_dev(ea), to_dev(sa), 0, to_dev(eb), to_dev(sb), 0, K, out=full[:, :N])
+    ref = mx.mx_gemm(to_dev(ea), to_dev(sa), 0, to_dev(eb), to_dev(sb), 0, K, dtype=dt)
+    assert torch.equal(full[:, :N], ref)
+    assert torch.all(full[:, N:] == 7.0)
+    C_ref, C_abs = oracle.gemm(ea, sa, 0, eb, sb, 0, K, want_abs=True)
+    got = to_host(ref)
+    if dt == torch.bfloat16:
+        got = bf16_bits_to_f64(got)
+        C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5
+    check_gemm(got, C_ref, C_abs, "ldc", hw_term_for(oracle, ea, sa, 0, eb, sb, 0, K))
