@@ -49,11 +49,23 @@ __global__ __launch_bounds__(256) void cast_dual_bf16_kernel(const uint16_t *__r
     constexpr int w = Fmt<FMT>::bits;
     __shared__ __attribute__((aligned(16))) uint8_t tile[DUAL_R * DUAL_C * 2];   // 16 KB, 128-byte rows
     const int t = threadIdx.x;
-    // XCD-first tile order, rows fastest: what one XCD writes along axis 0 is consecutive in memory
+    // XCD-first tile order: each XCD owns a contiguous run of tiles
     const int64_t tile_id = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int64_t)(blockIdx.x >> 3) >= per_xcd || tile_id >= n_tiles) return;   // uniform over the work-group
-    const int64_t c0 = (tile_id / row_tiles) * DUAL_C;
-    const int64_t r0 = (tile_id % row_tiles) * DUAL_R;
+    int64_t ct = tile_id / row_tiles, rt = tile_id % row_tiles;
+    {
+        // Groups of up to 16 adjacent column strips are walked strips-fastest: the row-part pieces
+        // a tile writes (64 / 48 / 32 bytes per row) are then completed to whole lines by the
+        // neighbouring strips while they are still in L2 (measured: 188 -> 146 us on a
+        // 16384 x 8192 FP6 cast), and the column-part pieces still follow each other closely.
+        const int64_t col_tiles = n_tiles / row_tiles;
+        const int64_t sg = (col_tiles & 15) == 0 ? 16 : (col_tiles & 7) == 0 ? 8 : (col_tiles & 3) == 0 ? 4 : (col_tiles & 1) == 0 ? 2 : 1;
+        const int64_t grp = tile_id / (sg * row_tiles), in = tile_id % (sg * row_tiles);
+        ct = grp * sg + in % sg;
+        rt = in / sg;
+    }
+    const int64_t c0 = ct * DUAL_C;
+    const int64_t r0 = rt * DUAL_R;
 
     // ---- coalesced loads: 8 lanes per 128-byte row segment, 32 rows per pass
     {
