@@ -170,10 +170,10 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
 constexpr int COL_TILE_R = 128, COL_TILE_C = 64;   // rows a multiple of 128 (256 measured slower)
 
 // Work-groups are dealt round-robin to the 8 XCDs, each with its own L2.  Tile
-// t = xcd * per_xcd + i with the row-tile index fastest, so the work-groups of
-// one XCD walk down the rows of a column strip: what they write (128 bytes of
-// codes and 4 scale bytes per column each) is consecutive in memory and merges
-// into full lines in that XCD's L2.
+// t = xcd * per_xcd + i, each XCD owning a contiguous run of column strips which
+// it walks down the rows, a few adjacent strips abreast: what its work-groups
+// write (128 bytes of codes and 4 scale bytes per column each) is consecutive in
+// memory and merges into full lines in that XCD's L2.
 template <int FMT, int RND>
 __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__restrict__ src, int64_t rows, int64_t cols,
                                                             int64_t ld, uint8_t *__restrict__ elems,
@@ -186,8 +186,19 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
     const int t = threadIdx.x;
     const int64_t tile_id = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int64_t)(blockIdx.x >> 3) >= per_xcd || tile_id >= n_tiles) return;   // uniform over the work-group
-    const int64_t c0 = (tile_id / row_tiles) * COL_TILE_C;
-    const int64_t r0 = (tile_id % row_tiles) * COL_TILE_R;
+    int64_t ct = tile_id / row_tiles, rt = tile_id % row_tiles;
+    {
+        // groups of up to 8 adjacent column strips are walked strips-fastest (measured best of
+        // 1 / 2 / 4 / 8 / 16): the XCD then reads up to 1 KB contiguous per source row at a time,
+        // and consecutive row tiles of a strip still follow each other within 8 tiles
+        const int64_t col_tiles = n_tiles / row_tiles;
+        const int64_t sg = (col_tiles & 7) == 0 ? 8 : (col_tiles & 3) == 0 ? 4 : (col_tiles & 1) == 0 ? 2 : 1;
+        const int64_t grp = tile_id / (sg * row_tiles), in = tile_id % (sg * row_tiles);
+        ct = grp * sg + in % sg;
+        rt = in / sg;
+    }
+    const int64_t c0 = ct * COL_TILE_C;
+    const int64_t r0 = rt * COL_TILE_R;
 
     // ---- coalesced loads: 8 lanes per 128-byte row segment, 32 rows per pass
     const int lr = t >> 3, lc = t & 7;
