@@ -67,7 +67,7 @@ typedef enum {
     MX_ERR_SHAPE = 3,       /* negative size, block axis not a multiple of 32,
                                leading dimension smaller than the row length   */
     MX_ERR_ALIGN = 4,       /* pointer or leading dimension not 16-byte aligned  */
-    MX_ERR_UNSUPPORTED = 5, /* MX_INT8 operand passed to a GEMM                  */
+    MX_ERR_UNSUPPORTED = 5, /* MX_INT8 paired with another format in a GEMM      */
     MX_ERR_LAUNCH = 6       /* the HIP runtime refused the launch                */
 } mx_status_t;
 
@@ -140,7 +140,10 @@ int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt,
  * C is row-major [M][N] of type c_dt with leading dimension ldc >= N (elements;
  * any value, a multiple of 16 bytes is fastest); the C pointer is 16-byte
  * aligned; bf16 output is the Float32 accumulator rounded to nearest even.
- * fmtA / fmtB may differ; MX_INT8 is MX_ERR_UNSUPPORTED.
+ * fmtA / fmtB may differ, except that MX_INT8 pairs only with MX_INT8 (anything
+ * else is MX_ERR_UNSUPPORTED): that pair runs the integer matrix instruction
+ * block by block -- every block sum is an exact integer -- and adds the scaled
+ * block sums in Float32.
  */
 int mx_gemm(int64_t M, int64_t N, int64_t K,
             const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,

@@ -90,7 +90,7 @@ static int gemm_common(bool qa, int64_t M, int64_t N, int64_t K, const void *A_e
     if (!fmt_ok(fmtA) || !fmt_ok(fmtB) || !dt_ok(c_dt)) return MX_ERR_ENUM;
     if (qa && rnd != MX_ROUND_RNE && rnd != MX_ROUND_HALF_AWAY) return MX_ERR_ENUM;
     if (M < 0 || N < 0 || K < 0 || K % mx::BLOCK || ldc < N || (qa && lda < K)) return MX_ERR_SHAPE;
-    if (fmtA == MX_INT8 || fmtB == MX_INT8) return MX_ERR_UNSUPPORTED;
+    if ((fmtA == MX_INT8) != (fmtB == MX_INT8)) return MX_ERR_UNSUPPORTED;   // MXINT8 only pairs with MXINT8
     if (M == 0 || N == 0) return MX_OK;
     if (!C || (K > 0 && ((qa ? !A_bf16 : (!A_elems || !A_scales)) || !B_elems || !B_scales))) return MX_ERR_NULL;
     if (!aligned16(B_elems) || !aligned16(B_scales) || !aligned16(C)) return MX_ERR_ALIGN;
@@ -125,7 +125,7 @@ const char *mx_strerror(int status)
         case MX_ERR_ENUM: return "format, rounding, dtype or axis out of range";
         case MX_ERR_SHAPE: return "bad shape: negative size, block axis not a multiple of 32, or leading dimension too small";
         case MX_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
-        case MX_ERR_UNSUPPORTED: return "MX_INT8 operands are not supported by the GEMM";
+        case MX_ERR_UNSUPPORTED: return "the GEMM pairs MX_INT8 only with MX_INT8";
         case MX_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
         default: return "unknown status";
     }

@@ -93,6 +93,20 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
                        const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
                        const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st)
 {
+    if (fmtA == INT8 && fmtB == INT8) {
+        if (!a_bf16) return launch_gemm_int8(M, N, K, A_elems, A_scales, B_elems, B_scales, C, c_dt, ldc, st);
+        // quantize-on-load: cast A into a stream-ordered workspace first (the bytes mx_quantize writes)
+        const size_t eb = (size_t)M * (size_t)K, sb = eb / BLOCK;
+        if (eb == 0) return launch_gemm_int8(M, N, K, nullptr, nullptr, B_elems, B_scales, C, c_dt, ldc, st);
+        uint8_t *ws = nullptr;
+        hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), eb + sb + 16, st);
+        if (e != hipSuccess) return e;
+        uint8_t *wss = ws + ((eb + 15) & ~(size_t)15);
+        e = launch_cast(a_bf16, DT_BF16, M, K, lda, 1, INT8, rnd, ws, wss, st);
+        if (e == hipSuccess) e = launch_gemm_int8(M, N, K, ws, wss, B_elems, B_scales, C, c_dt, ldc, st);
+        const hipError_t f = hipFreeAsync(ws, st);
+        return e != hipSuccess ? e : f;
+    }
     // Quantize-on-load on whole tiles.  The fused kernel casts each A tile once per column of
     // output tiles and reads it as bf16 that often, so it pays only for narrow outputs (measured:
     // up to two tile columns), and only when there are enough tiles to fill the chip, since the

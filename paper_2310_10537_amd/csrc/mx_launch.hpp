@@ -26,6 +26,10 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
                        const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
                        const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st);
 
+// MXINT8 x MXINT8: integer matrix instruction per block, Float32 accumulation of the scaled block sums
+hipError_t launch_gemm_int8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint8_t *Be,
+                            const uint8_t *Bs, void *C, int c_dt, int64_t ldc, hipStream_t st);
+
 // true when the LDS-tiled kernel takes the problem: FP8 / FP6 / FP4 operands, whole 256 x 256
 // tiles, K a multiple of 512
 bool gemm_tiled_applies(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);

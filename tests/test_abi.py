@@ -73,6 +73,7 @@ def test_status_codes(L):
     assert g(16, 16, 32, p, p, 0, p, p, 0, p, 0, 8, None) == SHAPE   # ldc < N
     assert g(16, 16, 32, p, p, 5, p, p, 0, p, 0, 16, None) == UNSUP  # MXINT8 operand
     assert g(16, 16, 32, p, p, 0, p, p, 5, p, 0, 16, None) == UNSUP
+    assert g(16, 16, 32, p, p, 5, p, p, 5, None, 0, 16, None) == NULL   # MXINT8 pairs with MXINT8
     assert g(16, 16, 32, p, p, 0, p, p, 0, p + 4, 1, 16, None) == ALIGN
     assert g(0, 16, 32, None, None, 0, None, None, 0, None, 0, 16, None) == OK
     ga = L.mx_gemm_qa

@@ -451,3 +451,96 @@ def test_tiled_kernel_output_leading_dimension(mx, oracle, dt, pad):
         got = bf16_bits_to_f64(got)
         C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5
     check_gemm(got, C_ref, C_abs, "ldc", hw_term_for(oracle, ea, sa, 0, eb, sb, 0, K))
+
+
+# ---------------------------------------------------------------------------------------------
+# MXINT8 x MXINT8: integer block sums (exact), Float32 accumulation of the scaled sums.
+# ---------------------------------------------------------------------------------------------
+INT8 = 5
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 32), (17, 33, 64), (64, 64, 96), (130, 257, 416), (300, 40, 1024), (256, 512, 1536)])
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_int8_gemm_shapes(mx, oracle, shape, dt):
+    M, N, K = shape
+    rng = np.random.default_rng(M + N)
+    a = inputs.student_t_f32((M, K), seed=130) * np.exp2(rng.integers(-8, 8, (M, K // 32))).repeat(32, axis=1).astype(np.float32)
+    b = inputs.gaussian_f32((N, K), seed=131, std=0.02) * np.exp2(rng.integers(-8, 8, (N, K // 32))).repeat(32, axis=1).astype(np.float32)
+    ea, sa = oracle.quantize(a, 1, INT8)
+    eb, sb = oracle.quantize(b, 1, INT8)
+    C_ref, C_abs = oracle.gemm(ea, sa, INT8, eb, sb, INT8, K, want_abs=True)
+    got = to_host(mx.mx_gemm(to_dev(ea), to_dev(sa), INT8, to_dev(eb), to_dev(sb), INT8, K, dtype=dt))
+    if dt == torch.bfloat16:
+        got = bf16_bits_to_f64(got)
+        C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5
+    check_gemm(got, C_ref, C_abs, f"int8 {shape}")
+
+
+def test_int8_gemm_one_hot_and_exact_integers(mx, oracle):
+    """One-hot A rows reproduce single elements of B exactly (pins the K position of every operand
+    byte); integer-valued operands at X = 2^6 give exactly known integer results."""
+    M, N, K = 96, 64, 128
+    a = np.zeros((M, K), np.float32)
+    a[np.arange(M), np.arange(M) % K] = 1.0
+    b = inputs.gaussian_f32((N, K), seed=132)
+    ea, sa = oracle.quantize(a, 1, INT8)
+    eb, sb = oracle.quantize(b, 1, INT8)
+    Bd = oracle.dequantize(eb, sb, INT8, N, K, 1)
+    C = to_host(mx.mx_gemm(to_dev(ea), to_dev(sa), INT8, to_dev(eb), to_dev(sb), INT8, K))
+    assert np.array_equal(C, Bd[:, np.arange(M) % K].T.astype(np.float32))
+    rng = np.random.default_rng(5)
+    qa = rng.integers(-127, 128, (M, K)).astype(np.int8)
+    qb = rng.integers(-127, 128, (N, K)).astype(np.int8)
+    s = np.full((M, K // 32), 127 + 6, np.uint8)          # X = 2^6: element value = the integer code
+    C = to_host(mx.mx_gemm(to_dev(qa.view(np.uint8)), to_dev(s), INT8, to_dev(qb.view(np.uint8)), to_dev(s[:N]), INT8, K))
+    assert np.array_equal(C, (qa.astype(np.int64) @ qb.astype(np.int64).T).astype(np.float32))
+
+
+def test_int8_gemm_nan_scale_and_mixed_pair_refused(mx, oracle):
+    M, N, K = 40, 48, 96
+    a = inputs.gaussian_f32((M, K), seed=133)
+    b = inputs.gaussian_f32((N, K), seed=134)
+    ea, sa = oracle.quantize(a, 1, INT8)
+    eb, sb = oracle.quantize(b, 1, INT8)
+    sa[5, 1] = 0xFF
+    sb[7, 2] = 0xFF
+    C_ref, C_abs = oracle.gemm(ea, sa, INT8, eb, sb, INT8, K, want_abs=True)
+    C = to_host(mx.mx_gemm(to_dev(ea), to_dev(sa), INT8, to_dev(eb), to_dev(sb), INT8, K))
+    assert np.isnan(C[5]).all() and np.isnan(C[:, 7]).all() and np.isnan(C).sum() == N + M - 1
+    check_gemm(C, C_ref, np.nan_to_num(C_abs), "int8 nan")
+    with pytest.raises(mx.MxError):
+        mx.mx_gemm(to_dev(ea), to_dev(sa), INT8, to_dev(eb), to_dev(sb), 0, K)
+
+
+@pytest.mark.parametrize("rnd", [RNE, AWAY], ids=["rne", "away"])
+def test_int8_gemm_qa_equals_quantize_then_gemm(mx, oracle, rnd):
+    M, N, K = 136, 80, 288
+    a = inputs.student_t_bf16((M, K), seed=135)
+    b = inputs.gaussian_f32((N, K), seed=136, std=0.02)
+    ad = to_dev(a)
+    gb = mx.mx_quantize(to_dev(b), 1, INT8)
+    ga = mx.mx_quantize(ad, 1, INT8, rnd)
+    C2 = mx.mx_gemm(ga[0], ga[1], INT8, gb[0], gb[1], INT8, K)
+    C1 = mx.mx_gemm_qa(ad, INT8, rnd, gb[0], gb[1], INT8)
+    assert torch.equal(C1.view(torch.int32), C2.view(torch.int32))
+    ea, sa = oracle.quantize(a, 1, INT8, rnd)
+    eb, sb = oracle.quantize(b, 1, INT8)
+    C_ref, C_abs = oracle.gemm(ea, sa, INT8, eb, sb, INT8, K, want_abs=True)
+    check_gemm(to_host(C1), C_ref, C_abs, "int8 qa")
+
+
+def test_int8_gemm_full_size_sampled(mx, oracle):
+    """The transformer projection shape of config 3 in MXINT8: sampled entries against the reference."""
+    M, K, N = 8192, 4096, 4096
+    a = inputs.gaussian_bf16((M, K), seed=2)
+    w = inputs.gaussian_f32((K, N), seed=102, std=0.02)
+    ga = mx.mx_quantize(to_dev(a), 1, INT8)
+    gb = mx.mx_quantize(to_dev(w), 0, INT8)
+    C = mx.mx_gemm(ga[0], ga[1], INT8, gb[0], gb[1], INT8, K, dtype=torch.float32)
+    A = (to_host(ga[0]), to_host(ga[1]))
+    B = (to_host(gb[0]), to_host(gb[1]))
+    rng = np.random.default_rng(8)
+    mi, ni = rng.integers(0, M, 2048), rng.integers(0, N, 2048)
+    C_ref, C_abs = oracle.gemm_entries(A[0], A[1], INT8, B[0], B[1], INT8, K, mi, ni)
+    got = C[torch.from_numpy(mi).cuda(), torch.from_numpy(ni).cuda()].cpu().numpy().astype(np.float64)
+    check_gemm(got, C_ref, C_abs, "int8 full size")
