@@ -10,15 +10,20 @@
 // this tile shape and store instructions as well).  A direct load writes its 64
 // lanes to consecutive 16-byte LDS slots, so any layout that permutes 16-byte
 // slots is free: the permutation is applied on the global side.
-//   8-bit: a row is 128 bytes = 8 slots; chunk c of row r sits in slot
-//          c ^ (r & 7), so the operand reads (32 rows, same chunk) are free of
-//          bank conflicts.  A lane's operand is chunks {4s+g, 4s+g+2} of sub-step s.
+// LDS has 64 banks of 4 bytes (measured: a 16-byte wave read takes 4 clocks when each group
+// of 16 lanes covers 256 distinct bytes, 8 clocks with the 32-bank swizzle c ^ (r & 7)).
+//   8-bit: a row is 128 bytes = 8 slots, two rows per bank sweep; chunk c of
+//          row r sits in slot c ^ ((r >> 1) & 7), so the operand reads (rows r ..
+//          r+15, same chunk) touch 16 different 16-byte bank groups.  A lane's
+//          operand is chunks {4s+g, 4s+g+2} of sub-step s.
 //   6-bit: a row is 96 bytes = 8 units of 12 bytes, fetched with 12-byte direct
 //          loads, which still land in 16-byte slots (4 bytes of each stay
-//          unused): same slot arithmetic as 8-bit, a lane's operand (one MX
-//          block, 24 bytes) is units {4s+2g, 4s+2g+1}, read as two 12-byte reads.
-//   4-bit: a row is 64 bytes = 4 slots, slot c ^ ((r >> 1) & 3); a lane's
-//          operand is the single chunk 2s+g.
+//          unused); unit u of row r sits in slot u ^ (r & 7) -- for the 12-byte
+//          reads this measured fewer bank conflicts than the 8-bit rule -- and a
+//          lane's operand (one MX block, 24 bytes) is units {4s+2g, 4s+2g+1}, read
+//          as two 12-byte reads.
+//   4-bit: a row is 64 bytes = 4 slots, four rows per bank sweep, slot
+//          c ^ ((r >> 2) & 3); a lane's operand is the single chunk 2s+g.
 // Scale bytes travel the same way, four K steps at a time: a row's scale bytes
 // for 512 elements are 16 consecutive bytes, so one 16-byte direct load per row
 // brings four steps' worth and touches its cache line once instead of four
@@ -64,16 +69,16 @@ template <> struct TileFmt<6> { static constexpr int ROW = 128, UNIT = 12, RPI =
 template <> struct TileFmt<4> { static constexpr int ROW = 64, UNIT = 16, RPI = 16; };   // wave-wide direct load (1 KB of LDS)
 
 // LDS byte offset of 16-byte chunk c (0..7) of tile row r, 8-bit operand
-__device__ __forceinline__ int swz(int r, int c) { return r * 128 + ((c ^ (r & 7)) << 4); }
+__device__ __forceinline__ int swz(int r, int c) { return r * 128 + ((c ^ ((r >> 1) & 7)) << 4); }
 
 // Byte offset, inside a tile of width W, of the first LDS slot lane (li, g) reads for sub-step 0 of
 // tile row r (a multiple of 32 rows further down only adds to it).
 template <int W>
 __device__ __forceinline__ int frag_ofs(int r, int g)
 {
-    if (W == 8) return r * 128 + ((g ^ (r & 7)) << 4);
+    if (W == 8) return r * 128 + ((g ^ ((r >> 1) & 7)) << 4);
     if (W == 6) return r * 128 + (((2 * g) ^ (r & 7)) << 4);
-    return r * 64 + ((g ^ ((r >> 1) & 3)) << 4);
+    return r * 64 + ((g ^ ((r >> 2) & 3)) << 4);
 }
 
 // One operand fragment: tile row block x (32 rows each), sub-step sub, from the tile at buf.
@@ -144,8 +149,10 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     // ---- staging map: one direct load of a wave fills 1 KB of LDS = RPI tile rows; wave w, load j
     // covers rows (4j + w) * RPI .. + RPI-1.  Lane l writes slot l % S of row l / S of that group
     // (S slots per row) and therefore fetches the unit that the layout keeps in that slot.
-    const int a_r = WA == 4 ? lane >> 2 : lane >> 3, a_u = WA == 4 ? (lane & 3) ^ ((a_r >> 1) & 3) : (lane & 7) ^ a_r;
-    const int b_r = WB == 4 ? lane >> 2 : lane >> 3, b_u = WB == 4 ? (lane & 3) ^ ((b_r >> 1) & 3) : (lane & 7) ^ b_r;
+    // (tile row of the lane = a multiple of 32 rows + wave * RPI + a_r, which fixes the swizzle term)
+    const int a_r = WA == 4 ? lane >> 2 : lane >> 3, b_r = WB == 4 ? lane >> 2 : lane >> 3;
+    const int a_u = WA == 4 ? (lane & 3) ^ ((a_r >> 2) & 3) : WA == 6 ? (lane & 7) ^ a_r : (lane & 7) ^ (((wave * 8 + a_r) >> 1) & 7);
+    const int b_u = WB == 4 ? (lane & 3) ^ ((b_r >> 2) & 3) : WB == 6 ? (lane & 7) ^ b_r : (lane & 7) ^ (((wave * 8 + b_r) >> 1) & 7);
     const int64_t a_row_bytes = K * WA / 8, b_row_bytes = K * WB / 8;
     const uint8_t *gA = QA ? nullptr : Ae + (m0 + wave * TA::RPI + a_r) * a_row_bytes + a_u * TA::UNIT;
     const uint8_t *gB = Be + (n0 + wave * TB::RPI + b_r) * b_row_bytes + b_u * TB::UNIT;
@@ -380,18 +387,35 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
         }
     }
 
-    // ---- epilogue: lane (li, g), register t of tile (x, y) -> C[8*(t/4) + 4g + t%4][li]
+    // ---- epilogue: lane (li, g), register t of tile (x, y) -> C[8*(t/4) + 4g + t%4][li].
+    // bf16 output uses the hardware's packed Float32 -> bf16 convert (round to nearest even, two
+    // values per instruction): the integer formulation costs some 2000 vector instructions per
+    // lane here, most of the epilogue.  A NaN stays a NaN (its payload is the hardware's choice).
 #pragma unroll
     for (int x = 0; x < 4; x++)
 #pragma unroll
-        for (int y = 0; y < 4; y++)
+        for (int y = 0; y < 4; y++) {
+            const int64_t c = n0 + wn * 128 + y * 32 + li;
+            if constexpr (CDT == DT_F32) {
 #pragma unroll
-            for (int t = 0; t < 16; t++) {
-                const int64_t r = m0 + wm * 128 + x * 32 + 8 * (t / 4) + 4 * g + (t % 4);
-                const int64_t c = n0 + wn * 128 + y * 32 + li;
-                if (CDT == DT_F32) reinterpret_cast<float *>(C)[r * ldc + c] = acc[x][y][t];
-                else reinterpret_cast<uint16_t *>(C)[r * ldc + c] = (uint16_t)f32_to_bf16_bits(acc[x][y][t]);
+                for (int t = 0; t < 16; t++) {
+                    const int64_t r = m0 + wm * 128 + x * 32 + 8 * (t / 4) + 4 * g + (t % 4);
+                    reinterpret_cast<float *>(C)[r * ldc + c] = acc[x][y][t];
+                }
+            } else {
+                typedef float f32x2_t __attribute__((ext_vector_type(2)));
+                typedef __bf16 bf16x2_t_ __attribute__((ext_vector_type(2)));
+#pragma unroll
+                for (int t = 0; t < 16; t += 2) {
+                    const int64_t r = m0 + wm * 128 + x * 32 + 8 * (t / 4) + 4 * g + (t % 4);
+                    const f32x2_t v = {acc[x][y][t], acc[x][y][t + 1]};
+                    const uint32_t pk = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t_));
+                    uint16_t *o = reinterpret_cast<uint16_t *>(C) + r * ldc + c;
+                    o[0] = (uint16_t)pk;            // rows r and r + 1
+                    o[ldc] = (uint16_t)(pk >> 16);
+                }
             }
+        }
 }
 
 template <int FA, int FB, int CDT, bool QA, int RND>
