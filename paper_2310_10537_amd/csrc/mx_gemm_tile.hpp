@@ -287,25 +287,28 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     _Pragma("unroll") for (int x = 0; x < 4; x++)                                                                     \
         acc[x][Y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(AF[x], BF, acc[x][Y], HA, HB, OPS, (int)sa[x], OPS, (int)sb[Y])
 
-    // ---- prologue: stage 0 and stage 1 on their way to LDS
+    // ---- prologue: stage 0 (and the first scale group), then stage 1, on their way to LDS; the
+    // first half step only needs stage 0, so stage 1 may stay in flight until the first barrier
     stage_b(0, lds + A_BYTES);
     stage_scales(0);
     {
         const int t1 = T > 1 ? 1 : 0;
-        stage_b(t1, lds + STAGE_BYTES + A_BYTES);
         if (!QA) {
             stage_a(0, lds);
             stage_a(t1, lds + STAGE_BYTES);
+            stage_b(t1, lds + STAGE_BYTES + A_BYTES);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NJA + NJB) : "memory");   // all but the loads of stage 1
         } else {
+            stage_b(t1, lds + STAGE_BYTES + A_BYTES);
 #pragma unroll
             for (int p = 0; p < 4; p++) qa_request(0, p);
 #pragma unroll
             for (int p = 0; p < 4; p++) qa_commit(0, p, lds);
 #pragma unroll
             for (int p = 0; p < 4; p++) qa_request(1, p);   // committed during the first step
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // both stages have landed in LDS
     __syncthreads();
 #pragma unroll
     for (int x = 0; x < 4; x++) { a0[x] = read_frag<WA>(lds, ra0, 0, x); b0[x] = read_frag<WB>(lds + A_BYTES, rb0, 0, x); }
