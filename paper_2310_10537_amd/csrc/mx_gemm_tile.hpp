@@ -144,7 +144,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     const int64_t m0 = (int64_t)tm * TM;
     const int64_t n0 = (int64_t)tn * TN;
     const int64_t nkb = K / BLOCK;
-    const int T = (int)(K / TK);
+    const int T = (int)(K / TK);          // K steps; at least 4
+    const int Tfull = T & ~(SCL_GROUP - 1);   // steps in whole scale groups; the rest form a last, partial group
 
     // ---- staging map: one direct load of a wave fills 1 KB of LDS = RPI tile rows; wave w, load j
     // covers rows (4j + w) * RPI .. + RPI-1.  Lane l writes slot l % S of row l / S of that group
@@ -221,13 +222,18 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
         else if (k - NJA < NJB) stage_b1(ts, dstB, k - NJA);
     };
     uint8_t *const scl = lds + 2 * STAGE_BYTES;
-    const int n_groups = T / SCL_GROUP;
+    const int n_groups = (T + SCL_GROUP - 1) / SCL_GROUP;
+    // Byte offset, inside a row's 16-byte LDS slot, of the scale dword of K step ts.  The partial
+    // last group is loaded as the row's LAST 16 scale bytes (steps T-4 .. T-1), so that the load
+    // never reaches past the row, and its steps sit further back in the slot accordingly.
+    auto scl_ofs = [&](int ts) { return ts < Tfull ? (ts & (SCL_GROUP - 1)) * 4 : (ts - (T - SCL_GROUP)) * 4; };
     // scale bytes of K steps 4G .. 4G+3 (group G, clamped to the last) into slot G & 1: A rows, then B rows
     auto stage_scales = [&](int G) {
         G = G < n_groups ? G : n_groups - 1;
         uint8_t *dst = scl + (G & 1) * SCL_BYTES;
         const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + wave * 1024));
-        const uint8_t *pa = sA + G * 16, *pb = sB + G * 16;
+        const int64_t src_ofs = G * SCL_GROUP + SCL_GROUP <= T ? (int64_t)G * 16 : (int64_t)T * 4 - 16;
+        const uint8_t *pa = sA + src_ofs, *pb = sB + src_ofs;
         if (!QA) asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pa), "s"(l0) : "m0");
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pb), "s"(l0 + TM * 16) : "m0");
     };
@@ -267,11 +273,13 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
         const int r = q_row + 64 * p;
         *reinterpret_cast<uint4 *>(dst + swz(r, 2 * q_kb)) = make_uint4(out[0], out[1], out[2], out[3]);
         *reinterpret_cast<uint4 *>(dst + swz(r, 2 * q_kb + 1)) = make_uint4(out[4], out[5], out[6], out[7]);
-        scl[((ts / SCL_GROUP) & 1) * SCL_BYTES + r * 16 + (ts & (SCL_GROUP - 1)) * 4 + q_kb] = (uint8_t)sbyte;
+        const int tsc = ts < T ? ts : T - 1;
+        scl[((tsc / SCL_GROUP) & 1) * SCL_BYTES + r * 16 + scl_ofs(tsc) + q_kb] = (uint8_t)sbyte;
     };
     // scale dwords of K step ts for this lane's rows
     auto read_scales = [&](int ts) {
-        const uint8_t *src = scl + ((ts / SCL_GROUP) & 1) * SCL_BYTES + (ts & (SCL_GROUP - 1)) * 4;
+        ts = ts < T ? ts : T - 1;
+        const uint8_t *src = scl + ((ts / SCL_GROUP) & 1) * SCL_BYTES + scl_ofs(ts);
 #pragma unroll
         for (int x = 0; x < 4; x++) {
             const uint32_t da = *reinterpret_cast<const uint32_t *>(src + rsa + x * 512);
@@ -316,9 +324,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
 
     // four K steps (one scale group) per trip, so that the scale request sits in a fixed place of
     // straight-line code (a branch inside the step would undo the interleaving)
-    for (int tt = 0; tt < T; tt += SCL_GROUP) {
-#pragma unroll
-      for (int h = 0; h < SCL_GROUP; h++) {
+    // (the body is a lambda so that the partial last group can run it with a run-time step index)
+    auto k_step = [&](const int tt, const int h) __attribute__((always_inline)) {
         const int t = tt + h;
         uint8_t *bufA = lds + (h & 1) * STAGE_BYTES;
         uint8_t *nxt = lds + ((h & 1) ^ 1) * STAGE_BYTES;
@@ -370,8 +377,13 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
 #undef MX_Y_GROUP
         read_scales(t + 1);   // for the next step; the matrix instructions above already hold theirs
         MX_FENCE();
-      }
+    };
+    for (int tt = 0; tt < Tfull; tt += SCL_GROUP) {
+#pragma unroll
+        for (int h = 0; h < SCL_GROUP; h++) k_step(tt, h);
     }
+#pragma unroll 1
+    for (int h = 0; h < T - Tfull; h++) k_step(Tfull, h);
 #undef MX_MFMA4
 #undef MX_MFMA1
     // every direct load (the last, clamped, stages included) must have landed before this

@@ -31,7 +31,7 @@ hipError_t launch_gemm_int8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, 
                             const uint8_t *Bs, void *C, int c_dt, int64_t ldc, hipStream_t st);
 
 // true when the LDS-tiled kernel takes the problem: FP8 / FP6 / FP4 operands, whole 256 x 256
-// tiles, K a multiple of 512
+// tiles, K a multiple of 128 and at least 512
 bool gemm_tiled_applies(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
 // true when the tiled kernel can cast a bf16 A operand inside its K loop (8-bit pairs)
 bool gemm_tiled_fuses_cast(int fmtA, int fmtB);
