@@ -89,9 +89,10 @@ static hipError_t dispatch_b(const GemmArgs &g, int fmtB, int rnd, int c_dt)
 // whether the fused quantize-on-load tiled kernel beats cast + plain tiled kernel (256 x 256 tiles)
 static bool qa_fused_pays(int64_t M, int64_t N) { return N / 256 <= 2 && (M / 256) * (N / 256) >= 256; }
 
-hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, const uint8_t *A_scales,
-                       const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
-                       const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st)
+// one problem, one kernel route
+static hipError_t launch_gemm_part(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, const uint8_t *A_scales,
+                                   const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
+                                   const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st)
 {
     if (fmtA == INT8 && fmtB == INT8) {
         if (!a_bf16) return launch_gemm_int8(M, N, K, A_elems, A_scales, B_elems, B_scales, C, c_dt, ldc, st);
@@ -140,6 +141,32 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
         case FP6_E2M3: return dispatch_b<FP6_E2M3>(g, fmtB, rnd, c_dt);
         default:       return dispatch_b<FP4_E2M1>(g, fmtB, rnd, c_dt);
     }
+}
+
+// A problem whose M or N is not a multiple of the 256 x 256 tile is cut into the largest interior
+// of whole tiles, which takes the tiled kernel, and an L-shaped fringe of fewer than 256 rows /
+// columns, which takes the direct kernel.  Every output entry is computed by exactly one launch
+// and each kernel sums K in the same order, so the result does not depend on the cut.
+hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, const uint8_t *A_scales,
+                       const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
+                       const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st)
+{
+    const int64_t M0 = M & ~(int64_t)255, N0 = N & ~(int64_t)255;
+    if ((M0 == M && N0 == N) || M0 == 0 || N0 == 0 || fmtA == INT8 || !gemm_tiled_applies(M0, N0, K, fmtA, fmtB))
+        return launch_gemm_part(M, N, K, A_elems, A_scales, a_bf16, lda, rnd, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
+    const int64_t bitsA = fmtA <= FP8_E5M2 ? 8 : fmtA <= FP6_E2M3 ? 6 : 4, bitsB = fmtB <= FP8_E5M2 ? 8 : fmtB <= FP6_E2M3 ? 6 : 4;
+    const int64_t nkb = K / BLOCK, esz = c_dt == DT_F32 ? 4 : 2;
+    const uint8_t *a16 = static_cast<const uint8_t *>(a_bf16);
+    auto part = [&](int64_t r0, int64_t rows, int64_t c0, int64_t cols) {
+        return launch_gemm_part(rows, cols, K, A_elems ? A_elems + r0 * (K * bitsA / 8) : nullptr,
+                                A_scales ? A_scales + r0 * nkb : nullptr, a16 ? a16 + r0 * lda * 2 : nullptr, lda, rnd, fmtA,
+                                B_elems + c0 * (K * bitsB / 8), B_scales + c0 * nkb, fmtB,
+                                static_cast<uint8_t *>(C) + (r0 * ldc + c0) * esz, c_dt, ldc, st);
+    };
+    hipError_t e = part(0, M0, 0, N0);
+    if (e == hipSuccess && M > M0) e = part(M0, M - M0, 0, N);
+    if (e == hipSuccess && N > N0) e = part(0, M0, N0, N - N0);
+    return e;
 }
 
 }  // namespace mx

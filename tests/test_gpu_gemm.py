@@ -553,3 +553,20 @@ def test_int8_gemm_full_size_sampled(mx, oracle):
     C_ref, C_abs = oracle.gemm_entries(A[0], A[1], INT8, B[0], B[1], INT8, K, mi, ni)
     got = C[torch.from_numpy(mi).cuda(), torch.from_numpy(ni).cuda()].cpu().numpy().astype(np.float64)
     check_gemm(got, C_ref, C_abs, "int8 full size")
+
+
+@pytest.mark.parametrize("shape", [(300, 520, 640), (512, 257, 512), (257, 512, 1024), (700, 300, 512)])
+@pytest.mark.parametrize("fa,fb", [(0, 0), (2, 4)], ids=["e4m3xe4m3", "e3m2xe2m1"])
+def test_ragged_shapes_with_a_tiled_interior(mx, oracle, shape, fa, fb):
+    """M or N not a multiple of 256: whole tiles go to the tiled kernel, the fringe to the direct
+    kernel; also with A cast on load."""
+    M, N, K = shape
+    a = inputs.student_t_bf16((M, K), seed=140)
+    b = inputs.gaussian_f32((N, K), seed=141, std=0.02)
+    ea, sa = oracle.quantize(a, 1, fa)
+    eb, sb = oracle.quantize(b, 1, fb)
+    C_ref, C_abs = oracle.gemm(ea, sa, fa, eb, sb, fb, K, want_abs=True)
+    C = mx.mx_gemm(to_dev(ea), to_dev(sa), fa, to_dev(eb), to_dev(sb), fb, K)
+    check_gemm(to_host(C), C_ref, C_abs, f"ragged {shape}", hw_term_for(oracle, ea, sa, fa, eb, sb, fb, K))
+    Cq = mx.mx_gemm_qa(to_dev(a), fa, RNE, to_dev(eb), to_dev(sb), fb)
+    assert torch.equal(C.view(torch.int32), Cq.view(torch.int32))
