@@ -186,6 +186,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     typedef __attribute__((address_space(3))) void lds_ptr_t;
     typedef __attribute__((address_space(1))) const void glb_ptr_t;
     uint32_t sa[4], sb[4];   // scale dwords of the current stage, already shifted for this lane
+    uint32_t sa_n[4], sb_n[4];   // ... and of the next one, read early in the second half of a step
     v8i_t a0[4], a1[4], b0[4], b1[4];   // operand fragments of sub-step 0 / 1, double-buffered in time
 
     // Direct loads of one operand tile for K offset kofs into LDS tile dst.  Written as inline
@@ -284,8 +285,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
         for (int x = 0; x < 4; x++) {
             const uint32_t da = *reinterpret_cast<const uint32_t *>(src + rsa + x * 512);
             const uint32_t db = *reinterpret_cast<const uint32_t *>(src + rsb + x * 512);
-            sa[x] = g ? da >> 8 : da;
-            sb[x] = g ? db >> 8 : db;
+            sa_n[x] = g ? da >> 8 : da;
+            sb_n[x] = g ? db >> 8 : db;
         }
     };
 #define MX_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -321,6 +322,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
 #pragma unroll
     for (int x = 0; x < 4; x++) { a0[x] = read_frag<WA>(lds, ra0, 0, x); b0[x] = read_frag<WB>(lds + A_BYTES, rb0, 0, x); }
     read_scales(0);
+#pragma unroll
+    for (int x = 0; x < 4; x++) { sa[x] = sa_n[x]; sb[x] = sb_n[x]; }
 
     // four K steps (one scale group) per trip, so that the scale request sits in a fixed place of
     // straight-line code (a branch inside the step would undo the interleaving)
@@ -338,19 +341,19 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
         // Quantize-on-load: the registers hold stage t+1 of A (requested half a step ago); one
         // pass per group is cast and written to the other buffer, whose last readers passed the
         // previous barrier.
-        a1[0] = read_frag<WA>(bufA, ra0, 1, 0); b1[0] = read_frag<WB>(bufB, rb0, 1, 0);
+        a1[0] = read_frag<WA>(bufA, ra0, 1, 0); b1[0] = read_frag<WB>(bufB, rb0, 1, 0); a1[1] = read_frag<WA>(bufA, ra0, 1, 1);
         MX_MFMA4(a0, b0[0], 0, 0);
         if (QA) qa_commit(t + 1, 0, nxt);
         MX_FENCE();
-        a1[1] = read_frag<WA>(bufA, ra0, 1, 1); a1[2] = read_frag<WA>(bufA, ra0, 1, 2);
+        a1[2] = read_frag<WA>(bufA, ra0, 1, 2); a1[3] = read_frag<WA>(bufA, ra0, 1, 3); b1[1] = read_frag<WB>(bufB, rb0, 1, 1);
         MX_MFMA4(a0, b0[1], 1, 0);
         if (QA) qa_commit(t + 1, 1, nxt);
         MX_FENCE();
-        a1[3] = read_frag<WA>(bufA, ra0, 1, 3); b1[1] = read_frag<WB>(bufB, rb0, 1, 1);
+        b1[2] = read_frag<WB>(bufB, rb0, 1, 2); b1[3] = read_frag<WB>(bufB, rb0, 1, 3);
         MX_MFMA4(a0, b0[2], 2, 0);
         if (QA) qa_commit(t + 1, 2, nxt);
         MX_FENCE();
-        b1[2] = read_frag<WB>(bufB, rb0, 1, 2); b1[3] = read_frag<WB>(bufB, rb0, 1, 3);
+        // (no reads in the last group: the barrier below waits for every read of this half step)
         MX_MFMA4(a0, b0[3], 3, 0);
         if (QA) qa_commit(t + 1, 3, nxt);
         MX_FENCE();
@@ -372,10 +375,13 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
         if (QA) { qa_request(t + 2, 2); qa_request(t + 2, 3); }
         MX_Y_GROUP(1, a0[1] = read_frag<WA>(nxt, ra0, 0, 1), a0[2] = read_frag<WA>(nxt, ra0, 0, 2), b1[1], 1);
         if (h == 0) stage_scales(tt / SCL_GROUP + 1);   // next group, once every four steps
+        read_scales(t + 1);
         MX_Y_GROUP(2, a0[3] = read_frag<WA>(nxt, ra0, 0, 3), b0[1] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 1), b1[2], 2);
         MX_Y_GROUP(3, b0[2] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 2), b0[3] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 3), b1[3], 3);
 #undef MX_Y_GROUP
-        read_scales(t + 1);   // for the next step; the matrix instructions above already hold theirs
+        // the next step's scales were read two groups ago (their LDS latency is long past)
+#pragma unroll
+        for (int x = 0; x < 4; x++) { sa[x] = sa_n[x]; sb[x] = sb_n[x]; }
         MX_FENCE();
     };
     for (int tt = 0; tt < Tfull; tt += SCL_GROUP) {
