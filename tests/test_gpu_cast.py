@@ -249,3 +249,25 @@ def test_quantize_dual_full_size_sampled(mx, oracle):
         assert np.array_equal(to_host(e1[lo:lo + 128]), re_) and np.array_equal(to_host(s1[lo:lo + 128]), rs)
         re_, rs = oracle.quantize(np.ascontiguousarray(x[:, lo:lo + 128]), 0, 0, 0)
         assert np.array_equal(to_host(e0[lo:lo + 128]), re_) and np.array_equal(to_host(s0[lo:lo + 128]), rs)
+
+
+@pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_dequantize_every_code_at_every_scale(mx, oracle, fmt, dt):
+    """Row r carries scale byte r (0 .. 255, the last one the NaN scale) in all its blocks, and
+    every element code of the format appears in every row: all (code, scale) pairs, including the
+    products that overflow Float32 or fall into the subnormal range of the output type."""
+    w = [8, 8, 6, 6, 4, 8][fmt]
+    length = 256
+    codes = np.tile(np.arange(length, dtype=np.uint32) % (1 << w), (256, 1))
+    bits = ((codes[..., None] >> np.arange(w, dtype=np.uint32)) & 1).astype(np.uint8)
+    elems = np.packbits(bits.reshape(256, -1), axis=-1, bitorder="little")
+    scales = np.repeat(np.arange(256, dtype=np.uint8)[:, None], length // 32, axis=1)
+    ref = oracle.dequantize(elems, scales, fmt, 256, length, 1, dst_dt=0 if dt == torch.float32 else 1)
+    got = to_host(mx.mx_dequantize(to_dev(elems), to_dev(scales), fmt, 256, length, 1, dtype=dt))
+    if dt == torch.float32:
+        same = (got.view(np.uint32) == ref.view(np.uint32)) | (np.isnan(got) & np.isnan(ref))
+    else:
+        same = (got == ref) | (((got & 0x7FFF) > 0x7F80) & ((ref & 0x7FFF) > 0x7F80))
+    rows_bad = np.unique(np.nonzero(~same)[0])
+    assert same.all(), f"mismatches at scale bytes {rows_bad[:20]} (first code {np.nonzero(~same)[1][:5]})"
