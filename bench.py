@@ -149,6 +149,18 @@ def other_configs(n):
         b = n_elem * (src_bytes + mx.FORMAT_BITS[fmt] / 8.0 + 1.0 / 32.0)
         out[label] = {"avg_ms": round(ms, 5), "GBps": round(b / ms / 1e6, 1)}
 
+    # config 1: 1024 x 1024 fp32 round trip and a 256^3 GEMM -- cache-resident and launch-latency-bound,
+    # reported in microseconds; not an HBM measurement
+    x1 = torch.from_numpy(inputs.gaussian_f32((1024, 1024), seed=0)).cuda()
+    q1 = mx.mx_quantize(x1, 1, mx.FP8_E4M3)
+    y1 = torch.empty_like(x1)
+    out["cfg1_quantize_1024x1024_f32_e4m3_us"] = round(1e3 * time_call(lambda: mx.mx_quantize(x1, 1, mx.FP8_E4M3, mx.ROUND_RNE, q1[0], q1[1]), n), 2)
+    out["cfg1_dequantize_1024x1024_e4m3_f32_us"] = round(1e3 * time_call(lambda: mx.mx_dequantize(q1[0], q1[1], mx.FP8_E4M3, 1024, 1024, 1, out=y1), n), 2)
+    ga1 = mx.mx_quantize(torch.from_numpy(inputs.gaussian_f32((256, 256), seed=1)).cuda(), 1, mx.FP8_E4M3)
+    gb1 = mx.mx_quantize(torch.from_numpy(inputs.gaussian_f32((256, 256), seed=2)).cuda(), 1, mx.FP8_E4M3)
+    c1 = torch.empty((256, 256), dtype=torch.float32, device="cuda")
+    out["cfg1_gemm_256x256x256_e4m3_us"] = round(1e3 * time_call(lambda: mx.mx_gemm(ga1[0], ga1[1], mx.FP8_E4M3, gb1[0], gb1[1], mx.FP8_E4M3, 256, out=c1), n), 2)
+
     # config 3, second projection: 8192 x 11008 x 4096, E4M3, A cast on load
     M, K, N = 8192, 4096, 11008
     a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=2))
@@ -176,6 +188,17 @@ def other_configs(n):
     gemm_entry("cfg4_gemm_4096x28672x8192_e3m2_e2m1", M, N, K,
                time_call(lambda: mx.mx_gemm(ga[0], ga[1], mx.FP6_E3M2, gb[0], gb[1], mx.FP4_E2M1, K, out=C), n), 6)
     del act, w, ga, gb, C
+
+    # MXINT8 on the projection shape of config 3 (integer matrix instruction per block)
+    M, K, N = 8192, 4096, 4096
+    a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=2))
+    w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=102, std=0.02)).cuda()
+    ga = mx.mx_quantize(a, 1, mx.INT8)
+    gb = mx.mx_quantize(w, 0, mx.INT8)
+    C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    ms = time_call(lambda: mx.mx_gemm(ga[0], ga[1], mx.INT8, gb[0], gb[1], mx.INT8, K, out=C), max(2, n // 3))
+    out["int8_gemm_8192x4096x4096"] = {"avg_ms": round(ms, 5), "TOPs": round(2.0 * M * N * K / ms / 1e9, 1)}
+    del a, w, ga, gb, C
 
     # config 5: E3M2 training triple, half-away rounding; T tokens, hidden H, ffn F
     T, H, F = 16384, 2048, 8192
