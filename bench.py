@@ -189,7 +189,7 @@ def other_configs(n):
                time_call(lambda: mx.mx_gemm(ga[0], ga[1], mx.FP6_E3M2, gb[0], gb[1], mx.FP4_E2M1, K, out=C), n), 6)
     del act, w, ga, gb, C
 
-    # MXINT8 on the projection shape of config 3 (integer matrix instruction per block)
+    # MXINT8 on the projection shape of config 3 (each element split into two E2M3 halves, tiled kernel at depth 4K)
     M, K, N = 8192, 4096, 4096
     a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=2))
     w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=102, std=0.02)).cuda()

@@ -141,9 +141,14 @@ int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt,
  * any value, a multiple of 16 bytes is fastest); the C pointer is 16-byte
  * aligned; bf16 output is the Float32 accumulator rounded to nearest even.
  * fmtA / fmtB may differ, except that MX_INT8 pairs only with MX_INT8 (anything
- * else is MX_ERR_UNSUPPORTED): that pair runs the integer matrix instruction
+ * else is MX_ERR_UNSUPPORTED).  That pair runs the integer matrix instruction
  * block by block -- every block sum is an exact integer -- and adds the scaled
- * block sums in Float32.
+ * block sums in Float32; problems of at least 64 whole 256 x 256 tiles instead
+ * split every element exactly into two FP6 E2M3 halves (a workspace of
+ * (M + N) * K * 3.125 bytes from the stream's memory pool, as described at
+ * mx_gemm_qa) and run one E2M3 product of depth 4K, whose products are exact in
+ * the block-scaled instruction; both routes differ from the exact sum only by
+ * Float32 accumulation rounding.
  */
 int mx_gemm(int64_t M, int64_t N, int64_t K,
             const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
@@ -162,8 +167,9 @@ int mx_gemm(int64_t M, int64_t N, int64_t K,
  * workspace); otherwise A is first cast into a workspace of
  * M*K*(bits/8 + 1/32) bytes taken from and returned to the device's default
  * memory pool in stream order (hipMallocAsync / hipFreeAsync on hip_stream) --
- * the only allocation the library makes (MX_INT8 takes the same route); if the
- * pool refuses, the fused kernel runs instead.  Every other problem casts in
+ * the only kind of allocation the library makes (MX_INT8 takes the same route,
+ * and large MX_INT8 products take a workspace of their own, see mx_gemm); if
+ * the pool refuses, the fused kernel runs instead.  Every other problem casts in
  * registers in the direct kernel.
  */
 int mx_gemm_qa(int64_t M, int64_t N, int64_t K,

@@ -538,6 +538,54 @@ def test_int8_gemm_qa_equals_quantize_then_gemm(mx, oracle, rnd):
     check_gemm(to_host(C1), C_ref, C_abs, "int8 qa")
 
 
+def test_int8_gemm_whole_tiles_every_code_exact(mx, oracle):
+    """64 whole 256 x 256 tiles (the route that splits each code into two 6-bit halves): every code
+    -128 .. 127 on both sides at X = 2^6 gives exactly known integers; one-hot rows pin positions."""
+    M, N, K = 2048, 2048, 256
+    rng = np.random.default_rng(6)
+    qa = rng.integers(-128, 128, (M, K)).astype(np.int8)
+    qb = rng.integers(-128, 128, (N, K)).astype(np.int8)
+    qa[:, :256] = np.arange(-128, 128, dtype=np.int8)[None, :]        # every code in every row ...
+    qb[:256, :] = np.roll(np.arange(-128, 128, dtype=np.int8), 77)[:, None]  # ... against every code
+    sa = np.full((M, K // 32), 127 + 6, np.uint8)
+    sb = np.full((N, K // 32), 127 + 6, np.uint8)
+    C = to_host(mx.mx_gemm(to_dev(qa.view(np.uint8)), to_dev(sa), INT8, to_dev(qb.view(np.uint8)), to_dev(sb), INT8, K))
+    assert np.array_equal(C, (qa.astype(np.float64) @ qb.astype(np.float64).T).astype(np.float32))   # < 2^24: exact
+    a = np.zeros((M, K), np.float32)
+    a[np.arange(M), (7 * np.arange(M)) % K] = -1.0
+    b = inputs.gaussian_f32((N, K), seed=137)
+    ea, sa = oracle.quantize(a, 1, INT8)
+    eb, sb = oracle.quantize(b, 1, INT8)
+    Bd = oracle.dequantize(eb, sb, INT8, N, K, 1)
+    C = to_host(mx.mx_gemm(to_dev(ea), to_dev(sa), INT8, to_dev(eb), to_dev(sb), INT8, K))
+    assert np.array_equal(C, -Bd[:, (7 * np.arange(M)) % K].T.astype(np.float32))
+
+
+@pytest.mark.parametrize("low", [None, 0, 2, 3], ids=["plain", "scale0", "scale2", "scale3"])
+def test_int8_gemm_whole_tiles_scale_range_and_nan(mx, oracle, low):
+    """Whole tiles with block scales over a wide range, a NaN scale on each side and -- `low` --
+    scale bytes too small for the split route to lower (the exact pass behind it takes over)."""
+    M, N, K = 4096, 1024, 384
+    rng = np.random.default_rng(9)
+    a = inputs.student_t_f32((M, K), seed=138) * np.exp2(rng.integers(-20, 20, (M, K // 32))).repeat(32, axis=1).astype(np.float32)
+    b = inputs.gaussian_f32((N, K), seed=139) * np.exp2(rng.integers(-20, 20, (N, K // 32))).repeat(32, axis=1).astype(np.float32)
+    ea, sa = oracle.quantize(a, 1, INT8)
+    eb, sb = oracle.quantize(b, 1, INT8)
+    sa[300, 5] = 0xFF
+    sb[9, 0] = 0xFF
+    if low is not None:
+        sa[:, 3] = low
+        sb[:, 3] = 250          # lifts the products with the tiny blocks into the Float32 range
+        sb[:, 11] = low
+        sa[:, 11] = 250
+    C_ref, C_abs = oracle.gemm(ea, sa, INT8, eb, sb, INT8, K, want_abs=True)
+    C = to_host(mx.mx_gemm(to_dev(ea), to_dev(sa), INT8, to_dev(eb), to_dev(sb), INT8, K))
+    assert np.isnan(C[300]).all() and np.isnan(C[:, 9]).all() and np.isnan(C).sum() == N + M - 1
+    ok = ~np.isnan(C_ref)
+    assert np.isfinite(C_ref[ok]).all() and np.abs(C_ref[ok]).max() < 3e38
+    check_gemm(C, C_ref, np.nan_to_num(C_abs), f"int8 tiles low={low}")
+
+
 def test_int8_gemm_full_size_sampled(mx, oracle):
     """The transformer projection shape of config 3 in MXINT8: sampled entries against the reference."""
     M, K, N = 8192, 4096, 4096
@@ -553,6 +601,8 @@ def test_int8_gemm_full_size_sampled(mx, oracle):
     C_ref, C_abs = oracle.gemm_entries(A[0], A[1], INT8, B[0], B[1], INT8, K, mi, ni)
     got = C[torch.from_numpy(mi).cuda(), torch.from_numpy(ni).cuda()].cpu().numpy().astype(np.float64)
     check_gemm(got, C_ref, C_abs, "int8 full size")
+    Cq = mx.mx_gemm_qa(to_dev(a), INT8, RNE, gb[0], gb[1], INT8, dtype=torch.float32)
+    assert torch.equal(Cq.view(torch.int32), C.view(torch.int32))
 
 
 @pytest.mark.parametrize("shape", [(300, 520, 640), (512, 257, 512), (257, 512, 1024), (700, 300, 512)])
