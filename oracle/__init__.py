@@ -13,7 +13,7 @@ import numpy as np
 FP8_E4M3, FP8_E5M2, FP6_E3M2, FP6_E2M3, FP4_E2M1, INT8 = range(6)
 FORMATS = (FP8_E4M3, FP8_E5M2, FP6_E3M2, FP6_E2M3, FP4_E2M1, INT8)
 FORMAT_NAMES = ("fp8_e4m3", "fp8_e5m2", "fp6_e3m2", "fp6_e2m3", "fp4_e2m1", "int8")
-ROUND_RNE, ROUND_HALF_AWAY = 0, 1
+ROUND_RNE, ROUND_HALF_AWAY, ROUND_TOWARD_ZERO, ROUND_STOCHASTIC = 0, 1, 2, 3
 DT_F32, DT_BF16 = 0, 1
 BLOCK = 32
 
@@ -36,6 +36,17 @@ def lib():
         L.mxo_quantize_block.argtypes = [vp, ci, ci, vp, vp]
         L.mxo_quantize_block.restype = None
         L.mxo_quantize.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp]
+        L.mxo_quantize_seeded.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, ctypes.c_uint64, vp, vp]
+        L.mxo_encode_u.argtypes = [ci, ci, ctypes.c_double, ctypes.c_double]
+        L.mxo_encode_u.restype = ctypes.c_uint
+        L.mxo_quantize_block_u.argtypes = [vp, ci, ci, vp, vp, vp]
+        L.mxo_quantize_block_u.restype = None
+        L.mxo_philox4x32.argtypes = [ctypes.c_uint64, ctypes.c_uint64, vp]
+        L.mxo_philox4x32.restype = None
+        L.mxo_philox4x32_words.argtypes = [vp, vp, vp]
+        L.mxo_philox4x32_words.restype = None
+        L.mxo_sr_uniform.argtypes = [ctypes.c_uint64, i64]
+        L.mxo_sr_uniform.restype = ctypes.c_double
         L.mxo_dequantize.argtypes = [vp, vp, ci, i64, i64, ci, vp, ci, i64]
         L.mxo_gemm.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, vp]
         L.mxo_gemm_entries.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, i64, vp, vp, vp, vp]
@@ -59,21 +70,46 @@ def decode(fmt, code):
     return lib().mxo_decode(fmt, int(code))
 
 
-def encode(fmt, rnd, x):
-    return lib().mxo_encode(fmt, rnd, float(x))
+def encode(fmt, rnd, x, u=0.0):
+    return lib().mxo_encode_u(fmt, rnd, float(x), float(u))
+
+
+def philox4x32(key, counter):
+    """Philox4x32-10 with a 64-bit key and a 64-bit counter (upper counter words 0)."""
+    out = np.zeros(4, dtype=np.uint32)
+    lib().mxo_philox4x32(int(key), int(counter), _ptr(out))
+    return out
+
+
+def philox4x32_words(ctr, key):
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().mxo_philox4x32_words(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def sr_uniform(seed, e):
+    return lib().mxo_sr_uniform(int(seed), int(e))
 
 
 def num_threads():
     return lib().mxo_num_threads()
 
 
-def quantize_block(values, fmt, rnd=ROUND_RNE):
-    """values: 32 floats (widened to double).  Returns (scale_byte, codes[32])."""
+def quantize_block(values, fmt, rnd=ROUND_RNE, u=None):
+    """values: 32 floats (widened to double); u: 32 random offsets in [0, 1) for the
+    stochastic mode.  Returns (scale_byte, codes[32])."""
     v = np.ascontiguousarray(values, dtype=np.float64)
     assert v.shape == (BLOCK,)
     scale = np.zeros(1, dtype=np.uint8)
     codes = np.zeros(BLOCK, dtype=np.uint32)
-    lib().mxo_quantize_block(_ptr(v), fmt, rnd, _ptr(scale), _ptr(codes))
+    if u is None:
+        lib().mxo_quantize_block(_ptr(v), fmt, rnd, _ptr(scale), _ptr(codes))
+    else:
+        uu = np.ascontiguousarray(u, dtype=np.float64)
+        assert uu.shape == (BLOCK,)
+        lib().mxo_quantize_block_u(_ptr(v), fmt, rnd, _ptr(uu), _ptr(scale), _ptr(codes))
     return int(scale[0]), codes
 
 
@@ -86,8 +122,9 @@ def _src_dt(src):
     raise TypeError("source must be float32 or uint16 (bf16 bits)")
 
 
-def quantize(src, axis, fmt, rnd=ROUND_RNE):
+def quantize(src, axis, fmt, rnd=ROUND_RNE, seed=None):
     """src: 2-D C-contiguous float32 array or uint16 array of bf16 bits.
+    seed: required by (and only by) the stochastic mode.
     Returns (elems uint8 [n_out, len*bits/8], scales uint8 [n_out, len/32])."""
     src = np.ascontiguousarray(src)
     rows, cols = src.shape
@@ -95,8 +132,10 @@ def quantize(src, axis, fmt, rnd=ROUND_RNE):
     w = elem_bits(fmt)
     elems = np.zeros((n_out, length * w // 8), dtype=np.uint8)
     scales = np.zeros((n_out, length // BLOCK), dtype=np.uint8)
-    st = lib().mxo_quantize(_ptr(src), _src_dt(src), rows, cols, cols, axis, fmt, rnd,
-                            _ptr(elems), _ptr(scales))
+    if (rnd == ROUND_STOCHASTIC) != (seed is not None):
+        raise ValueError("a seed goes with the stochastic mode and with no other")
+    st = lib().mxo_quantize_seeded(_ptr(src), _src_dt(src), rows, cols, cols, axis, fmt, rnd,
+                                   int(seed or 0), _ptr(elems), _ptr(scales))
     if st != 0:
         raise ValueError("mxo_quantize rejected its arguments")
     return elems, scales

@@ -109,12 +109,21 @@ double mxo_decode(int fmt, unsigned code)
     return s * ldexp((double)((1u << f->mbits) + M), (int)E - f->bias - f->mbits);
 }
 
-/* Round the non-negative exact quotient q to an integer. */
-static double round_q(double q, int rnd)
+/* Round the non-negative exact quotient q to an integer.  u in [0, 1) is used
+ * by the stochastic mode only: the magnitude goes up when the discarded
+ * fraction plus u reaches 1, i.e. with probability equal to that fraction.
+ * u is a multiple of 2^-25 and q has at most 24 significant bits, so whenever
+ * the double sum q + u is not exact, q is far too small to move it across an
+ * integer: the floor is that of the exact sum. */
+static double round_q(double q, int rnd, double u)
 {
     double fl = floor(q);
     double d = q - fl; /* exact: q has at most 53 significant bits */
-    if (rnd == MXO_ROUND_HALF_AWAY) {
+    if (rnd == MXO_ROUND_TOWARD_ZERO) {
+        /* magnitude truncated */
+    } else if (rnd == MXO_ROUND_STOCHASTIC) {
+        fl = floor(q + u);
+    } else if (rnd == MXO_ROUND_HALF_AWAY) {
         if (d >= 0.5) fl += 1.0;
     } else { /* ties to even */
         if (d > 0.5 || (d == 0.5 && fmod(fl, 2.0) != 0.0)) fl += 1.0;
@@ -127,6 +136,11 @@ static double round_q(double q, int rnd)
  * after it), applied to x = V / X.
  * ---------------------------------------------------------------------- */
 unsigned mxo_encode(int fmt, int rnd, double x)
+{
+    return mxo_encode_u(fmt, rnd, x, 0.0);
+}
+
+unsigned mxo_encode_u(int fmt, int rnd, double x, double u)
 {
     if (!fmt_ok(fmt)) return 0;
     const fmt_t *f = &FMT[fmt];
@@ -147,7 +161,7 @@ unsigned mxo_encode(int fmt, int rnd, double x)
     double a = fabs(x);
 
     if (fmt == MXO_INT8) {
-        double q = round_q(ldexp(a, 6), rnd); /* grid step 2^-6 */
+        double q = round_q(ldexp(a, 6), rnd, u); /* grid step 2^-6 */
         if (q > 127.0) q = 127.0;             /* symmetric clamp */
         int iq = (int)q;
         if (sign) iq = -iq;
@@ -163,7 +177,7 @@ unsigned mxo_encode(int fmt, int rnd, double x)
     else
         step_exp = floor_log2(a) - f->mbits;
 
-    double q = round_q(ldexp(a, -step_exp), rnd);
+    double q = round_q(ldexp(a, -step_exp), rnd, u);
     double r = ldexp(q, step_exp);
     double vmax = fp_max_normal(f);
     if (r > vmax) r = vmax; /* clamp normals, keep sign */
@@ -189,6 +203,13 @@ unsigned mxo_encode(int fmt, int rnd, double x)
 
 void mxo_quantize_block(const double v[MXO_BLOCK], int fmt, int rnd,
                         uint8_t *scale, unsigned codes[MXO_BLOCK])
+{
+    mxo_quantize_block_u(v, fmt, rnd, NULL, scale, codes);
+}
+
+void mxo_quantize_block_u(const double v[MXO_BLOCK], int fmt, int rnd,
+                          const double *u, uint8_t *scale,
+                          unsigned codes[MXO_BLOCK])
 {
     const fmt_t *f = &FMT[fmt];
     int any_nonfinite = 0;
@@ -230,8 +251,67 @@ void mxo_quantize_block(const double v[MXO_BLOCK], int fmt, int rnd,
             x = copysign(0.0, v[i]); /* Float32 subnormal -> P_i = 0 */
         else
             x = ldexp(v[i], 127 - s);
-        codes[i] = mxo_encode(fmt, rnd, x);
+        codes[i] = mxo_encode_u(fmt, rnd, x, u ? u[i] : 0.0);
     }
+}
+
+/* ------------------------------------------------------------------------
+ * Random offsets of the stochastic mode: Philox4x32-10 (Salmon, Moraes, Dror,
+ * Shaw, "Parallel random numbers: as easy as 1, 2, 3", SC 2011), a counter
+ * based generator, so the number that belongs to a tensor element depends on
+ * (seed, element index) only and not on who computes it.
+ * One round: (c0,c1,c2,c3) <- (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1,
+ * lo(M0*c0)); the key goes up by the two Weyl constants before every round
+ * after the first.
+ * ---------------------------------------------------------------------- */
+void mxo_philox4x32(uint64_t key, uint64_t counter, uint32_t out[4])
+{
+    const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c[4] = { (uint32_t)counter, (uint32_t)(counter >> 32), 0u, 0u };
+    uint32_t k0 = (uint32_t)key, k1 = (uint32_t)(key >> 32);
+    for (int round = 0; round < 10; round++) {
+        if (round > 0) { k0 += W0; k1 += W1; }
+        uint64_t p0 = (uint64_t)M0 * c[0];
+        uint64_t p1 = (uint64_t)M1 * c[2];
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c[1] ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c[3] ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c[0] = n0; c[1] = n1; c[2] = n2; c[3] = n3;
+    }
+    for (int i = 0; i < 4; i++) out[i] = c[i];
+}
+
+/* same with a full 128-bit counter and 64-bit key given as words (used to
+ * check the generator against its published known answers) */
+void mxo_philox4x32_words(const uint32_t ctr[4], const uint32_t key[2],
+                          uint32_t out[4])
+{
+    const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c[4] = { ctr[0], ctr[1], ctr[2], ctr[3] };
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; round++) {
+        if (round > 0) { k0 += W0; k1 += W1; }
+        uint64_t p0 = (uint64_t)M0 * c[0];
+        uint64_t p1 = (uint64_t)M1 * c[2];
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c[1] ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c[3] ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c[0] = n0; c[1] = n1; c[2] = n2; c[3] = n3;
+    }
+    for (int i = 0; i < 4; i++) out[i] = c[i];
+}
+
+/* u of tensor element number e (row * cols + col of the source tensor):
+ * word e mod 4 of the generator's output for counter e / 4, top 25 bits. */
+double mxo_sr_uniform(uint64_t seed, int64_t e)
+{
+    uint32_t w[4];
+    mxo_philox4x32(seed, (uint64_t)e >> 2, w);
+    return ldexp((double)(w[e & 3] >> 7), -25);
 }
 
 /* ------------------------------------------------------------------------
@@ -285,9 +365,18 @@ int mxo_quantize(const void *src, int src_dt, int64_t rows, int64_t cols,
                  int64_t ld, int axis, int fmt, int rnd,
                  uint8_t *elems_out, uint8_t *scales_out)
 {
+    if (rnd == MXO_ROUND_STOCHASTIC) return MXO_ERR_ARG; /* needs a seed */
+    return mxo_quantize_seeded(src, src_dt, rows, cols, ld, axis, fmt, rnd, 0,
+                               elems_out, scales_out);
+}
+
+int mxo_quantize_seeded(const void *src, int src_dt, int64_t rows, int64_t cols,
+                        int64_t ld, int axis, int fmt, int rnd, uint64_t seed,
+                        uint8_t *elems_out, uint8_t *scales_out)
+{
     if (!src || !elems_out || !scales_out || !fmt_ok(fmt)) return MXO_ERR_ARG;
     if (src_dt != MXO_DT_F32 && src_dt != MXO_DT_BF16) return MXO_ERR_ARG;
-    if (rnd != MXO_ROUND_RNE && rnd != MXO_ROUND_HALF_AWAY) return MXO_ERR_ARG;
+    if (rnd < MXO_ROUND_RNE || rnd > MXO_ROUND_STOCHASTIC) return MXO_ERR_ARG;
     if (!shape_ok(rows, cols, axis) || ld < cols) return MXO_ERR_ARG;
 
     int w = FMT[fmt].bits;
@@ -302,14 +391,16 @@ int mxo_quantize(const void *src, int src_dt, int64_t rows, int64_t cols,
     for (int64_t o = 0; o < n_out; o++) {
         uint8_t *erow = elems_out + o * row_bytes;
         for (int64_t b = 0; b < nblk; b++) {
-            double v[MXO_BLOCK];
+            double v[MXO_BLOCK], u[MXO_BLOCK];
             unsigned codes[MXO_BLOCK];
             for (int i = 0; i < MXO_BLOCK; i++) {
                 int64_t l = b * MXO_BLOCK + i;
-                int64_t idx = axis == 1 ? o * ld + l : l * ld + o;
-                v[i] = load_scalar(src, src_dt, idx);
+                int64_t row = axis == 1 ? o : l, col = axis == 1 ? l : o;
+                v[i] = load_scalar(src, src_dt, row * ld + col);
+                u[i] = rnd == MXO_ROUND_STOCHASTIC
+                           ? mxo_sr_uniform(seed, row * cols + col) : 0.0;
             }
-            mxo_quantize_block(v, fmt, rnd, &scales_out[o * nblk + b], codes);
+            mxo_quantize_block_u(v, fmt, rnd, u, &scales_out[o * nblk + b], codes);
             for (int i = 0; i < MXO_BLOCK; i++)
                 put_code(erow, b * MXO_BLOCK + i, w, codes[i]);
         }
@@ -333,7 +424,7 @@ static uint16_t to_bf16_bits(double v)
     if (isinf(a)) return sign | 0x7F80;
     if (a == 0.0) return sign;
     int step_exp = (a < F32_MIN_NORMAL) ? -126 - 7 : floor_log2(a) - 7;
-    double r = ldexp(round_q(ldexp(a, -step_exp), MXO_ROUND_RNE), step_exp);
+    double r = ldexp(round_q(ldexp(a, -step_exp), MXO_ROUND_RNE, 0.0), step_exp);
     if (r > 0x1.FEp127) return sign | 0x7F80; /* above the largest bf16 */
     float fr = (float)r; /* exact: r is on the bf16 grid */
     uint32_t u;

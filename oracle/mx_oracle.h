@@ -39,8 +39,12 @@ enum {
 };
 
 /* Rounding used by quantize_to_element_format (Section 4.3: ties to even;
- * Section 4.5: ties away from zero). */
-enum { MXO_ROUND_RNE = 0, MXO_ROUND_HALF_AWAY = 1 };
+ * Section 4.5: ties away from zero).  The paper studies only those two; the
+ * other two are extensions of this build: the magnitude truncated, and the
+ * magnitude rounded up with probability equal to the discarded fraction
+ * (u in [0, 1), a multiple of 2^-25, is added to |x| / step before the floor). */
+enum { MXO_ROUND_RNE = 0, MXO_ROUND_HALF_AWAY = 1, MXO_ROUND_TOWARD_ZERO = 2,
+       MXO_ROUND_STOCHASTIC = 3 };
 
 /* Scalar float types of tensors handed to the cast. */
 enum { MXO_DT_F32 = 0, MXO_DT_BF16 = 1 };
@@ -67,12 +71,32 @@ double mxo_decode(int fmt, unsigned code);
  * caller handles non-finite inputs at block level and this returns 0. */
 unsigned mxo_encode(int fmt, int rnd, double x);
 
+/* Same with the random offset u of the stochastic mode (ignored by the other
+ * modes; mxo_encode passes 0, which makes that mode truncate). */
+unsigned mxo_encode_u(int fmt, int rnd, double x, double u);
+
 /* Algorithm 1 on one block of 32 values, already widened (exactly) from
  * Float32 or BFloat16 to double.  Inputs below 2^-126 in magnitude are
  * Float32 subnormals and become P_i = 0.  Writes the E8M0 byte and the 32
  * element codes. */
 void mxo_quantize_block(const double v[MXO_BLOCK], int fmt, int rnd,
                         uint8_t *scale, unsigned codes[MXO_BLOCK]);
+
+/* Same with one random offset per element (u may be NULL = all 0). */
+void mxo_quantize_block_u(const double v[MXO_BLOCK], int fmt, int rnd,
+                          const double *u, uint8_t *scale,
+                          unsigned codes[MXO_BLOCK]);
+
+/* Philox4x32-10 (Salmon et al., SC 2011) with counter words
+ * (lo32(counter), hi32(counter), 0, 0) and key words (lo32(key), hi32(key));
+ * the _words form takes all six words. */
+void mxo_philox4x32(uint64_t key, uint64_t counter, uint32_t out[4]);
+void mxo_philox4x32_words(const uint32_t ctr[4], const uint32_t key[2],
+                          uint32_t out[4]);
+
+/* Random offset of tensor element e = row * cols + col under `seed`:
+ * (word e mod 4 of philox(key = seed, counter = e / 4)) >> 7, times 2^-25. */
+double mxo_sr_uniform(uint64_t seed, int64_t e);
 
 /* Cast a row-major [rows, cols] tensor (leading dimension ld, in elements).
  * axis = 1: blocks of 32 along the last dimension;
@@ -84,6 +108,12 @@ void mxo_quantize_block(const double v[MXO_BLOCK], int fmt, int rnd,
 int mxo_quantize(const void *src, int src_dt, int64_t rows, int64_t cols,
                  int64_t ld, int axis, int fmt, int rnd,
                  uint8_t *elems_out, uint8_t *scales_out);
+
+/* Same for every rounding mode; the stochastic one draws element (row, col)'s
+ * offset as mxo_sr_uniform(seed, row * cols + col), whatever the axis. */
+int mxo_quantize_seeded(const void *src, int src_dt, int64_t rows, int64_t cols,
+                        int64_t ld, int axis, int fmt, int rnd, uint64_t seed,
+                        uint8_t *elems_out, uint8_t *scales_out);
 
 /* Inverse: v = X * P (Section 2), X = NaN makes the whole block NaN, results
  * beyond Float32 range become +-Inf.  Writes row-major [rows, cols]. */
