@@ -54,8 +54,17 @@ typedef enum {
 } mx_format_t;
 
 /* Rounding of V/X onto the element grid: ties to even (Section 4.3) or ties
- * away from zero (Section 4.5). */
-typedef enum { MX_ROUND_RNE = 0, MX_ROUND_HALF_AWAY = 1 } mx_round_t;
+ * away from zero (Section 4.5), the two modes the paper studies.  Two more are
+ * extensions of this library: the magnitude truncated (toward zero), and
+ * stochastic rounding -- the magnitude goes to the next grid value up with
+ * probability equal to the discarded fraction of a grid step, else down -- which
+ * needs a seed and therefore its own entry point, mx_quantize_sr. */
+typedef enum {
+    MX_ROUND_RNE = 0,
+    MX_ROUND_HALF_AWAY = 1,
+    MX_ROUND_TOWARD_ZERO = 2,
+    MX_ROUND_STOCHASTIC = 3
+} mx_round_t;
 
 /* Scalar float types. */
 typedef enum { MX_DT_F32 = 0, MX_DT_BF16 = 1 } mx_dtype_t;
@@ -86,7 +95,8 @@ size_t mx_scale_bytes(int64_t rows, int64_t cols, int axis);
  *                 cast of the transpose, so the block axis is contiguous again:
  *                 elems [cols][rows*bits/8], scales [cols][rows/32]
  *              (the two differ: cast and transpose do not commute, Section 3)
- *   fmt, rnd   element format and rounding mode
+ *   fmt, rnd   element format and rounding mode (MX_ROUND_STOCHASTIC is
+ *              MX_ERR_ENUM here: see mx_quantize_sr)
  *   elems_out  device, mx_elem_bytes() bytes, 16-byte aligned
  *   scales_out device, mx_scale_bytes() bytes, 16-byte aligned
  * The length of the block axis must be a multiple of 32.
@@ -102,15 +112,35 @@ int mx_quantize(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols,
                 void *elems_out, uint8_t *scales_out, void *hip_stream);
 
 /*
+ * Algorithm 1 with stochastic rounding in quantize_to_element_format (an
+ * extension; Section 3 leaves the element rounding to the implementation and
+ * the paper's studies use the two nearest modes).  Arguments, layouts, scale
+ * bytes, clamping and Inf/NaN handling as mx_quantize.  With step the grid
+ * spacing of the element format at |V/X|, the stored magnitude is
+ *     step * floor(|V/X| / step + u),   u = r / 2^25,
+ * r the top 25 bits of word (e mod 4) of Philox4x32-10 (Salmon et al., SC 2011)
+ * with key = seed and counter = e / 4, where e = row*cols + col numbers the
+ * elements of the SOURCE tensor.  The offset therefore belongs to the tensor
+ * element: casts of one tensor along axis 1 and axis 0 with one seed draw the
+ * same u for an element, and a result can be reproduced anywhere from
+ * (seed, shape).  Use a fresh seed per tensor and per step.
+ */
+int mx_quantize_sr(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols,
+                   int64_t ld, int axis, mx_format_t fmt, uint64_t seed,
+                   void *elems_out, uint8_t *scales_out, void *hip_stream);
+
+/*
  * Both casts of one tensor in a single call: (elems_axis1, scales_axis1) receive
  * exactly what mx_quantize writes with axis = 1 and (elems_axis0, scales_axis0)
  * what it writes with axis = 0.  A training step needs each tensor with its
  * blocks along the reduction axis of every GEMM that uses it (X and X^T, W and
  * W^T, dY and dY^T -- Section 4.1, Figure 2 -- and the two casts differ), so the
  * source is read once instead of twice.  rows and cols must both be multiples
- * of 32.  bf16 sources made of whole 128 x 64 tiles take the one-pass kernel;
- * anything else runs the two casts one after the other.  Arguments, alignment
- * and error behaviour as for mx_quantize.
+ * of 32.  bf16 sources made of whole 128 x 64 tiles, rounded to nearest, take
+ * the one-pass kernel; anything else runs the two casts one after the other.
+ * Arguments, alignment and error behaviour as for mx_quantize (for stochastic
+ * rounding call mx_quantize_sr twice with one seed: both axes then draw the
+ * same offset for an element).
  */
 int mx_quantize_dual(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols,
                      int64_t ld, mx_format_t fmt, mx_round_t rnd,
@@ -170,7 +200,9 @@ int mx_gemm(int64_t M, int64_t N, int64_t K,
  * the only kind of allocation the library makes (MX_INT8 takes the same route,
  * and large MX_INT8 products take a workspace of their own, see mx_gemm); if
  * the pool refuses, the fused kernel runs instead.  Every other problem casts in
- * registers in the direct kernel.
+ * registers in the direct kernel.  The in-kernel casts round to nearest:
+ * MX_ROUND_TOWARD_ZERO always casts into the workspace first (MX_ERR_LAUNCH if
+ * the pool refuses); MX_ROUND_STOCHASTIC is MX_ERR_ENUM.
  */
 int mx_gemm_qa(int64_t M, int64_t N, int64_t K,
                const void *A_bf16, int64_t lda, mx_format_t fmtA, mx_round_t rnd,

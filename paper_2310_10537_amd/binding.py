@@ -12,7 +12,7 @@ import torch
 FP8_E4M3, FP8_E5M2, FP6_E3M2, FP6_E2M3, FP4_E2M1, INT8 = range(6)
 FORMAT_NAMES = ("fp8_e4m3", "fp8_e5m2", "fp6_e3m2", "fp6_e2m3", "fp4_e2m1", "int8")
 FORMAT_BITS = (8, 8, 6, 6, 4, 8)
-ROUND_RNE, ROUND_HALF_AWAY = 0, 1
+ROUND_RNE, ROUND_HALF_AWAY, ROUND_TOWARD_ZERO, ROUND_STOCHASTIC = 0, 1, 2, 3
 DT_F32, DT_BF16 = 0, 1
 MX_OK = 0
 BLOCK = 32
@@ -42,6 +42,7 @@ def lib() -> ctypes.CDLL:
         L.mx_scale_bytes.argtypes = [i64, i64, ci]
         L.mx_scale_bytes.restype = ctypes.c_size_t
         L.mx_quantize.argtypes = [vp, ci, i64, i64, i64, ci, ci, ci, vp, vp, vp]
+        L.mx_quantize_sr.argtypes = [vp, ci, i64, i64, i64, ci, ci, ctypes.c_uint64, vp, vp, vp]
         L.mx_quantize_dual.argtypes = [vp, ci, i64, i64, i64, ci, ci, vp, vp, vp, vp, vp]
         L.mx_dequantize.argtypes = [vp, vp, ci, i64, i64, ci, vp, ci, i64, vp]
         L.mx_gemm.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, ci, i64, vp]
@@ -103,6 +104,24 @@ def mx_quantize(src, axis, fmt, rnd=ROUND_RNE, elems_out=None, scales_out=None, 
         scales_out = torch.empty((n_out, length // BLOCK), dtype=torch.uint8, device=src.device)
     _check(lib().mx_quantize(src.data_ptr(), _dt(src), rows, cols, ld, axis, fmt, rnd,
                              elems_out.data_ptr(), scales_out.data_ptr(), _stream(stream)))
+    return elems_out, scales_out
+
+
+def mx_quantize_sr(src, axis, fmt, seed, elems_out=None, scales_out=None, stream=None):
+    """mx_quantize with stochastic rounding; the random offset of an element is a function of
+    (seed, its index in src) only."""
+    _dev(src, "src")
+    assert src.dim() == 2 and (src.shape[1] == 0 or src.stride(1) == 1)
+    rows, cols = src.shape
+    ld = src.stride(0) if rows > 1 else cols
+    n_out, length = (rows, cols) if axis == 1 else (cols, rows)
+    w = FORMAT_BITS[fmt] if 0 <= fmt < 6 else 8
+    if elems_out is None:
+        elems_out = torch.empty((n_out, length * w // 8), dtype=torch.uint8, device=src.device)
+    if scales_out is None:
+        scales_out = torch.empty((n_out, length // BLOCK), dtype=torch.uint8, device=src.device)
+    _check(lib().mx_quantize_sr(src.data_ptr(), _dt(src), rows, cols, ld, axis, fmt, int(seed) & (2 ** 64 - 1),
+                                elems_out.data_ptr(), scales_out.data_ptr(), _stream(stream)))
     return elems_out, scales_out
 
 

@@ -9,6 +9,8 @@ namespace {
 
 bool fmt_ok(int f) { return f >= 0 && f < mx::NUM_FORMATS; }
 bool dt_ok(int d) { return d == MX_DT_F32 || d == MX_DT_BF16; }
+// the modes that need no seed
+bool rnd_ok(int r) { return r == MX_ROUND_RNE || r == MX_ROUND_HALF_AWAY || r == MX_ROUND_TOWARD_ZERO; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 int esize(int dt) { return dt == MX_DT_BF16 ? 2 : 4; }
 
@@ -38,26 +40,39 @@ size_t mx_scale_bytes(int64_t rows, int64_t cols, int axis)
     return (size_t)rows * (size_t)cols / mx::BLOCK;
 }
 
-int mx_quantize(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols, int64_t ld, int axis, mx_format_t fmt,
-                mx_round_t rnd, void *elems_out, uint8_t *scales_out, void *hip_stream)
+static int quantize_common(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols, int64_t ld, int axis,
+                           mx_format_t fmt, int rnd, uint64_t seed, void *elems_out, uint8_t *scales_out, void *hip_stream)
 {
-    if (!fmt_ok(fmt) || !dt_ok(src_dt) || (rnd != MX_ROUND_RNE && rnd != MX_ROUND_HALF_AWAY) || (axis != 0 && axis != 1))
-        return MX_ERR_ENUM;
+    if (!fmt_ok(fmt) || !dt_ok(src_dt) || (axis != 0 && axis != 1)) return MX_ERR_ENUM;
     if (int st = tensor_shape_status(rows, cols, axis, ld)) return st;
     if (rows == 0 || cols == 0) return MX_OK;
     if (!src || !elems_out || !scales_out) return MX_ERR_NULL;
     if (!aligned16(src) || !aligned16(elems_out) || !aligned16(scales_out) || (ld * esize(src_dt)) % 16)
         return MX_ERR_ALIGN;
     hipError_t e = mx::launch_cast(src, src_dt, rows, cols, ld, axis, fmt, rnd, static_cast<uint8_t *>(elems_out),
-                                   scales_out, static_cast<hipStream_t>(hip_stream));
+                                   scales_out, static_cast<hipStream_t>(hip_stream), seed);
     return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+}
+
+int mx_quantize(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols, int64_t ld, int axis, mx_format_t fmt,
+                mx_round_t rnd, void *elems_out, uint8_t *scales_out, void *hip_stream)
+{
+    if (!rnd_ok(rnd)) return MX_ERR_ENUM;   // the stochastic mode needs a seed: mx_quantize_sr
+    return quantize_common(src, src_dt, rows, cols, ld, axis, fmt, rnd, 0, elems_out, scales_out, hip_stream);
+}
+
+int mx_quantize_sr(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols, int64_t ld, int axis, mx_format_t fmt,
+                   uint64_t seed, void *elems_out, uint8_t *scales_out, void *hip_stream)
+{
+    return quantize_common(src, src_dt, rows, cols, ld, axis, fmt, MX_ROUND_STOCHASTIC, seed, elems_out, scales_out,
+                           hip_stream);
 }
 
 int mx_quantize_dual(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols, int64_t ld, mx_format_t fmt,
                      mx_round_t rnd, void *elems_axis1, uint8_t *scales_axis1, void *elems_axis0, uint8_t *scales_axis0,
                      void *hip_stream)
 {
-    if (!fmt_ok(fmt) || !dt_ok(src_dt) || (rnd != MX_ROUND_RNE && rnd != MX_ROUND_HALF_AWAY)) return MX_ERR_ENUM;
+    if (!fmt_ok(fmt) || !dt_ok(src_dt) || !rnd_ok(rnd)) return MX_ERR_ENUM;
     if (int st = tensor_shape_status(rows, cols, 1, ld)) return st;
     if (int st = tensor_shape_status(rows, cols, 0, ld)) return st;
     if (rows == 0 || cols == 0) return MX_OK;
@@ -88,7 +103,7 @@ static int gemm_common(bool qa, int64_t M, int64_t N, int64_t K, const void *A_e
                        mx_format_t fmtB, void *C, mx_dtype_t c_dt, int64_t ldc, void *hip_stream)
 {
     if (!fmt_ok(fmtA) || !fmt_ok(fmtB) || !dt_ok(c_dt)) return MX_ERR_ENUM;
-    if (qa && rnd != MX_ROUND_RNE && rnd != MX_ROUND_HALF_AWAY) return MX_ERR_ENUM;
+    if (qa && !rnd_ok(rnd)) return MX_ERR_ENUM;
     if (M < 0 || N < 0 || K < 0 || K % mx::BLOCK || ldc < N || (qa && lda < K)) return MX_ERR_SHAPE;
     if ((fmtA == MX_INT8) != (fmtB == MX_INT8)) return MX_ERR_UNSUPPORTED;   // MXINT8 only pairs with MXINT8
     if (M == 0 || N == 0) return MX_OK;

@@ -11,6 +11,7 @@
 //                    four adjacent lanes write one contiguous output line.
 #include "mx_device.hpp"
 #include "mx_launch.hpp"
+#include "mx_philox.hpp"
 
 namespace mx {
 
@@ -63,9 +64,10 @@ __device__ __forceinline__ void store_dwords(void *p, const uint32_t *d)
     }
 }
 
-// Quantize the N elements a lane holds, given the block's scale byte.
+// Quantize the N elements a lane holds, given the block's scale byte (r: their 25-bit random
+// offsets, read by the stochastic mode only).
 template <int FMT, int RND, int N>
-__device__ __forceinline__ void encode_lane(const uint32_t (&v)[N], uint32_t s, uint32_t *packed)
+__device__ __forceinline__ void encode_lane(const uint32_t (&v)[N], uint32_t s, const uint32_t (&r)[N], uint32_t *packed)
 {
     uint32_t c[N];
     if (!Fmt<FMT>::elem_nan && s == SCALE_NAN) {
@@ -73,7 +75,7 @@ __device__ __forceinline__ void encode_lane(const uint32_t (&v)[N], uint32_t s, 
         for (int i = 0; i < N; i++) c[i] = 0;
     } else {
 #pragma unroll
-        for (int i = 0; i < N; i++) c[i] = encode_elem<FMT, RND>(v[i], s);
+        for (int i = 0; i < N; i++) c[i] = encode_elem<FMT, RND>(v[i], s, r[i]);
     }
     pack_codes<FMT, N>(c, packed);
 }
@@ -85,7 +87,7 @@ __device__ __forceinline__ void encode_lane(const uint32_t (&v)[N], uint32_t s, 
 template <int SRC, int FMT, int RND, int EPL>
 __global__ __launch_bounds__(256) void cast_row_kernel(const void *__restrict__ src, int64_t cols, int64_t ld,
                                                        uint8_t *__restrict__ elems, uint8_t *__restrict__ scales,
-                                                       int64_t n_units)
+                                                       int64_t n_units, uint64_t seed)
 {
     constexpr int G = BLOCK / EPL;
     constexpr int w = Fmt<FMT>::bits;
@@ -103,6 +105,8 @@ __global__ __launch_bounds__(256) void cast_row_kernel(const void *__restrict__ 
             int64_t r = u / units_per_row;
             off = r * ld + (u - r * units_per_row) * EPL;
         }
+        uint32_t rr[EPL] = {};
+        if (RND == ROUND_STOCHASTIC) sr_offsets_run<EPL>(seed, u * EPL, rr);   // u * EPL = row * cols + col
         uint32_t v[EPL];
         load_as_f32_bits<SRC, EPL>(reinterpret_cast<const char *>(src) + off * esz, v);
 
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(256) void cast_row_kernel(const void *__restrict__ 
         const uint32_t s = scale_byte<FMT>(amax);
 
         uint32_t packed[ND];
-        encode_lane<FMT, RND, EPL>(v, s, packed);
+        encode_lane<FMT, RND, EPL>(v, s, rr, packed);
         store_dwords<ND>(elems + u * (EPL * w / 8), packed);
         if (G == 1 || (threadIdx.x & (G - 1)) == 0) scales[u / G] = (uint8_t)s;
     }
@@ -130,12 +134,42 @@ __global__ __launch_bounds__(256) void cast_row_kernel(const void *__restrict__ 
 template <int SRC, int FMT, int RND>
 __global__ __launch_bounds__(256) void cast_col_simple_kernel(const void *__restrict__ src, int64_t rows, int64_t cols,
                                                               int64_t ld, uint8_t *__restrict__ elems,
-                                                              uint8_t *__restrict__ scales)
+                                                              uint8_t *__restrict__ scales, uint64_t seed)
 {
     constexpr int w = Fmt<FMT>::bits;
     const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t rb = blockIdx.y;
     if (c >= cols) return;
+    uint32_t rr[BLOCK] = {};
+    if (RND == ROUND_STOCHASTIC) {
+        if ((cols & 3) == 0) {
+            // The four lanes of a quad hold columns 4j .. 4j+3, i.e. the four words of one generator
+            // call per row (cols is a multiple of 4, so a quad is never cut by the c >= cols exit):
+            // lane l of the quad runs the generator for rows l, l+4, ... and the quad swaps the words.
+            const int ql = threadIdx.x & 3;
+            Philox4 p[BLOCK / 4];
+#pragma unroll
+            for (int k = 0; k < BLOCK / 4; k++)
+                p[k] = philox4x32_10(seed, (uint64_t)(((rb * BLOCK + 4 * k + ql) * cols + (c & ~(int64_t)3)) >> 2));
+#pragma unroll
+            for (int i = 0; i < BLOCK; i++) {
+                uint32_t b[4];
+#pragma unroll
+                for (int m = 0; m < 4; m++) {
+                    const int src = (int)p[i >> 2].w[m];
+                    // quad_perm with all four selectors equal: every lane reads quad lane i % 4
+                    b[m] = (uint32_t)((i & 3) == 0   ? __builtin_amdgcn_update_dpp(0, src, 0x00, 0xF, 0xF, false)
+                                      : (i & 3) == 1 ? __builtin_amdgcn_update_dpp(0, src, 0x55, 0xF, 0xF, false)
+                                      : (i & 3) == 2 ? __builtin_amdgcn_update_dpp(0, src, 0xAA, 0xF, 0xF, false)
+                                                     : __builtin_amdgcn_update_dpp(0, src, 0xFF, 0xF, 0xF, false));
+                }
+                rr[i] = (ql == 0 ? b[0] : ql == 1 ? b[1] : ql == 2 ? b[2] : b[3]) >> 7;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < BLOCK; i++) rr[i] = sr_offset(seed, (rb * BLOCK + i) * cols + c);
+        }
+    }
     uint32_t v[BLOCK];
 #pragma unroll
     for (int i = 0; i < BLOCK; i++) {
@@ -151,7 +185,7 @@ __global__ __launch_bounds__(256) void cast_col_simple_kernel(const void *__rest
     }
     const uint32_t s = scale_byte<FMT>(amax);
     uint32_t packed[w];
-    encode_lane<FMT, RND, BLOCK>(v, s, packed);
+    encode_lane<FMT, RND, BLOCK>(v, s, rr, packed);
     const int64_t nrb = rows / BLOCK;
     store_dwords<w>(elems + (c * nrb + rb) * (BLOCK * w / 8), packed);
     scales[c * nrb + rb] = (uint8_t)s;
@@ -162,7 +196,7 @@ __global__ __launch_bounds__(256) void cast_col_simple_kernel(const void *__rest
 // ---------------------------------------------------------------------------
 template <int SRC, int FMT, int RND>
 static hipError_t launch_row(const void *src, int64_t rows, int64_t cols, int64_t ld, uint8_t *elems, uint8_t *scales,
-                             hipStream_t st)
+                             uint64_t seed, hipStream_t st)
 {
     // FP6 needs at least 16 elements per lane to store whole dwords
     constexpr int EPL = (Fmt<FMT>::bits == 6) ? 16 : 8;
@@ -171,54 +205,64 @@ static hipError_t launch_row(const void *src, int64_t rows, int64_t cols, int64_
     const int64_t cap = 256 * 32;   // enough work-groups to fill 256 CUs several times over
     if (nb > cap) nb = cap;
     hipLaunchKernelGGL((cast_row_kernel<SRC, FMT, RND, EPL>), dim3((unsigned)nb), dim3(256), 0, st, src, cols, ld, elems,
-                       scales, n_units);
+                       scales, n_units, seed);
     return hipGetLastError();
 }
 
 template <int SRC, int FMT, int RND>
 static hipError_t launch_col(const void *src, int64_t rows, int64_t cols, int64_t ld, uint8_t *elems, uint8_t *scales,
-                             hipStream_t st)
+                             uint64_t seed, hipStream_t st)
 {
     dim3 grid((unsigned)((cols + 255) / 256), (unsigned)(rows / BLOCK));
-    hipLaunchKernelGGL((cast_col_simple_kernel<SRC, FMT, RND>), grid, dim3(256), 0, st, src, rows, cols, ld, elems, scales);
+    hipLaunchKernelGGL((cast_col_simple_kernel<SRC, FMT, RND>), grid, dim3(256), 0, st, src, rows, cols, ld, elems, scales,
+                       seed);
     return hipGetLastError();
 }
 
 template <int SRC, int FMT>
-static hipError_t dispatch_rnd(int rnd, int axis, const void *src, int64_t rows, int64_t cols, int64_t ld, uint8_t *elems,
-                               uint8_t *scales, hipStream_t st)
+static hipError_t dispatch_rnd(int rnd, uint64_t seed, int axis, const void *src, int64_t rows, int64_t cols, int64_t ld,
+                               uint8_t *elems, uint8_t *scales, hipStream_t st)
 {
     if (axis == 1) {
-        return rnd == ROUND_RNE ? launch_row<SRC, FMT, ROUND_RNE>(src, rows, cols, ld, elems, scales, st)
-                                : launch_row<SRC, FMT, ROUND_HALF_AWAY>(src, rows, cols, ld, elems, scales, st);
+        switch (rnd) {
+            case ROUND_RNE:         return launch_row<SRC, FMT, ROUND_RNE>(src, rows, cols, ld, elems, scales, seed, st);
+            case ROUND_HALF_AWAY:   return launch_row<SRC, FMT, ROUND_HALF_AWAY>(src, rows, cols, ld, elems, scales, seed, st);
+            case ROUND_TOWARD_ZERO: return launch_row<SRC, FMT, ROUND_TOWARD_ZERO>(src, rows, cols, ld, elems, scales, seed, st);
+            default:                return launch_row<SRC, FMT, ROUND_STOCHASTIC>(src, rows, cols, ld, elems, scales, seed, st);
+        }
     }
-    return rnd == ROUND_RNE ? launch_col<SRC, FMT, ROUND_RNE>(src, rows, cols, ld, elems, scales, st)
-                            : launch_col<SRC, FMT, ROUND_HALF_AWAY>(src, rows, cols, ld, elems, scales, st);
+    switch (rnd) {
+        case ROUND_RNE:         return launch_col<SRC, FMT, ROUND_RNE>(src, rows, cols, ld, elems, scales, seed, st);
+        case ROUND_HALF_AWAY:   return launch_col<SRC, FMT, ROUND_HALF_AWAY>(src, rows, cols, ld, elems, scales, seed, st);
+        case ROUND_TOWARD_ZERO: return launch_col<SRC, FMT, ROUND_TOWARD_ZERO>(src, rows, cols, ld, elems, scales, seed, st);
+        default:                return launch_col<SRC, FMT, ROUND_STOCHASTIC>(src, rows, cols, ld, elems, scales, seed, st);
+    }
 }
 
 template <int SRC>
-static hipError_t dispatch_fmt(int fmt, int rnd, int axis, const void *src, int64_t rows, int64_t cols, int64_t ld,
-                               uint8_t *elems, uint8_t *scales, hipStream_t st)
+static hipError_t dispatch_fmt(int fmt, int rnd, uint64_t seed, int axis, const void *src, int64_t rows, int64_t cols,
+                               int64_t ld, uint8_t *elems, uint8_t *scales, hipStream_t st)
 {
     switch (fmt) {
-        case FP8_E4M3: return dispatch_rnd<SRC, FP8_E4M3>(rnd, axis, src, rows, cols, ld, elems, scales, st);
-        case FP8_E5M2: return dispatch_rnd<SRC, FP8_E5M2>(rnd, axis, src, rows, cols, ld, elems, scales, st);
-        case FP6_E3M2: return dispatch_rnd<SRC, FP6_E3M2>(rnd, axis, src, rows, cols, ld, elems, scales, st);
-        case FP6_E2M3: return dispatch_rnd<SRC, FP6_E2M3>(rnd, axis, src, rows, cols, ld, elems, scales, st);
-        case FP4_E2M1: return dispatch_rnd<SRC, FP4_E2M1>(rnd, axis, src, rows, cols, ld, elems, scales, st);
-        default:       return dispatch_rnd<SRC, INT8>(rnd, axis, src, rows, cols, ld, elems, scales, st);
+        case FP8_E4M3: return dispatch_rnd<SRC, FP8_E4M3>(rnd, seed, axis, src, rows, cols, ld, elems, scales, st);
+        case FP8_E5M2: return dispatch_rnd<SRC, FP8_E5M2>(rnd, seed, axis, src, rows, cols, ld, elems, scales, st);
+        case FP6_E3M2: return dispatch_rnd<SRC, FP6_E3M2>(rnd, seed, axis, src, rows, cols, ld, elems, scales, st);
+        case FP6_E2M3: return dispatch_rnd<SRC, FP6_E2M3>(rnd, seed, axis, src, rows, cols, ld, elems, scales, st);
+        case FP4_E2M1: return dispatch_rnd<SRC, FP4_E2M1>(rnd, seed, axis, src, rows, cols, ld, elems, scales, st);
+        default:       return dispatch_rnd<SRC, INT8>(rnd, seed, axis, src, rows, cols, ld, elems, scales, st);
     }
 }
 
 hipError_t launch_cast(const void *src, int src_dt, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,
-                       uint8_t *elems, uint8_t *scales, hipStream_t st)
+                       uint8_t *elems, uint8_t *scales, hipStream_t st, uint64_t seed)
 {
-    if (src_dt == DT_BF16) {
+    // the kernels built on the hardware converts round to nearest only
+    if (src_dt == DT_BF16 && (rnd == ROUND_RNE || rnd == ROUND_HALF_AWAY)) {
         hipError_t e = launch_cast_bf16_fast(src, rows, cols, ld, axis, fmt, rnd, elems, scales, st);
         if (e != hipErrorNotSupported) return e;
     }
-    return src_dt == DT_BF16 ? dispatch_fmt<DT_BF16>(fmt, rnd, axis, src, rows, cols, ld, elems, scales, st)
-                             : dispatch_fmt<DT_F32>(fmt, rnd, axis, src, rows, cols, ld, elems, scales, st);
+    return src_dt == DT_BF16 ? dispatch_fmt<DT_BF16>(fmt, rnd, seed, axis, src, rows, cols, ld, elems, scales, st)
+                             : dispatch_fmt<DT_F32>(fmt, rnd, seed, axis, src, rows, cols, ld, elems, scales, st);
 }
 
 }  // namespace mx

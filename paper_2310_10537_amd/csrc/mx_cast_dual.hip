@@ -144,7 +144,7 @@ static hipError_t launch_dual_r(int rnd, const uint16_t *src, int64_t rows, int6
 hipError_t launch_cast_dual(const void *src, int src_dt, int64_t rows, int64_t cols, int64_t ld, int fmt, int rnd,
                             uint8_t *e1, uint8_t *s1, uint8_t *e0, uint8_t *s0, hipStream_t st)
 {
-    if (src_dt == DT_BF16 && rows % DUAL_R == 0 && cols % DUAL_C == 0) {
+    if (src_dt == DT_BF16 && (rnd == ROUND_RNE || rnd == ROUND_HALF_AWAY) && rows % DUAL_R == 0 && cols % DUAL_C == 0) {
         const uint16_t *p = static_cast<const uint16_t *>(src);
         hipError_t e;
         switch (fmt) {

@@ -12,7 +12,10 @@
 namespace mx {
 
 enum : int { FP8_E4M3 = 0, FP8_E5M2 = 1, FP6_E3M2 = 2, FP6_E2M3 = 3, FP4_E2M1 = 4, INT8 = 5, NUM_FORMATS = 6 };
-enum : int { ROUND_RNE = 0, ROUND_HALF_AWAY = 1 };
+// ties to even (Section 4.3), ties away from zero (Section 4.5); the paper studies only those.  The
+// other two extend quantize_to_element_format: the magnitude truncated, and the magnitude rounded
+// up with probability equal to the discarded fraction.
+enum : int { ROUND_RNE = 0, ROUND_HALF_AWAY = 1, ROUND_TOWARD_ZERO = 2, ROUND_STOCHASTIC = 3 };
 enum : int { DT_F32 = 0, DT_BF16 = 1 };
 
 constexpr int BLOCK = 32;          // elements per shared scale (Table 1)
@@ -67,9 +70,13 @@ __device__ __forceinline__ uint32_t scale_byte(uint32_t amax)
 //   normal), rounded, and added onto the exponent field, so a rounding carry
 //   moves into the next binade by itself.  Magnitudes beyond the largest normal
 //   clamp to it; Float32 subnormals and zero give (signed) zero.
+//   Stochastic mode: r25, a uniform 25-bit integer, is added as r25 * 2^-25 grid steps before the
+//   magnitude is truncated.  The significand has 24 bits, so for shifts up to 25 only the top
+//   `shift` bits of r25 can produce a carry, and beyond 25 only the bits of the significand at
+//   or above 2^-25 of a step can: both truncations leave the floor unchanged.
 // ---------------------------------------------------------------------------
 template <int FMT, int RND>
-__device__ __forceinline__ uint32_t encode_elem(uint32_t fbits, uint32_t s)
+__device__ __forceinline__ uint32_t encode_elem(uint32_t fbits, uint32_t s, uint32_t r25 = 0)
 {
     using F = Fmt<FMT>;
     const uint32_t sign = fbits >> 31;
@@ -78,9 +85,15 @@ __device__ __forceinline__ uint32_t encode_elem(uint32_t fbits, uint32_t s)
     const uint32_t sig = (a & 0x7FFFFFu) | 0x800000u;
     const int be = E - (int)s + F::bias;
     int shift = (23 - F::mbits) + (be < 1 ? 1 - be : 0);
+    const int shift_true = shift;
     shift = shift > 25 ? 25 : shift;
     uint32_t q;
-    if (RND == ROUND_HALF_AWAY)
+    if (RND == ROUND_TOWARD_ZERO)
+        q = sig >> shift;                       // shift 25 already empties the 24-bit significand
+    else if (RND == ROUND_STOCHASTIC)
+        q = shift_true <= 25 ? (sig + (r25 >> (25 - shift))) >> shift
+                             : ((sig >> (shift_true - 25 > 31 ? 31 : shift_true - 25)) + r25) >> 25;
+    else if (RND == ROUND_HALF_AWAY)
         q = (sig + (1u << (shift - 1))) >> shift;
     else
         q = (sig + ((1u << (shift - 1)) - 1u) + ((sig >> shift) & 1u)) >> shift;

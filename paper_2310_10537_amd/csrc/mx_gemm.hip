@@ -151,6 +151,19 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
                        const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
                        const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st)
 {
+    if (a_bf16 && rnd != ROUND_RNE && rnd != ROUND_HALF_AWAY && M * K > 0) {
+        // the in-kernel casts round to nearest only: any other mode casts A into a workspace first
+        const size_t bits = fmtA == FP4_E2M1 ? 4 : (fmtA == FP6_E3M2 || fmtA == FP6_E2M3) ? 6 : 8;
+        const size_t eb = ((size_t)M * (size_t)K * bits / 8 + 15) & ~(size_t)15, sb = (size_t)M * (size_t)K / BLOCK;
+        uint8_t *ws = nullptr;
+        hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), eb + sb, st);
+        if (e != hipSuccess) return e;
+        e = launch_cast(a_bf16, DT_BF16, M, K, lda, 1, fmtA, rnd, ws, ws + eb, st);
+        if (e == hipSuccess)
+            e = launch_gemm(M, N, K, ws, ws + eb, nullptr, 0, ROUND_RNE, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
+        const hipError_t f = hipFreeAsync(ws, st);
+        return e != hipSuccess ? e : f;
+    }
     const int64_t M0 = M & ~(int64_t)255, N0 = N & ~(int64_t)255;
     if ((M0 == M && N0 == N) || M0 == 0 || N0 == 0 || fmtA == INT8 || !gemm_tiled_applies(M0, N0, K, fmtA, fmtB))
         return launch_gemm_part(M, N, K, A_elems, A_scales, a_bf16, lda, rnd, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);

@@ -184,7 +184,6 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     // fenced group by group, so the LDS pipe and the matrix pipe work at the same time.
     // Stages beyond the last are clamped to the last one (harmless extra loads, no branches).
     typedef __attribute__((address_space(3))) void lds_ptr_t;
-    typedef __attribute__((address_space(1))) const void glb_ptr_t;
     uint32_t sa[4], sb[4];   // scale dwords of the current stage, already shifted for this lane
     uint32_t sa_n[4], sb_n[4];   // ... and of the next one, read early in the second half of a step
     v8i_t a0[4], a1[4], b0[4], b1[4];   // operand fragments of sub-step 0 / 1, double-buffered in time

@@ -7,10 +7,12 @@
 
 namespace mx {
 
+// seed: read by the stochastic rounding mode only
 hipError_t launch_cast(const void *src, int src_dt, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,
-                       uint8_t *elems, uint8_t *scales, hipStream_t st);
+                       uint8_t *elems, uint8_t *scales, hipStream_t st, uint64_t seed = 0);
 
-// bf16 sources only; hipErrorNotSupported when the shape is outside what the fast kernels take
+// bf16 sources and the two round-to-nearest modes only; hipErrorNotSupported when the shape is
+// outside what the fast kernels take
 hipError_t launch_cast_bf16_fast(const void *src, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,
                                  uint8_t *elems, uint8_t *scales, hipStream_t st);
 

@@ -23,7 +23,7 @@ def test_exports_match_header(L):
     text = open(os.path.join(ROOT, "include", "mx.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(mx_[a-z_]+)\s*\(", text))
-    assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_dual", "mx_dequantize", "mx_gemm",
+    assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_sr", "mx_quantize_dual", "mx_dequantize", "mx_gemm",
                      "mx_gemm_qa", "mx_strerror"}
     for n in names:
         assert hasattr(L, n), n
@@ -44,7 +44,9 @@ def test_status_codes(L):
     assert q(None, 1, 32, 32, 32, 1, 0, 0, p, p, None) == NULL
     assert q(p, 1, 32, 32, 32, 1, 6, 0, p, p, None) == ENUM
     assert q(p, 2, 32, 32, 32, 1, 0, 0, p, p, None) == ENUM
-    assert q(p, 1, 32, 32, 32, 1, 0, 2, p, p, None) == ENUM
+    assert q(p, 1, 32, 32, 32, 1, 0, 3, p, p, None) == ENUM      # stochastic rounding needs a seed: mx_quantize_sr
+    assert q(p, 1, 32, 32, 32, 1, 0, 4, p, p, None) == ENUM
+    assert q(None, 1, 32, 32, 32, 1, 0, 2, p, p, None) == NULL   # toward zero is a mode of mx_quantize
     assert q(p, 1, 32, 32, 32, 2, 0, 0, p, p, None) == ENUM
     assert q(p, 1, 32, 48, 48, 1, 0, 0, p, p, None) == SHAPE     # block axis not a multiple of 32
     assert q(p, 1, 48, 32, 32, 0, 0, 0, p, p, None) == SHAPE
@@ -55,7 +57,14 @@ def test_status_codes(L):
     assert q(p, 1, 32, 32, 32, 1, 0, 0, p, p + 8, None) == ALIGN
     assert q(None, 1, 0, 32, 32, 1, 0, 0, None, None, None) == OK  # empty: nothing to do
     assert q(None, 1, 32, 0, 0, 0, 0, 0, None, None, None) == OK
+    qs = L.mx_quantize_sr
+    assert qs(None, 1, 32, 32, 32, 1, 0, 7, p, p, None) == NULL
+    assert qs(p, 1, 32, 32, 32, 1, 6, 7, p, p, None) == ENUM
+    assert qs(p, 1, 32, 48, 48, 1, 0, 7, p, p, None) == SHAPE
+    assert qs(p, 1, 32, 32, 32, 1, 0, 7, p + 4, p, None) == ALIGN
+    assert qs(None, 1, 0, 32, 32, 1, 0, 7, None, None, None) == OK
     qd = L.mx_quantize_dual
+    assert qd(p, 1, 32, 32, 32, 0, 3, p, p, p, p, None) == ENUM
     assert qd(p, 1, 32, 32, 32, 0, 0, p, p, p, None, None) == NULL
     assert qd(p, 1, 32, 32, 32, 6, 0, p, p, p, p, None) == ENUM
     assert qd(p, 1, 48, 32, 32, 0, 0, p, p, p, p, None) == SHAPE    # both axes must be multiples of 32

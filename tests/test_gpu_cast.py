@@ -271,3 +271,127 @@ def test_dequantize_every_code_at_every_scale(mx, oracle, fmt, dt):
         same = (got == ref) | (((got & 0x7FFF) > 0x7F80) & ((ref & 0x7FFF) > 0x7F80))
     rows_bad = np.unique(np.nonzero(~same)[0])
     assert same.all(), f"mismatches at scale bytes {rows_bad[:20]} (first code {np.nonzero(~same)[1][:5]})"
+
+
+# ---------------------------------------------------------------------------------------------
+# The two added rounding modes: magnitude truncation and stochastic rounding.
+# ---------------------------------------------------------------------------------------------
+RTZ, SR = 2, 3
+
+
+def dev_view(src_np):
+    """Device tensor of src_np as a view into a wider allocation when its row length is not a
+    16-byte multiple (the library wants aligned rows, not aligned column counts)."""
+    rows, cols = src_np.shape
+    pad = (-cols) % 8
+    if pad == 0:
+        return to_dev(src_np)
+    wide = np.zeros((rows, cols + pad), dtype=src_np.dtype)
+    wide[:, :cols] = src_np
+    return to_dev(wide)[:, :cols]
+
+
+def check_cast_sr(mx, oracle, src_np, axis, fmt, seed, tag=""):
+    e_ref, s_ref = oracle.quantize(src_np, axis, fmt, SR, seed=seed)
+    e, s = mx.mx_quantize_sr(dev_view(src_np), axis, fmt, seed)
+    torch.cuda.synchronize()
+    e, s = to_host(e), to_host(s)
+    assert np.array_equal(s, s_ref), f"{tag} scale bytes differ"
+    bad = np.argwhere(e != e_ref)
+    assert bad.size == 0, f"{tag} element byte mismatch at {bad[:5].tolist()}: got {e[tuple(bad[0])]} want {e_ref[tuple(bad[0])]}"
+    return e_ref, s_ref
+
+
+@pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("axis,shape", [(1, (203, 416)), (0, (160, 200)), (0, (96, 203))], ids=["axis1", "axis0", "axis0_odd_cols"])
+def test_cast_toward_zero(mx, oracle, fmt, dt, axis, shape):
+    x = inputs.student_t_f32(shape, seed=60 + fmt)
+    src = x if dt == "f32" else inputs.f32_to_bf16_bits(x)
+    e_ref, s_ref = oracle.quantize(src, axis, fmt, RTZ)
+    e, s = mx.mx_quantize(dev_view(src), axis, fmt, RTZ)
+    assert np.array_equal(to_host(s), s_ref) and np.array_equal(to_host(e), e_ref)
+
+
+@pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("axis,shape", [(1, (203, 416)), (0, (160, 200)), (0, (96, 204)), (0, (64, 203))],
+                         ids=["axis1", "axis0", "axis0_cols_204", "axis0_odd_cols"])
+def test_cast_stochastic(mx, oracle, fmt, dt, axis, shape):
+    """Bit-exact against the reference: same generator, same element numbering, same arithmetic.
+    Column counts that are and are not multiples of 4 take the two ways the axis-0 kernel draws
+    its numbers."""
+    x = inputs.student_t_f32(shape, seed=70 + fmt)
+    src = x if dt == "f32" else inputs.f32_to_bf16_bits(x)
+    check_cast_sr(mx, oracle, src, axis, fmt, seed=0x9E3779B97F4A7C15 + fmt)
+    check_cast_sr(mx, oracle, src, axis, fmt, seed=1)
+
+
+@pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
+@pytest.mark.parametrize("mode", ["rtz", "sr"])
+@pytest.mark.parametrize("axis", [1, 0])
+def test_added_modes_adversarial(mx, oracle, fmt, mode, axis):
+    """All-zero, single-outlier, exact ties, Float32 subnormals, +-Inf, NaN, largest finite, -0 and
+    full-exponent-range blocks under the two added modes."""
+    x = inputs.adversarial_f32(256, 512, seed=4)
+    if axis == 0:
+        x = np.ascontiguousarray(x.T)
+    if mode == "rtz":
+        check_cast(mx, oracle, x, axis, fmt, RTZ)
+    else:
+        check_cast_sr(mx, oracle, x, axis, fmt, seed=77)
+
+
+def test_stochastic_leading_dimension_and_large_index(mx, oracle):
+    """A source view with ld > cols numbers its elements by (row, col), not by address; a tall
+    tensor takes the element counter past 2^25 (64-bit index arithmetic is not exercised below
+    2^32 elements, which would need 8 GiB: the index type is int64 throughout)."""
+    full = inputs.gaussian_f32((128, 160), seed=80)
+    view = to_dev(full)[:, :96]
+    e, s = mx.mx_quantize_sr(view, 1, 0, 5)
+    e_ref, s_ref = oracle.quantize(np.ascontiguousarray(full[:, :96]), 1, 0, SR, seed=5)
+    assert np.array_equal(to_host(e), e_ref) and np.array_equal(to_host(s), s_ref)
+    e, s = mx.mx_quantize_sr(view, 0, 0, 5)
+    e_ref, s_ref = oracle.quantize(np.ascontiguousarray(full[:, :96]), 0, 0, SR, seed=5)
+    assert np.array_equal(to_host(e), e_ref) and np.array_equal(to_host(s), s_ref)
+    tall = inputs.gaussian_bf16((8192, 4160), seed=81)          # 34 M elements
+    for axis in (1, 0):
+        e, s = mx.mx_quantize_sr(to_dev(tall), axis, 4, 9)
+        e_ref, s_ref = oracle.quantize(tall, axis, 4, SR, seed=9)
+        assert np.array_equal(to_host(e), e_ref) and np.array_equal(to_host(s), s_ref)
+
+
+def test_stochastic_is_unbiased_on_the_gpu(mx, oracle):
+    """Mean of dequantized casts over seeds approaches the input; round-to-nearest does not move."""
+    x = inputs.gaussian_f32((64, 256), seed=82)
+    xd = to_dev(x)
+    acc = torch.zeros_like(xd, dtype=torch.float64)
+    n = 64
+    for seed in range(n):
+        e, s = mx.mx_quantize_sr(xd, 1, 4, seed)            # FP4: the coarsest grid
+        acc += mx.mx_dequantize(e, s, 4, 64, 256, 1).double()
+    mean = to_host(acc / n)
+    e, s = mx.mx_quantize(xd, 1, 4, RNE)
+    X = np.exp2(to_host(s).astype(np.float64) - 127).repeat(32, axis=1)
+    target = np.clip(x.astype(np.float64), -6 * X, 6 * X)
+    assert np.all(np.abs(mean - target) <= 5 * 2 * X / (2 * np.sqrt(n)))
+    near = to_host(mx.mx_dequantize(e, s, 4, 64, 256, 1)).astype(np.float64)
+    assert np.abs(mean - target).mean() < 0.5 * np.abs(near - target).mean()
+
+
+def test_gemm_qa_toward_zero(mx, oracle):
+    """mx_gemm_qa with truncation = truncating cast + mx_gemm, on a tiled and on a ragged shape."""
+    for (M, N, K) in ((256, 256, 512), (100, 72, 96)):
+        a = inputs.student_t_bf16((M, K), seed=83)
+        b = inputs.gaussian_f32((N, K), seed=84, std=0.02)
+        for fa in (0, 3, 5):
+            fb = 5 if fa == 5 else 0
+            gb = mx.mx_quantize(to_dev(b), 1, fb)
+            ga = mx.mx_quantize(to_dev(a), 1, fa, RTZ)
+            ea, sa = oracle.quantize(a, 1, fa, RTZ)
+            assert np.array_equal(to_host(ga[0]), ea) and np.array_equal(to_host(ga[1]), sa)
+            C2 = mx.mx_gemm(ga[0], ga[1], fa, gb[0], gb[1], fb, K)
+            C1 = mx.mx_gemm_qa(to_dev(a), fa, RTZ, gb[0], gb[1], fb)
+            assert torch.equal(C1.view(torch.int32), C2.view(torch.int32))
+    with pytest.raises(mx.MxError):
+        mx.mx_gemm_qa(to_dev(a), 0, SR, gb[0], gb[1], 0)
