@@ -16,12 +16,17 @@
 //          row r sits in slot c ^ ((r >> 1) & 7), so the operand reads (rows r ..
 //          r+15, same chunk) touch 16 different 16-byte bank groups.  A lane's
 //          operand is chunks {4s+g, 4s+g+2} of sub-step s.
-//   6-bit: a row is 96 bytes = 8 units of 12 bytes, fetched with 12-byte direct
-//          loads, which still land in 16-byte slots (4 bytes of each stay
-//          unused); unit u of row r sits in slot u ^ (r & 7) -- for the 12-byte
-//          reads this measured fewer bank conflicts than the 8-bit rule -- and a
-//          lane's operand (one MX block, 24 bytes) is units {4s+2g, 4s+2g+1}, read
-//          as two 12-byte reads.
+//   6-bit: a row is 96 bytes = 6 slots and the tile is stored densely, row after
+//          row (slot number 6r + c'), so that it takes 6 wave-wide loads per wave
+//          instead of the 8 that 12-byte pieces in 16-byte slots would need --
+//          the number of load instructions, not their bytes, is what limits this
+//          kernel.  A wave-wide load then covers 10 2/3 rows: lane l of load
+//          number n holds slot 64n + l and works out its row and chunk once.  A
+//          lane's operand (one MX block, 24 bytes at byte 48s + 24g of the row) is
+//          read as three 8-byte pieces.  The 32 rows of an operand read, 96 bytes
+//          apart, would meet in 8 of the 16 bank groups; chunk c of row r sits in
+//          slot c ^ ((r >> 3) & 1) of its row, which spreads them over all 16
+//          (two rows per bank group is the minimum for 8-byte reads of one half).
 //   4-bit: a row is 64 bytes = 4 slots, four rows per bank sweep, slot
 //          c ^ ((r >> 2) & 3); a lane's operand is the single chunk 2s+g.
 // Scale bytes travel the same way, four K steps at a time: a row's scale bytes
@@ -56,7 +61,6 @@ typedef int v8i_t __attribute__((ext_vector_type(8)));
 typedef float v16f_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-typedef uint32_t u32x3_t __attribute__((ext_vector_type(3)));
 
 constexpr int TM = 256, TN = 256, TK = 128;      // work-group tile (TK in elements)
 constexpr int SCL_GROUP = 4;                     // K steps per scale group
@@ -65,36 +69,51 @@ constexpr int SCL_BYTES = (TM + TN) * 4 * SCL_GROUP;   // one group: 16 scale by
 // How an operand of element width W travels through LDS.
 template <int W> struct TileFmt;
 template <> struct TileFmt<8> { static constexpr int ROW = 128, UNIT = 16, RPI = 8; };   // LDS bytes per row, global bytes per
-template <> struct TileFmt<6> { static constexpr int ROW = 128, UNIT = 12, RPI = 8; };   // lane of a direct load, tile rows per
-template <> struct TileFmt<4> { static constexpr int ROW = 64, UNIT = 16, RPI = 16; };   // wave-wide direct load (1 KB of LDS)
+template <> struct TileFmt<6> { static constexpr int ROW = 96, UNIT = 16, RPI = 0; };    // lane of a direct load, tile rows per
+template <> struct TileFmt<4> { static constexpr int ROW = 64, UNIT = 16, RPI = 16; };   // wave-wide direct load (1 KB of LDS;
+                                                                                         // 6-bit: 10 2/3 rows, see above)
 
 // LDS byte offset of 16-byte chunk c (0..7) of tile row r, 8-bit operand
 __device__ __forceinline__ int swz(int r, int c) { return r * 128 + ((c ^ ((r >> 1) & 7)) << 4); }
 
-// Byte offset, inside a tile of width W, of the first LDS slot lane (li, g) reads for sub-step 0 of
-// tile row r (a multiple of 32 rows further down only adds to it).
+// Where lane (li, g) finds its operand of tile row r (a multiple of 32 rows further down only adds
+// a constant).  8- / 4-bit: the byte offset of the first slot for sub-step 0; the other slots follow
+// by XOR.  6-bit: the byte offsets of the three 8-byte pieces of either sub-step.
+template <int W> struct FragOfs { int o; };
+template <> struct FragOfs<6> { int o[2][3]; };
 template <int W>
-__device__ __forceinline__ int frag_ofs(int r, int g)
+__device__ __forceinline__ FragOfs<W> frag_ofs(int r, int g)
 {
-    if (W == 8) return r * 128 + ((g ^ ((r >> 1) & 7)) << 4);
-    if (W == 6) return r * 128 + (((2 * g) ^ (r & 7)) << 4);
-    return r * 64 + ((g ^ ((r >> 2) & 3)) << 4);
+    FragOfs<W> f;
+    if constexpr (W == 8) f.o = r * 128 + ((g ^ ((r >> 1) & 7)) << 4);
+    else if constexpr (W == 4) f.o = r * 64 + ((g ^ ((r >> 2) & 3)) << 4);
+    else {
+#pragma unroll
+        for (int s = 0; s < 2; s++)
+#pragma unroll
+            for (int k = 0; k < 3; k++) {
+                const int t = 48 * s + 24 * g + 8 * k;          // byte of the row
+                f.o[s][k] = r * 96 + (((t >> 4) ^ ((r >> 3) & 1)) << 4) + (t & 8);
+            }
+    }
+    return f;
 }
 
 // One operand fragment: tile row block x (32 rows each), sub-step sub, from the tile at buf.
 template <int W>
-__device__ __forceinline__ v8i_t read_frag(const uint8_t *buf, int ofs0, int sub, int x)
+__device__ __forceinline__ v8i_t read_frag(const uint8_t *buf, const FragOfs<W> &f, int sub, int x)
 {
     if constexpr (W == 8) {
-        const uint4 lo = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 6)) + x * 4096);
-        const uint4 hi = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 6) ^ 32) + x * 4096);
+        const uint4 lo = *reinterpret_cast<const uint4 *>(buf + (f.o ^ (sub << 6)) + x * 4096);
+        const uint4 hi = *reinterpret_cast<const uint4 *>(buf + (f.o ^ (sub << 6) ^ 32) + x * 4096);
         return v8i_t{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
     } else if constexpr (W == 6) {
-        const u32x3_t lo = *reinterpret_cast<const u32x3_t *>(buf + (ofs0 ^ (sub << 6)) + x * 4096);
-        const u32x3_t hi = *reinterpret_cast<const u32x3_t *>(buf + (ofs0 ^ (sub << 6) ^ 16) + x * 4096);
-        return v8i_t{(int)lo[0], (int)lo[1], (int)lo[2], (int)hi[0], (int)hi[1], (int)hi[2], 0, 0};
+        const uint2 p0 = *reinterpret_cast<const uint2 *>(buf + f.o[sub][0] + x * 3072);
+        const uint2 p1 = *reinterpret_cast<const uint2 *>(buf + f.o[sub][1] + x * 3072);
+        const uint2 p2 = *reinterpret_cast<const uint2 *>(buf + f.o[sub][2] + x * 3072);
+        return v8i_t{(int)p0.x, (int)p0.y, (int)p1.x, (int)p1.y, (int)p2.x, (int)p2.y, 0, 0};
     } else {
-        const uint4 lo = *reinterpret_cast<const uint4 *>(buf + (ofs0 ^ (sub << 5)) + x * 2048);
+        const uint4 lo = *reinterpret_cast<const uint4 *>(buf + (f.o ^ (sub << 5)) + x * 2048);
         return v8i_t{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, 0, 0, 0, 0};
     }
 }
@@ -111,8 +130,15 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     typedef TileFmt<WA> TA;
     typedef TileFmt<WB> TB;
     constexpr int A_BYTES = TM * TA::ROW, B_BYTES = TN * TB::ROW, STAGE_BYTES = A_BYTES + B_BYTES;
-    // {A tile, B tile} x two stages, then {A scale dwords, B scale dwords} x two stages
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * STAGE_BYTES + 2 * SCL_BYTES];
+    // Stages in flight.  A stage is requested NSTAGE - 1 steps before it is read.  With 6- / 4-bit
+    // operands a step holds only 1024 clocks of matrix instructions, less than the latency of a
+    // load under this traffic, so two stages leave the matrix pipe waiting for memory every step;
+    // wherever three stages fit in the 160 KB of LDS, three are used.
+    // (measured: +9 % for a 6-bit x 4-bit pair, +1.5 % for 4 x 4; an 8-bit operand brings enough
+    // matrix work per step, and such pairs ran 7 % slower with three stages)
+    constexpr int NSTAGE = (!QA && WA < 8 && WB < 8 && 3 * STAGE_BYTES + 2 * SCL_BYTES <= 160 * 1024) ? 3 : 2;
+    // {A tile, B tile} x NSTAGE stages, then {A scale dwords, B scale dwords} x two groups
+    __shared__ __attribute__((aligned(16))) uint8_t lds[NSTAGE * STAGE_BYTES + 2 * SCL_BYTES];
     constexpr int HA = hw_fmt(FA), HB = hw_fmt(FB);   // must reach the builtin as literal constants
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -151,12 +177,24 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     // covers rows (4j + w) * RPI .. + RPI-1.  Lane l writes slot l % S of row l / S of that group
     // (S slots per row) and therefore fetches the unit that the layout keeps in that slot.
     // (tile row of the lane = a multiple of 32 rows + wave * RPI + a_r, which fixes the swizzle term)
+    // (6-bit tiles are dense: lane l of the wave's load j holds slot (4j + wave) * 64 + l = 6 * row + c',
+    // and fetches chunk c' ^ ((row >> 3) & 1) of that row; its byte offset from the tile's first row
+    // differs from load to load, one register each)
     const int a_r = WA == 4 ? lane >> 2 : lane >> 3, b_r = WB == 4 ? lane >> 2 : lane >> 3;
-    const int a_u = WA == 4 ? (lane & 3) ^ ((a_r >> 2) & 3) : WA == 6 ? (lane & 7) ^ a_r : (lane & 7) ^ (((wave * 8 + a_r) >> 1) & 7);
-    const int b_u = WB == 4 ? (lane & 3) ^ ((b_r >> 2) & 3) : WB == 6 ? (lane & 7) ^ b_r : (lane & 7) ^ (((wave * 8 + b_r) >> 1) & 7);
+    const int a_u = WA == 4 ? (lane & 3) ^ ((a_r >> 2) & 3) : (lane & 7) ^ (((wave * 8 + a_r) >> 1) & 7);
+    const int b_u = WB == 4 ? (lane & 3) ^ ((b_r >> 2) & 3) : (lane & 7) ^ (((wave * 8 + b_r) >> 1) & 7);
     const int64_t a_row_bytes = K * WA / 8, b_row_bytes = K * WB / 8;
-    const uint8_t *gA = QA ? nullptr : Ae + (m0 + wave * TA::RPI + a_r) * a_row_bytes + a_u * TA::UNIT;
-    const uint8_t *gB = Be + (n0 + wave * TB::RPI + b_r) * b_row_bytes + b_u * TB::UNIT;
+    const uint8_t *gA = QA ? nullptr : WA == 6 ? Ae + m0 * a_row_bytes : Ae + (m0 + wave * TA::RPI + a_r) * a_row_bytes + a_u * TA::UNIT;
+    const uint8_t *gB = WB == 6 ? Be + n0 * b_row_bytes : Be + (n0 + wave * TB::RPI + b_r) * b_row_bytes + b_u * TB::UNIT;
+    uint32_t a6[6] = {}, b6[6] = {};
+    if (WA == 6 || WB == 6) {
+#pragma unroll
+        for (int j = 0; j < 6; j++) {
+            const uint32_t q = (uint32_t)((4 * j + wave) * 64 + lane), row = q / 6, c = (q - row * 6) ^ ((row >> 3) & 1);
+            if (WA == 6) a6[j] = row * (uint32_t)a_row_bytes + c * 16;
+            if (WB == 6) b6[j] = row * (uint32_t)b_row_bytes + c * 16;
+        }
+    }
     const int st_l = wave * 1024;                  // LDS offset of this wave's 1 KB slot within a 4 KB group
     // ---- scale staging: wave w fetches the dwords of rows 64w .. 64w+63 of A and of B
     const uint8_t *sA = As + (m0 + wave * 64 + lane) * nkb;
@@ -164,7 +202,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     // ---- scale reads: dword of tile row wm*128 + 32x + li (A) / wn*128 + 32y + li (B)
     const int rsa = (wm * 128 + li) * 16, rsb = TM * 16 + (wn * 128 + li) * 16;
     // ---- operand read offsets inside a stage's tile (sub-step 0, row block 0)
-    const int ra0 = frag_ofs<WA>(wm * 128 + li, g), rb0 = frag_ofs<WB>(wn * 128 + li, g);
+    const FragOfs<WA> ra0 = frag_ofs<WA>(wm * 128 + li, g);
+    const FragOfs<WB> rb0 = frag_ofs<WB>(wn * 128 + li, g);
 
     v16f_t acc[4][4];
 #pragma unroll
@@ -193,18 +232,18 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     // about (it cannot tell that the two stage buffers never overlap), which serialises the whole
     // pipeline.  Here the only consumer-side wait is the explicit vmcnt(0) before the barrier.
     // M0 carries the wave-uniform LDS destination; lane l lands at destination + 16 * l.
-    constexpr int NJA = QA ? 0 : TM / (4 * TA::RPI), NJB = TN / (4 * TB::RPI);   // direct loads per wave per stage
+    constexpr int NJA = QA ? 0 : A_BYTES / 4096, NJB = B_BYTES / 4096;   // direct loads per wave per stage (1 KB each)
     auto stage_a1 = [&](int ts, uint8_t *dst, int j) {
         const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
-        const uint8_t *gp = gA + (int64_t)ts * (TK * WA / 8) + j * (4 * TA::RPI) * a_row_bytes;
-        if (WA == 6) asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx3 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
-        else asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
+        const uint8_t *gp = WA == 6 ? gA + (int64_t)ts * (TK * WA / 8) + a6[j < 6 ? j : 0]
+                                    : gA + (int64_t)ts * (TK * WA / 8) + j * (4 * TA::RPI) * a_row_bytes;
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
     };
     auto stage_b1 = [&](int ts, uint8_t *dst, int j) {
         const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
-        const uint8_t *gp = gB + (int64_t)ts * (TK * WB / 8) + j * (4 * TB::RPI) * b_row_bytes;
-        if (WB == 6) asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx3 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
-        else asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
+        const uint8_t *gp = WB == 6 ? gB + (int64_t)ts * (TK * WB / 8) + b6[j < 6 ? j : 0]
+                                    : gB + (int64_t)ts * (TK * WB / 8) + j * (4 * TB::RPI) * b_row_bytes;
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gp), "s"(l0 + j * 4096) : "m0");
     };
     auto stage_a = [&](int ts, uint8_t *dst) {
 #pragma unroll
@@ -221,7 +260,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
         if (k < NJA) stage_a1(ts, dstA, k);
         else if (k - NJA < NJB) stage_b1(ts, dstB, k - NJA);
     };
-    uint8_t *const scl = lds + 2 * STAGE_BYTES;
+    uint8_t *const scl = lds + NSTAGE * STAGE_BYTES;
     const int n_groups = (T + SCL_GROUP - 1) / SCL_GROUP;
     // Byte offset, inside a row's 16-byte LDS slot, of the scale dword of K step ts.  The partial
     // last group is loaded as the row's LAST 16 scale bytes (steps T-4 .. T-1), so that the load
@@ -295,8 +334,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     _Pragma("unroll") for (int x = 0; x < 4; x++)                                                                     \
         acc[x][Y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(AF[x], BF, acc[x][Y], HA, HB, OPS, (int)sa[x], OPS, (int)sb[Y])
 
-    // ---- prologue: stage 0 (and the first scale group), then stage 1, on their way to LDS; the
-    // first half step only needs stage 0, so stage 1 may stay in flight until the first barrier
+    // ---- prologue: stage 0 (and the first scale group), then stages 1 .. NSTAGE-1, on their way
+    // to LDS; the first half step only needs stage 0, so the others may stay in flight
     stage_b(0, lds + A_BYTES);
     stage_scales(0);
     {
@@ -305,7 +344,12 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
             stage_a(0, lds);
             stage_a(t1, lds + STAGE_BYTES);
             stage_b(t1, lds + STAGE_BYTES + A_BYTES);
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NJA + NJB) : "memory");   // all but the loads of stage 1
+            if (NSTAGE == 3) {
+                const int t2 = T > 2 ? 2 : T - 1;
+                stage_a(t2, lds + 2 * STAGE_BYTES);
+                stage_b(t2, lds + 2 * STAGE_BYTES + A_BYTES);
+            }
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 1) * (NJA + NJB)) : "memory");   // all but the later stages
         } else {
             stage_b(t1, lds + STAGE_BYTES + A_BYTES);
 #pragma unroll
@@ -327,12 +371,14 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     // four K steps (one scale group) per trip, so that the scale request sits in a fixed place of
     // straight-line code (a branch inside the step would undo the interleaving)
     // (the body is a lambda so that the partial last group can run it with a run-time step index)
+    int ring = 0;   // three stages: buffer of the current step (wave-uniform, run-time)
     auto k_step = [&](const int tt, const int h) __attribute__((always_inline)) {
         const int t = tt + h;
-        uint8_t *bufA = lds + (h & 1) * STAGE_BYTES;
-        uint8_t *nxt = lds + ((h & 1) ^ 1) * STAGE_BYTES;
+        const int cur = NSTAGE == 2 ? (h & 1) : ring;
+        uint8_t *bufA = lds + cur * STAGE_BYTES;
+        uint8_t *nxt = lds + (NSTAGE == 2 ? (cur ^ 1) : (cur == 2 ? 0 : cur + 1)) * STAGE_BYTES;
         uint8_t *bufB = bufA + A_BYTES;
-        const int t2 = t + 2 < T ? t + 2 : T - 1;
+        const int t2 = t + NSTAGE < T ? t + NSTAGE : T - 1;   // the stage requested during this step
         MX_FENCE();
 
         // ---- X: the 16 matrix instructions of sub-step 0; meanwhile all fragments of sub-step 1
@@ -356,14 +402,17 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
         MX_MFMA4(a0, b0[3], 3, 0);
         if (QA) qa_commit(t + 1, 3, nxt);
         MX_FENCE();
-        // Stage t+1 (requested one step ago) must be in LDS, and every wave must have issued its
-        // last read of stage t, before the buffers change roles.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // Stage t+1 must be in LDS, and every wave must have issued its last read of stage t,
+        // before the buffers change roles.  With three stages the loads issued during the previous
+        // step (stage t+2: NJA + NJB of them, and at most the two scale loads in their midst, which
+        // this count then forces to land early) may stay in flight: loads complete in order.
+        if (NSTAGE == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NJA + NJB) : "memory");
         __syncthreads();
         MX_FENCE();
 
-        // ---- Y: the 16 matrix instructions of sub-step 1; meanwhile stage t+2 is requested into
-        // the buffer stage t just vacated and the sub-step-0 fragments of stage t+1 are read
+        // ---- Y: the 16 matrix instructions of sub-step 1; meanwhile stage t+NSTAGE is requested
+        // into the buffer stage t just vacated and the sub-step-0 fragments of stage t+1 are read
 #define MX_Y_GROUP(GRP, READ0, READ1, BF, Y)                                                                             \
     stage_one(4 * GRP + 0, t2, bufA, bufB); READ0; MX_MFMA1(a1, BF, 0, Y, 2); MX_FENCE();                                   \
     stage_one(4 * GRP + 1, t2, bufA, bufB);        MX_MFMA1(a1, BF, 1, Y, 2); MX_FENCE();                                   \
@@ -381,6 +430,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
         // the next step's scales were read two groups ago (their LDS latency is long past)
 #pragma unroll
         for (int x = 0; x < 4; x++) { sa[x] = sa_n[x]; sb[x] = sb_n[x]; }
+        if (NSTAGE == 3) ring = ring == 2 ? 0 : ring + 1;
         MX_FENCE();
     };
     for (int tt = 0; tt < Tfull; tt += SCL_GROUP) {

@@ -9,7 +9,8 @@ hipError_t launch_gemm_tiled_a4(const TileArgs &a, int, int fmtB) { return launc
 bool gemm_tiled_applies(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB)
 {
     return fmtA >= FP8_E4M3 && fmtA <= FP4_E2M1 && fmtB >= FP8_E4M3 && fmtB <= FP4_E2M1 && M % TM == 0 && N % TN == 0 &&
-           K % TK == 0 && K >= TK * SCL_GROUP && M > 0 && N > 0 && (M / TM) * (N / TN) <= (1 << 24);
+           K % TK == 0 && K >= TK * SCL_GROUP && K <= (1 << 23) /* 32-bit byte offsets inside a tile */ && M > 0 && N > 0 &&
+           (M / TM) * (N / TN) <= (1 << 24);
 }
 
 bool gemm_tiled_fuses_cast(int fmtA, int fmtB) { return fmtA <= FP8_E5M2 && fmtB <= FP8_E5M2; }
