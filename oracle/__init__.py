@@ -130,8 +130,9 @@ def quantize(src, axis, fmt, rnd=ROUND_RNE, seed=None):
     rows, cols = src.shape
     n_out, length = (rows, cols) if axis == 1 else (cols, rows)
     w = elem_bits(fmt)
-    elems = np.zeros((n_out, length * w // 8), dtype=np.uint8)
-    scales = np.zeros((n_out, length // BLOCK), dtype=np.uint8)
+    nblk = -(-length // BLOCK)          # a partial last block is stored whole (zero fill)
+    elems = np.zeros((n_out, nblk * BLOCK * w // 8), dtype=np.uint8)
+    scales = np.zeros((n_out, nblk), dtype=np.uint8)
     if (rnd == ROUND_STOCHASTIC) != (seed is not None):
         raise ValueError("a seed goes with the stochastic mode and with no other")
     st = lib().mxo_quantize_seeded(_ptr(src), _src_dt(src), rows, cols, cols, axis, fmt, rnd,

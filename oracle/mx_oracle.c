@@ -353,12 +353,13 @@ static unsigned get_code(const uint8_t *row, int64_t j, int w)
     return code;
 }
 
+/* The block axis may have any length: the last block of a line is then filled
+ * up with zeros (which neither move the block maximum nor produce a non-zero
+ * code), and the stored line holds whole blocks. */
 static int shape_ok(int64_t rows, int64_t cols, int axis)
 {
     if (rows <= 0 || cols <= 0) return 0;
-    if (axis == 1) return cols % MXO_BLOCK == 0;
-    if (axis == 0) return rows % MXO_BLOCK == 0;
-    return 0;
+    return axis == 0 || axis == 1;
 }
 
 int mxo_quantize(const void *src, int src_dt, int64_t rows, int64_t cols,
@@ -384,8 +385,8 @@ int mxo_quantize_seeded(const void *src, int src_dt, int64_t rows, int64_t cols,
      * l = position along the block axis */
     int64_t n_out = axis == 1 ? rows : cols;
     int64_t len = axis == 1 ? cols : rows;
-    int64_t row_bytes = len * w / 8;
-    int64_t nblk = len / MXO_BLOCK;
+    int64_t nblk = (len + MXO_BLOCK - 1) / MXO_BLOCK;
+    int64_t row_bytes = nblk * MXO_BLOCK * w / 8;
 
 #pragma omp parallel for schedule(static)
     for (int64_t o = 0; o < n_out; o++) {
@@ -396,6 +397,7 @@ int mxo_quantize_seeded(const void *src, int src_dt, int64_t rows, int64_t cols,
             for (int i = 0; i < MXO_BLOCK; i++) {
                 int64_t l = b * MXO_BLOCK + i;
                 int64_t row = axis == 1 ? o : l, col = axis == 1 ? l : o;
+                if (l >= len) { v[i] = 0.0; u[i] = 0.0; continue; } /* fill */
                 v[i] = load_scalar(src, src_dt, row * ld + col);
                 u[i] = rnd == MXO_ROUND_STOCHASTIC
                            ? mxo_sr_uniform(seed, row * cols + col) : 0.0;
@@ -457,8 +459,8 @@ int mxo_dequantize(const uint8_t *elems, const uint8_t *scales, int fmt,
     int w = FMT[fmt].bits;
     int64_t n_out = axis == 1 ? rows : cols;
     int64_t len = axis == 1 ? cols : rows;
-    int64_t row_bytes = len * w / 8;
-    int64_t nblk = len / MXO_BLOCK;
+    int64_t nblk = (len + MXO_BLOCK - 1) / MXO_BLOCK;
+    int64_t row_bytes = nblk * MXO_BLOCK * w / 8; /* whole blocks are stored */
 
 #pragma omp parallel for schedule(static)
     for (int64_t o = 0; o < n_out; o++) {

@@ -104,7 +104,11 @@ double mxo_sr_uniform(uint64_t seed, int64_t e);
  * axis = 0: blocks of 32 along dimension 0, output written as the cast of the
  *           transpose: elems [cols][rows*bits/8], scales [cols][rows/32].
  * Elements are densely bit-packed little-endian: element j of an output row
- * occupies bits [j*w, (j+1)*w) of that row's byte string. */
+ * occupies bits [j*w, (j+1)*w) of that row's byte string.
+ * The block axis may have any length L: the paper does not say what happens to
+ * a last, partial block; here it is filled up with zeros, and every stored row
+ * holds ceil(L/32) whole blocks (elems [..][ceil(L/32)*32*bits/8], scales
+ * [..][ceil(L/32)]; the fill positions hold code 0). */
 int mxo_quantize(const void *src, int src_dt, int64_t rows, int64_t cols,
                  int64_t ld, int axis, int fmt, int rnd,
                  uint8_t *elems_out, uint8_t *scales_out);
@@ -116,7 +120,9 @@ int mxo_quantize_seeded(const void *src, int src_dt, int64_t rows, int64_t cols,
                         uint8_t *elems_out, uint8_t *scales_out);
 
 /* Inverse: v = X * P (Section 2), X = NaN makes the whole block NaN, results
- * beyond Float32 range become +-Inf.  Writes row-major [rows, cols]. */
+ * beyond Float32 range become +-Inf.  Writes row-major [rows, cols]; with a
+ * block-axis length that is not a multiple of 32 the stored rows hold whole
+ * blocks (as mxo_quantize writes them) and the fill positions are skipped. */
 int mxo_dequantize(const uint8_t *elems, const uint8_t *scales, int fmt,
                    int64_t rows, int64_t cols, int axis,
                    void *dst, int dst_dt, int64_t ld);

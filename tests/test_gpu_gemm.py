@@ -620,3 +620,37 @@ def test_ragged_shapes_with_a_tiled_interior(mx, oracle, shape, fa, fb):
     check_gemm(to_host(C), C_ref, C_abs, f"ragged {shape}", hw_term_for(oracle, ea, sa, fa, eb, sb, fb, K))
     Cq = mx.mx_gemm_qa(to_dev(a), fa, RNE, to_dev(eb), to_dev(sb), fb)
     assert torch.equal(C.view(torch.int32), Cq.view(torch.int32))
+
+
+def test_calls_on_a_side_stream(mx, oracle):
+    """Every entry point enqueues on the stream it is given (workspaces included: they come from
+    and go back to the memory pool in that stream's order).  A chain of calls on a side stream,
+    with no synchronisation between them, must give what the same chain gives on the default
+    stream -- for the routes with a workspace (two-pass quantize-on-load, MXINT8 split) too."""
+    M, N, K = 2048, 2048, 512
+    a = to_dev(inputs.student_t_bf16((M, K), seed=150))
+    b = to_dev(inputs.gaussian_f32((N, K), seed=151, std=0.02))
+
+    def chain(stream):
+        out = []
+        for fa, fb in ((0, 0), (2, 4), (5, 5)):
+            gb = mx.mx_quantize(b, 1, fb, stream=stream)
+            ga = mx.mx_quantize(a, 1, fa, 1, stream=stream)
+            out.append(mx.mx_gemm(ga[0], ga[1], fa, gb[0], gb[1], fb, K, dtype=torch.bfloat16, stream=stream))
+            out.append(mx.mx_gemm_qa(a, fa, 1, gb[0], gb[1], fb, dtype=torch.bfloat16, stream=stream))
+            out.append(mx.mx_dequantize(ga[0], ga[1], fa, M, K, 1, dtype=torch.bfloat16, stream=stream))
+        d1, d0 = mx.mx_quantize_dual(a, 3, stream=stream)
+        out += [d1[0], d1[1], d0[0], d0[1]]
+        out += list(mx.mx_quantize_sr(a, 0, 1, 11, stream=stream))
+        return out
+
+    ref = chain(None)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        got = chain(side)
+    side.synchronize()
+    for i, (x, y) in enumerate(zip(ref, got)):
+        assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), i
+    assert torch.equal(ref[0], ref[1]) and torch.equal(ref[6], ref[7])     # quantize-on-load = cast + GEMM
