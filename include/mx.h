@@ -73,16 +73,18 @@ typedef enum {
     MX_OK = 0,
     MX_ERR_NULL = 1,        /* a required pointer is NULL                        */
     MX_ERR_ENUM = 2,        /* format / rounding / dtype / axis out of range     */
-    MX_ERR_SHAPE = 3,       /* negative size, block axis not a multiple of 32,
-                               leading dimension smaller than the row length   */
+    MX_ERR_SHAPE = 3,       /* negative size, leading dimension smaller than the
+                               row length, block axis not a multiple of 32
+                               where whole blocks are required (GEMM K, dual cast) */
     MX_ERR_ALIGN = 4,       /* pointer or leading dimension not 16-byte aligned  */
     MX_ERR_UNSUPPORTED = 5, /* MX_INT8 paired with another format in a GEMM      */
     MX_ERR_LAUNCH = 6       /* the HIP runtime refused the launch                */
 } mx_status_t;
 
-/* Size in bytes of the elems array for a [rows, cols] source cast along axis. */
+/* Size in bytes of the elems array for a [rows, cols] source cast along axis:
+ * lines * ceil(L/32) * 32*bits/8 with L the block-axis length. */
 size_t mx_elem_bytes(mx_format_t fmt, int64_t rows, int64_t cols, int axis);
-/* Size in bytes of the scales array (rows*cols/32). */
+/* Size in bytes of the scales array: lines * ceil(L/32). */
 size_t mx_scale_bytes(int64_t rows, int64_t cols, int axis);
 
 /*
@@ -99,7 +101,13 @@ size_t mx_scale_bytes(int64_t rows, int64_t cols, int axis);
  *              MX_ERR_ENUM here: see mx_quantize_sr)
  *   elems_out  device, mx_elem_bytes() bytes, 16-byte aligned
  *   scales_out device, mx_scale_bytes() bytes, 16-byte aligned
- * The length of the block axis must be a multiple of 32.
+ * The block axis may have any length L.  The paper defines the cast on whole
+ * blocks only; here a partial last block is filled up with zeros (they neither
+ * move the block maximum nor give a non-zero code) and every stored line holds
+ * ceil(L/32) whole blocks: elems [..][ceil(L/32)*32*bits/8], scales
+ * [..][ceil(L/32)], which is what mx_elem_bytes / mx_scale_bytes return.  Such
+ * a tensor is a valid mx_gemm operand with K = 32*ceil(L/32): the fill adds 0.
+ * (Whole blocks take the fast kernels; a ragged length takes the generic one.)
  * Per block: scale byte = clamp(floor(log2 max|V|) - emax_elem + 127, 0, 254)
  * over the normal finite inputs (0 if there are none); Float32-subnormal inputs
  * give P = 0; finite values beyond the largest normal clamp to it with their
@@ -151,7 +159,9 @@ int mx_quantize_dual(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t c
  * v = X * P (Section 2) for an MX tensor produced by mx_quantize with the same
  * rows, cols and axis; writes row-major dst [rows, cols] with leading
  * dimension ld (elements).  Scale byte 0xFF gives NaN for the whole block;
- * |X*P| beyond Float32 range gives +-Inf.  Pointers 16-byte aligned.
+ * |X*P| beyond Float32 range gives +-Inf.  Pointers 16-byte aligned.  With a
+ * block-axis length that is not a multiple of 32 the fill positions of the
+ * last block are skipped.
  */
 int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt,
                   int64_t rows, int64_t cols, int axis,

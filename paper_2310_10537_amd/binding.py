@@ -98,10 +98,11 @@ def mx_quantize(src, axis, fmt, rnd=ROUND_RNE, elems_out=None, scales_out=None, 
     ld = src.stride(0) if rows > 1 else cols
     n_out, length = (rows, cols) if axis == 1 else (cols, rows)
     w = FORMAT_BITS[fmt] if 0 <= fmt < 6 else 8
+    nblk = -(-length // BLOCK)      # a partial last block is stored whole
     if elems_out is None:
-        elems_out = torch.empty((n_out, length * w // 8), dtype=torch.uint8, device=src.device)
+        elems_out = torch.empty((n_out, nblk * BLOCK * w // 8), dtype=torch.uint8, device=src.device)
     if scales_out is None:
-        scales_out = torch.empty((n_out, length // BLOCK), dtype=torch.uint8, device=src.device)
+        scales_out = torch.empty((n_out, nblk), dtype=torch.uint8, device=src.device)
     _check(lib().mx_quantize(src.data_ptr(), _dt(src), rows, cols, ld, axis, fmt, rnd,
                              elems_out.data_ptr(), scales_out.data_ptr(), _stream(stream)))
     return elems_out, scales_out
@@ -116,10 +117,11 @@ def mx_quantize_sr(src, axis, fmt, seed, elems_out=None, scales_out=None, stream
     ld = src.stride(0) if rows > 1 else cols
     n_out, length = (rows, cols) if axis == 1 else (cols, rows)
     w = FORMAT_BITS[fmt] if 0 <= fmt < 6 else 8
+    nblk = -(-length // BLOCK)      # a partial last block is stored whole
     if elems_out is None:
-        elems_out = torch.empty((n_out, length * w // 8), dtype=torch.uint8, device=src.device)
+        elems_out = torch.empty((n_out, nblk * BLOCK * w // 8), dtype=torch.uint8, device=src.device)
     if scales_out is None:
-        scales_out = torch.empty((n_out, length // BLOCK), dtype=torch.uint8, device=src.device)
+        scales_out = torch.empty((n_out, nblk), dtype=torch.uint8, device=src.device)
     _check(lib().mx_quantize_sr(src.data_ptr(), _dt(src), rows, cols, ld, axis, fmt, int(seed) & (2 ** 64 - 1),
                                 elems_out.data_ptr(), scales_out.data_ptr(), _stream(stream)))
     return elems_out, scales_out

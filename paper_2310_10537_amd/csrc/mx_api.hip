@@ -14,13 +14,16 @@ bool rnd_ok(int r) { return r == MX_ROUND_RNE || r == MX_ROUND_HALF_AWAY || r ==
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 int esize(int dt) { return dt == MX_DT_BF16 ? 2 : 4; }
 
-int tensor_shape_status(int64_t rows, int64_t cols, int axis, int64_t ld)
+// whole_blocks: the block axis must be a multiple of 32 (entry points without a partial-block path)
+int tensor_shape_status(int64_t rows, int64_t cols, int axis, int64_t ld, bool whole_blocks = false)
 {
     if (rows < 0 || cols < 0) return MX_ERR_SHAPE;
-    if ((axis == 1 ? cols : rows) % mx::BLOCK) return MX_ERR_SHAPE;
+    if (whole_blocks && (axis == 1 ? cols : rows) % mx::BLOCK) return MX_ERR_SHAPE;
     if (ld < cols) return MX_ERR_SHAPE;
     return MX_OK;
 }
+
+int64_t blocks_of(int64_t len) { return (len + mx::BLOCK - 1) / mx::BLOCK; }
 
 }  // namespace
 
@@ -28,16 +31,16 @@ extern "C" {
 
 size_t mx_elem_bytes(mx_format_t fmt, int64_t rows, int64_t cols, int axis)
 {
-    (void)axis;
-    if (!fmt_ok(fmt) || rows < 0 || cols < 0) return 0;
-    return (size_t)rows * (size_t)cols * (size_t)mx::fmt_bits(fmt) / 8;
+    if (!fmt_ok(fmt) || rows < 0 || cols < 0 || (axis != 0 && axis != 1)) return 0;
+    const int64_t lines = axis == 1 ? rows : cols, len = axis == 1 ? cols : rows;
+    return (size_t)lines * (size_t)blocks_of(len) * (size_t)(mx::BLOCK * mx::fmt_bits(fmt) / 8);
 }
 
 size_t mx_scale_bytes(int64_t rows, int64_t cols, int axis)
 {
-    (void)axis;
-    if (rows < 0 || cols < 0) return 0;
-    return (size_t)rows * (size_t)cols / mx::BLOCK;
+    if (rows < 0 || cols < 0 || (axis != 0 && axis != 1)) return 0;
+    const int64_t lines = axis == 1 ? rows : cols, len = axis == 1 ? cols : rows;
+    return (size_t)lines * (size_t)blocks_of(len);
 }
 
 static int quantize_common(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t cols, int64_t ld, int axis,
@@ -73,8 +76,8 @@ int mx_quantize_dual(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t c
                      void *hip_stream)
 {
     if (!fmt_ok(fmt) || !dt_ok(src_dt) || !rnd_ok(rnd)) return MX_ERR_ENUM;
-    if (int st = tensor_shape_status(rows, cols, 1, ld)) return st;
-    if (int st = tensor_shape_status(rows, cols, 0, ld)) return st;
+    if (int st = tensor_shape_status(rows, cols, 1, ld, true)) return st;
+    if (int st = tensor_shape_status(rows, cols, 0, ld, true)) return st;
     if (rows == 0 || cols == 0) return MX_OK;
     if (!src || !elems_axis1 || !scales_axis1 || !elems_axis0 || !scales_axis0) return MX_ERR_NULL;
     if (!aligned16(src) || !aligned16(elems_axis1) || !aligned16(scales_axis1) || !aligned16(elems_axis0) ||

@@ -42,6 +42,19 @@ __device__ __forceinline__ void load_as_f32_bits(const void *p, uint32_t (&v)[N]
     }
 }
 
+// The first n (< N) of N consecutive elements, one by one; the rest read as zero (the fill of a
+// partial last block).
+template <int SRC, int N>
+__device__ __forceinline__ void load_head_as_f32_bits(const void *p, int n, uint32_t (&v)[N])
+{
+#pragma unroll
+    for (int i = 0; i < N; i++) {
+        uint32_t x = 0;
+        if (i < n) x = SRC == DT_BF16 ? (uint32_t)reinterpret_cast<const uint16_t *>(p)[i] << 16 : reinterpret_cast<const uint32_t *>(p)[i];
+        v[i] = x;
+    }
+}
+
 struct __attribute__((packed, aligned(4))) dword3 { uint32_t a, b, c; };
 
 // store ND dwords to a pointer aligned to min(16, largest power of two dividing 4*ND)
@@ -82,10 +95,12 @@ __device__ __forceinline__ void encode_lane(const uint32_t (&v)[N], uint32_t s, 
 
 // ---------------------------------------------------------------------------
 // Row cast.  unit = one lane-iteration = EPL elements; units are numbered in
-// row-major order over the tensor, so unit u belongs to block u / G.
+// row-major order over the tensor with its rows filled up to whole blocks
+// (pcols columns), so unit u belongs to block u / G.  Elements at or beyond
+// cols read as zero.
 // ---------------------------------------------------------------------------
 template <int SRC, int FMT, int RND, int EPL>
-__global__ __launch_bounds__(256) void cast_row_kernel(const void *__restrict__ src, int64_t cols, int64_t ld,
+__global__ __launch_bounds__(256) void cast_row_kernel(const void *__restrict__ src, int64_t cols, int64_t pcols, int64_t ld,
                                                        uint8_t *__restrict__ elems, uint8_t *__restrict__ scales,
                                                        int64_t n_units, uint64_t seed)
 {
@@ -94,21 +109,33 @@ __global__ __launch_bounds__(256) void cast_row_kernel(const void *__restrict__ 
     constexpr int esz = SRC == DT_BF16 ? 2 : 4;
     constexpr int ND = EPL * w / 32;
     const int64_t stride = (int64_t)gridDim.x * 256;
-    const int64_t units_per_row = cols / EPL;
-    const bool flat = (ld == cols);
+    const int64_t units_per_row = pcols / EPL;
+    const bool flat = (ld == cols && cols == pcols);
 
     for (int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x; u < n_units; u += stride) {
-        int64_t off;  // element offset of this lane's first element
+        int64_t off;     // element offset of this lane's first element in the source
+        int64_t e0;      // its number in the tensor, row * cols + col
+        int n_valid = EPL;
         if (flat) {
-            off = u * EPL;
+            off = e0 = u * EPL;
         } else {
-            int64_t r = u / units_per_row;
-            off = r * ld + (u - r * units_per_row) * EPL;
+            const int64_t r = u / units_per_row, c0 = (u - r * units_per_row) * EPL;
+            off = r * ld + c0;
+            e0 = r * cols + c0;
+            n_valid = cols - c0 >= EPL ? EPL : cols - c0 > 0 ? (int)(cols - c0) : 0;
         }
         uint32_t rr[EPL] = {};
-        if (RND == ROUND_STOCHASTIC) sr_offsets_run<EPL>(seed, u * EPL, rr);   // u * EPL = row * cols + col
+        if (RND == ROUND_STOCHASTIC) {
+            if ((cols & 3) == 0) {
+                sr_offsets_run<EPL>(seed, e0, rr);      // e0 is a multiple of 4: one generator call per 4 elements
+            } else {
+#pragma unroll
+                for (int i = 0; i < EPL; i++) rr[i] = sr_offset(seed, e0 + i);
+            }
+        }
         uint32_t v[EPL];
-        load_as_f32_bits<SRC, EPL>(reinterpret_cast<const char *>(src) + off * esz, v);
+        if (n_valid == EPL) load_as_f32_bits<SRC, EPL>(reinterpret_cast<const char *>(src) + off * esz, v);
+        else load_head_as_f32_bits<SRC, EPL>(reinterpret_cast<const char *>(src) + off * esz, n_valid, v);
 
         uint32_t amax = 0;
 #pragma unroll
@@ -173,9 +200,10 @@ __global__ __launch_bounds__(256) void cast_col_simple_kernel(const void *__rest
     uint32_t v[BLOCK];
 #pragma unroll
     for (int i = 0; i < BLOCK; i++) {
-        int64_t idx = (rb * BLOCK + i) * ld + c;
-        if (SRC == DT_BF16) v[i] = (uint32_t)reinterpret_cast<const uint16_t *>(src)[idx] << 16;
-        else v[i] = reinterpret_cast<const uint32_t *>(src)[idx];
+        const int64_t row = rb * BLOCK + i, idx = row * ld + c;
+        uint32_t x = 0;                                   // rows beyond the tensor: the fill of a partial last block
+        if (row < rows) x = SRC == DT_BF16 ? (uint32_t)reinterpret_cast<const uint16_t *>(src)[idx] << 16 : reinterpret_cast<const uint32_t *>(src)[idx];
+        v[i] = x;
     }
     uint32_t amax = 0;
 #pragma unroll
@@ -186,7 +214,7 @@ __global__ __launch_bounds__(256) void cast_col_simple_kernel(const void *__rest
     const uint32_t s = scale_byte<FMT>(amax);
     uint32_t packed[w];
     encode_lane<FMT, RND, BLOCK>(v, s, rr, packed);
-    const int64_t nrb = rows / BLOCK;
+    const int64_t nrb = (rows + BLOCK - 1) / BLOCK;
     store_dwords<w>(elems + (c * nrb + rb) * (BLOCK * w / 8), packed);
     scales[c * nrb + rb] = (uint8_t)s;
 }
@@ -200,12 +228,13 @@ static hipError_t launch_row(const void *src, int64_t rows, int64_t cols, int64_
 {
     // FP6 needs at least 16 elements per lane to store whole dwords
     constexpr int EPL = (Fmt<FMT>::bits == 6) ? 16 : 8;
-    const int64_t n_units = rows * cols / EPL;
+    const int64_t pcols = (cols + BLOCK - 1) / BLOCK * BLOCK;
+    const int64_t n_units = rows * pcols / EPL;
     int64_t nb = (n_units + 255) / 256;
     const int64_t cap = 256 * 32;   // enough work-groups to fill 256 CUs several times over
     if (nb > cap) nb = cap;
-    hipLaunchKernelGGL((cast_row_kernel<SRC, FMT, RND, EPL>), dim3((unsigned)nb), dim3(256), 0, st, src, cols, ld, elems,
-                       scales, n_units, seed);
+    hipLaunchKernelGGL((cast_row_kernel<SRC, FMT, RND, EPL>), dim3((unsigned)nb), dim3(256), 0, st, src, cols, pcols, ld,
+                       elems, scales, n_units, seed);
     return hipGetLastError();
 }
 
@@ -213,7 +242,7 @@ template <int SRC, int FMT, int RND>
 static hipError_t launch_col(const void *src, int64_t rows, int64_t cols, int64_t ld, uint8_t *elems, uint8_t *scales,
                              uint64_t seed, hipStream_t st)
 {
-    dim3 grid((unsigned)((cols + 255) / 256), (unsigned)(rows / BLOCK));
+    dim3 grid((unsigned)((cols + 255) / 256), (unsigned)((rows + BLOCK - 1) / BLOCK));
     hipLaunchKernelGGL((cast_col_simple_kernel<SRC, FMT, RND>), grid, dim3(256), 0, st, src, rows, cols, ld, elems, scales,
                        seed);
     return hipGetLastError();

@@ -309,6 +309,7 @@ static hipError_t launch_fast_r(int rnd, const void *src, int64_t rows, int64_t 
 hipError_t launch_cast_bf16_fast(const void *src, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,
                                  uint8_t *elems, uint8_t *scales, hipStream_t st)
 {
+    if ((axis == 1 ? cols : rows) % BLOCK) return hipErrorNotSupported;   // whole blocks only
     switch (fmt) {
         case FP8_E4M3: return launch_fast_r<FP8_E4M3>(rnd, src, rows, cols, ld, axis, elems, scales, st);
         case FP8_E5M2: return launch_fast_r<FP8_E5M2>(rnd, src, rows, cols, ld, axis, elems, scales, st);

@@ -78,13 +78,15 @@ __device__ __forceinline__ void decode8_hw(const uint8_t *p, uint32_t s, float (
 
 // TR = false: dst[o][l .. l+7] contiguous (blocks along the last axis).
 // TR = true : the MX tensor is the cast of the transpose; value (o, l) goes to dst[l][o].
+// len is the block-axis length of the result; the MX tensor stores whole blocks (plen = len
+// rounded up to 32 positions per line) and the positions at or beyond len are not written.
 template <int FMT, int DST, bool TR>
 __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t *__restrict__ elems,
                                                       const uint8_t *__restrict__ scales, void *__restrict__ dst,
-                                                      int64_t n_out, int64_t len, int64_t ld)
+                                                      int64_t n_out, int64_t len, int64_t plen, int64_t ld)
 {
     constexpr int w = Fmt<FMT>::bits;
-    const int64_t units_per_row = len / 8;
+    const int64_t units_per_row = plen / 8;
     const int64_t n_units = n_out * units_per_row;
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x; u < n_units; u += stride) {
@@ -96,6 +98,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t *__restrict_
             o = u / units_per_row;
             l = (u % units_per_row) * 8;
         }
+        if (l >= len) continue;   // fill positions of a partial last block
         const int64_t unit_in_tensor = o * units_per_row + l / 8;
         const uint32_t s = scales[unit_in_tensor / 4];
         float f[8];
@@ -108,7 +111,14 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t *__restrict_
 #pragma unroll
             for (int i = 0; i < 8; i++) f[i] = decode_scaled<FMT>(c[i], s);
         }
-        if (!TR) {
+        if (!TR && l + 8 > len) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                if (l + i >= len) break;
+                if (DST == DT_F32) reinterpret_cast<float *>(dst)[o * ld + l + i] = f[i];
+                else reinterpret_cast<uint16_t *>(dst)[o * ld + l + i] = (uint16_t)f32_to_bf16_bits(f[i]);
+            }
+        } else if (!TR) {
             if (DST == DT_F32) {
                 float *d = reinterpret_cast<float *>(dst) + o * ld + l;
                 *reinterpret_cast<float4 *>(d) = make_float4(f[0], f[1], f[2], f[3]);
@@ -125,6 +135,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint8_t *__restrict_
         } else {
 #pragma unroll
             for (int i = 0; i < 8; i++) {
+                if (l + i >= len) break;
                 if (DST == DT_F32) reinterpret_cast<float *>(dst)[(l + i) * ld + o] = f[i];
                 else reinterpret_cast<uint16_t *>(dst)[(l + i) * ld + o] = (uint16_t)f32_to_bf16_bits(f[i]);
             }
@@ -138,14 +149,15 @@ static hipError_t launch_t(const uint8_t *elems, const uint8_t *scales, int64_t 
 {
     const int64_t n_out = axis == 1 ? rows : cols;
     const int64_t len = axis == 1 ? cols : rows;
-    int64_t nb = (n_out * (len / 8) + 255) / 256;
+    const int64_t plen = (len + BLOCK - 1) / BLOCK * BLOCK;
+    int64_t nb = (n_out * (plen / 8) + 255) / 256;
     if (nb > 0x7FFFFFFF) nb = 0x7FFFFFFF;   // one unit per thread (a capped grid with a stride loop: Float32 output 20 % slower, bf16 3 % faster)
     if (axis == 1)
         hipLaunchKernelGGL((dequant_kernel<FMT, DST, false>), dim3((unsigned)nb), dim3(256), 0, st, elems, scales, dst,
-                           n_out, len, ld);
+                           n_out, len, plen, ld);
     else
         hipLaunchKernelGGL((dequant_kernel<FMT, DST, true>), dim3((unsigned)nb), dim3(256), 0, st, elems, scales, dst,
-                           n_out, len, ld);
+                           n_out, len, plen, ld);
     return hipGetLastError();
 }
 

@@ -395,3 +395,48 @@ def test_gemm_qa_toward_zero(mx, oracle):
             assert torch.equal(C1.view(torch.int32), C2.view(torch.int32))
     with pytest.raises(mx.MxError):
         mx.mx_gemm_qa(to_dev(a), 0, SR, gb[0], gb[1], 0)
+
+
+# ---------------------------------------------------------------------------------------------
+# Block-axis lengths that are not multiples of 32: the last block is filled with zeros.
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("axis,shape", [(1, (67, 100)), (1, (5, 31)), (1, (40, 1)), (1, (33, 203)), (0, (100, 72)), (0, (31, 40)),
+                                        (0, (1, 8)), (0, (203, 41))],
+                         ids=lambda v: str(v).replace(" ", ""))
+def test_partial_last_block(mx, oracle, fmt, dt, axis, shape):
+    x = inputs.student_t_f32(shape, seed=90 + fmt)
+    src = x if dt == "f32" else inputs.f32_to_bf16_bits(x)
+    dev = dev_view(src)
+    for rnd in (RNE, AWAY, RTZ):
+        e_ref, s_ref = oracle.quantize(src, axis, fmt, rnd)
+        e, s = mx.mx_quantize(dev, axis, fmt, rnd)
+        assert e.shape == e_ref.shape and s.shape == s_ref.shape
+        assert np.array_equal(to_host(s), s_ref) and np.array_equal(to_host(e), e_ref), rnd
+    e_ref, s_ref = oracle.quantize(src, axis, fmt, SR, seed=21)
+    e, s = mx.mx_quantize_sr(dev, axis, fmt, 21)
+    assert np.array_equal(to_host(s), s_ref) and np.array_equal(to_host(e), e_ref)
+    # and back: only the positions of the tensor are written
+    for out_dt, odt in ((torch.float32, 0), (torch.bfloat16, 1)):
+        rows, cols = shape
+        pad = (-cols) % 8
+        wide = torch.full((rows, cols + pad + 8), 7.0, dtype=out_dt, device="cuda")
+        mx.mx_dequantize(e, s, fmt, rows, cols, axis, out=wide[:, :cols])
+        ref = oracle.dequantize(e_ref, s_ref, fmt, rows, cols, axis, odt)
+        assert same_floats(to_host(wide[:, :cols].contiguous()), ref)
+        assert torch.all(wide[:, cols:] == 7.0)
+
+
+def test_partial_block_tensor_feeds_the_gemm(mx, oracle):
+    """An operand with K = 100 is cast into 4 blocks (128 positions); the fill adds nothing."""
+    M, N, K = 48, 40, 100
+    a = inputs.student_t_bf16((M, K), seed=95)
+    b = inputs.gaussian_f32((N, K), seed=96)
+    ga = mx.mx_quantize(dev_view(a), 1, 0)
+    gb = mx.mx_quantize(dev_view(b), 1, 2)
+    C = to_host(mx.mx_gemm(ga[0], ga[1], 0, gb[0], gb[1], 2, 128))
+    Ad = oracle.dequantize(*oracle.quantize(a, 1, 0), 0, M, K, 1).astype(np.float64)
+    Bd = oracle.dequantize(*oracle.quantize(b, 1, 2), 2, N, K, 1).astype(np.float64)
+    ref = Ad @ Bd.T
+    assert np.all(np.abs(C - ref) <= 1e-5 * (np.abs(Ad) @ np.abs(Bd).T) + 14 * 2.0 ** -14 * np.abs(Ad).max() * np.abs(Bd).max() * 16)
