@@ -220,6 +220,26 @@ int mx_gemm_qa(int64_t M, int64_t N, int64_t K,
                void *C, mx_dtype_t c_dt, int64_t ldc, void *hip_stream);
 
 /* Static, human-readable text for a status code. */
+/*
+ * The product of mx_gemm with C delivered as an MX tensor: Algorithm 1 (Section
+ * 3) applied to the Float32 result along N, which is how the output of one
+ * MatMul reaches the next as an operand (Figure 2).  C_elems [M][ceil(N/32)*
+ * 32*bits/8] and C_scales [M][ceil(N/32)] receive, bit for bit, what
+ * mx_quantize(axis 1, fmtC, rnd) writes for the Float32 C of mx_gemm.
+ * Problems the LDS-tiled kernel takes (whole 256 x 256 tiles, FP8 / FP6 / FP4
+ * operands, K a multiple of 128, at least 512) with an FP8 / FP6 / FP4 fmtC and
+ * a round-to-nearest mode cast the accumulators in that kernel's epilogue: C
+ * never exists in memory at more than fmtC's width.  Everything else computes
+ * C as Float32 into a workspace from the stream's memory pool (M*N*4 bytes,
+ * see mx_gemm_qa) and casts it.  rnd: not MX_ROUND_STOCHASTIC.  Pointers 16-byte
+ * aligned, device memory, caller-owned; errors as mx_gemm.
+ */
+int mx_gemm_q(int64_t M, int64_t N, int64_t K,
+              const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
+              const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB,
+              mx_format_t fmtC, mx_round_t rnd,
+              void *C_elems, uint8_t *C_scales, void *hip_stream);
+
 const char *mx_strerror(int status);
 
 #ifdef __cplusplus

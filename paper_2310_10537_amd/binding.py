@@ -47,6 +47,7 @@ def lib() -> ctypes.CDLL:
         L.mx_dequantize.argtypes = [vp, vp, ci, i64, i64, ci, vp, ci, i64, vp]
         L.mx_gemm.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, ci, i64, vp]
         L.mx_gemm_qa.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
+        L.mx_gemm_q.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, ci, ci, vp, vp, vp]
         L.mx_strerror.argtypes = [ci]
         L.mx_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -169,6 +170,21 @@ def mx_gemm(A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, K, dtype=torch.flo
     _check(lib().mx_gemm(M, N, K, A_elems.data_ptr(), A_scales.data_ptr(), fmtA,
                          B_elems.data_ptr(), B_scales.data_ptr(), fmtB,
                          out.data_ptr(), _dt(out), ldc, _stream(stream)))
+    return out
+
+
+def mx_gemm_q(A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, K, fmtC, rnd=ROUND_RNE, out=None, stream=None):
+    """C = A . B^T delivered as an MX tensor blocked along N.  Returns (elems, scales)."""
+    for t, n in ((A_elems, "A_elems"), (A_scales, "A_scales"), (B_elems, "B_elems"), (B_scales, "B_scales")):
+        _dev(t, n)
+    M, N = A_scales.shape[0], B_scales.shape[0]
+    w = FORMAT_BITS[fmtC] if 0 <= fmtC < 6 else 8
+    nblk = -(-N // BLOCK)
+    if out is None:
+        out = (torch.empty((M, nblk * BLOCK * w // 8), dtype=torch.uint8, device=A_elems.device),
+               torch.empty((M, nblk), dtype=torch.uint8, device=A_elems.device))
+    _check(lib().mx_gemm_q(M, N, K, A_elems.data_ptr(), A_scales.data_ptr(), fmtA, B_elems.data_ptr(), B_scales.data_ptr(),
+                           fmtB, fmtC, rnd, out[0].data_ptr(), out[1].data_ptr(), _stream(stream)))
     return out
 
 

@@ -135,6 +135,24 @@ int mx_gemm_qa(int64_t M, int64_t N, int64_t K, const void *A_bf16, int64_t lda,
                        hip_stream);
 }
 
+int mx_gemm_q(int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
+              const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB, mx_format_t fmtC, mx_round_t rnd, void *C_elems,
+              uint8_t *C_scales, void *hip_stream)
+{
+    if (!fmt_ok(fmtA) || !fmt_ok(fmtB) || !fmt_ok(fmtC) || !rnd_ok(rnd)) return MX_ERR_ENUM;
+    if (M < 0 || N < 0 || K < 0 || K % mx::BLOCK) return MX_ERR_SHAPE;
+    if ((fmtA == MX_INT8) != (fmtB == MX_INT8)) return MX_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return MX_OK;
+    if (!C_elems || !C_scales || (K > 0 && (!A_elems || !A_scales || !B_elems || !B_scales))) return MX_ERR_NULL;
+    if (!aligned16(A_elems) || !aligned16(A_scales) || !aligned16(B_elems) || !aligned16(B_scales) || !aligned16(C_elems) ||
+        !aligned16(C_scales))
+        return MX_ERR_ALIGN;
+    hipError_t e = mx::launch_gemm_q(M, N, K, static_cast<const uint8_t *>(A_elems), A_scales, fmtA,
+                                     static_cast<const uint8_t *>(B_elems), B_scales, fmtB, static_cast<uint8_t *>(C_elems),
+                                     C_scales, fmtC, rnd, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+}
+
 const char *mx_strerror(int status)
 {
     switch (status) {

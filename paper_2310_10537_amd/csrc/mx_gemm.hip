@@ -182,4 +182,24 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
     return e;
 }
 
+// C as an MX tensor.  Whole-tile problems cast the accumulators in the tiled kernel's epilogue;
+// every other problem (and MXINT8 or truncated output) writes C as Float32 into a stream-ordered
+// workspace and casts that -- the same accumulators and the same Algorithm 1, hence the same bytes.
+hipError_t launch_gemm_q(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, int fmtA, const uint8_t *Be,
+                         const uint8_t *Bs, int fmtB, uint8_t *Ce, uint8_t *Cs, int fmtC, int rndC, hipStream_t st)
+{
+    if (fmtA != INT8) {
+        const hipError_t e = launch_gemm_tiled_mx(M, N, K, Ae, As, fmtA, Be, Bs, fmtB, Ce, Cs, fmtC, rndC, st);
+        if (e != hipErrorNotSupported) return e;
+    }
+    float *ws = nullptr;
+    const int64_t ldw = (N + 3) & ~(int64_t)3;   // rows of the workspace stay 16-byte aligned
+    hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), (size_t)M * (size_t)ldw * sizeof(float), st);
+    if (e != hipSuccess) return e;
+    e = launch_gemm(M, N, K, Ae, As, nullptr, 0, ROUND_RNE, fmtA, Be, Bs, fmtB, ws, DT_F32, ldw, st);
+    if (e == hipSuccess) e = launch_cast(ws, DT_F32, M, N, ldw, 1, fmtC, rndC, Ce, Cs, st);
+    const hipError_t f = hipFreeAsync(ws, st);
+    return e != hipSuccess ? e : f;
+}
+
 }  // namespace mx

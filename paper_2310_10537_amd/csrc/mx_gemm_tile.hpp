@@ -118,13 +118,142 @@ __device__ __forceinline__ v8i_t read_frag(const uint8_t *buf, const FragOfs<W> 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Epilogue that writes C as an MX tensor (blocks of 32 along N): Algorithm 1 applied to the
+// Float32 accumulators, i.e. the cast that would otherwise read C back from memory (Figure 2:
+// the output of one MatMul is cast for the next).  An accumulator block -- one row of a 32 x 32
+// matrix-instruction tile -- is spread over 32 lanes, so each wave passes its accumulators through
+// a 32-row patch of LDS (free once the K loop is over) and gets whole blocks per lane back.
+// ---------------------------------------------------------------------------------------------
+constexpr int DT_MX = 2;                 // internal output kind next to DT_F32 / DT_BF16
+constexpr int EP_PITCH = 544;            // bytes per patch row: 128 Float32 + 32 bytes, so that rows 4 apart
+                                         // (the two halves of a wave) start 32 banks apart
+
+// Hardware converts on a whole block of Float32 values (finite, scale byte >= FAST_MIN_SCALE; FP8
+// with the saturate mode set).  Ties away from zero: the lowest significand bit is set first -- a
+// rounding boundary of these grids has that bit (and many above it) clear, so exactly the ties move.
+template <int FMT, int RND>
+__device__ __forceinline__ void convert_f32_fast(const uint32_t (&v)[32], uint32_t s, uint32_t *out)
+{
+    const float sf = __uint_as_float(s << 23);
+    auto f = [](uint32_t b) { return __uint_as_float(RND == ROUND_HALF_AWAY ? (b | 1u) : b); };
+    if constexpr (FMT == FP8_E4M3 || FMT == FP8_E5M2) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            i16x2_t r = {0, 0};
+            if (FMT == FP8_E4M3) {
+                r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, f(v[4 * j]), f(v[4 * j + 1]), sf, false);
+                r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, f(v[4 * j + 2]), f(v[4 * j + 3]), sf, true);
+            } else {
+                r = __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(r, f(v[4 * j]), f(v[4 * j + 1]), sf, false);
+                r = __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(r, f(v[4 * j + 2]), f(v[4 * j + 3]), sf, true);
+            }
+            out[j] = __builtin_bit_cast(uint32_t, r);
+        }
+    } else if constexpr (FMT == FP4_E2M1) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            uint32_t q = 0;
+            q = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q, f(v[8 * j + 0]), f(v[8 * j + 1]), sf, 0);
+            q = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q, f(v[8 * j + 2]), f(v[8 * j + 3]), sf, 1);
+            q = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q, f(v[8 * j + 4]), f(v[8 * j + 5]), sf, 2);
+            q = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q, f(v[8 * j + 6]), f(v[8 * j + 7]), sf, 3);
+            out[j] = q;
+        }
+    } else {
+        f32x16_t a, b;   // the instruction interleaves its two sources: element 2i from a, 2i+1 from b
+#pragma unroll
+        for (int i = 0; i < 16; i++) { a[i] = f(v[2 * i]); b[i] = f(v[2 * i + 1]); }
+        const u32x6_t r = cvt_2xpk16_fp6_from_f32<FMT == FP6_E2M3>(a, b, sf);
+#pragma unroll
+        for (int i = 0; i < 6; i++) out[i] = r[i];
+    }
+}
+
+// One block of 32 Float32 values at src (LDS, 16-byte aligned) -> scale byte and packed codes.
+template <int FMT, int RND>
+__device__ __forceinline__ uint32_t quantize_block_lds(const uint32_t *src, uint32_t *packed)
+{
+    constexpr int w = Fmt<FMT>::bits;
+    uint32_t v[32];
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        const uint4 d = *reinterpret_cast<const uint4 *>(src + 4 * i);
+        v[4 * i] = d.x; v[4 * i + 1] = d.y; v[4 * i + 2] = d.z; v[4 * i + 3] = d.w;
+    }
+    uint32_t amax = 0, raw = 0;
+#pragma unroll
+    for (int i = 0; i < 32; i++) {
+        const uint32_t a = v[i] & 0x7FFFFFFFu, k = amax_key<FMT>(v[i]);
+        raw = raw > a ? raw : a;
+        amax = amax > k ? amax : k;
+    }
+    const uint32_t s = scale_byte<FMT>(amax);
+    if (raw < 0x7F800000u && s >= FAST_MIN_SCALE) {
+        convert_f32_fast<FMT, RND>(v, s, packed);
+        return s;
+    }
+    // rare: a non-finite value, or a scale so small that Float32 subnormals matter.  Exact integer
+    // encoder, one element per trip from LDS, codes shifted into the top of a w-dword register.
+    uint32_t o[w];
+#pragma unroll
+    for (int i = 0; i < w; i++) o[i] = 0;
+    if (Fmt<FMT>::elem_nan || s != SCALE_NAN) {
+#pragma unroll 1
+        for (int it = 0; it < 32; it++) {
+            const uint32_t code = encode_elem<FMT, RND>(src[it], s);
+#pragma unroll
+            for (int j = 0; j < w - 1; j++) o[j] = (o[j] >> w) | (o[j + 1] << (32 - w));
+            o[w - 1] = (o[w - 1] >> w) | (code << (32 - w));
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < w; i++) packed[i] = o[i];
+    return s;
+}
+
+// the same for a run-time format and rounding mode; stores the block (4 * bits bytes at dst, a
+// multiple of 8) and returns the scale byte
+template <int FMT, int RND>
+__device__ __forceinline__ uint32_t quantize_store_block(const uint32_t *src, uint8_t *dst)
+{
+    constexpr int w = Fmt<FMT>::bits;
+    uint32_t pk[w];
+    const uint32_t s = quantize_block_lds<FMT, RND>(src, pk);
+    if constexpr (w == 8) {
+        st16(dst, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+        st16(dst + 16, make_uint4(pk[4], pk[5], pk[6], pk[7]));
+    } else if constexpr (w == 6) {
+#pragma unroll
+        for (int i = 0; i < 3; i++) *reinterpret_cast<uint2 *>(dst + 8 * i) = make_uint2(pk[2 * i], pk[2 * i + 1]);
+    } else {
+        st16(dst, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+    }
+    return s;
+}
+
+__device__ __forceinline__ uint32_t quantize_store_block_rt(int fc, int rc, const uint32_t *src, uint8_t *dst)
+{
+#define MX_QS(F) (rc == ROUND_RNE ? quantize_store_block<F, ROUND_RNE>(src, dst) : quantize_store_block<F, ROUND_HALF_AWAY>(src, dst))
+    switch (fc) {
+        case FP8_E4M3: return MX_QS(FP8_E4M3);
+        case FP8_E5M2: return MX_QS(FP8_E5M2);
+        case FP6_E3M2: return MX_QS(FP6_E3M2);
+        case FP6_E2M3: return MX_QS(FP6_E2M3);
+        default:       return MX_QS(FP4_E2M1);
+    }
+#undef MX_QS
+}
+
 template <int FA, int FB, int CDT, bool QA, int RND>
 __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N, int64_t K,
                                                             const uint8_t *__restrict__ Ae, const uint8_t *__restrict__ As,
                                                             const uint16_t *__restrict__ Abf, int64_t lda,
                                                             const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
-                                                            void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n)
+                                                            void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n,
+                                                            uint8_t *__restrict__ Cs, int fcr)
 {
+    static_assert(!(QA && CDT == DT_MX), "the MX epilogue is built for plain operands");
     constexpr int WA = Fmt<FA>::bits, WB = Fmt<FB>::bits;
     static_assert(!QA || WA == 8, "the fused cast is written for 8-bit A operands");
     typedef TileFmt<WA> TA;
@@ -457,6 +586,37 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
         }
     }
 
+    // ---- MX output: C = element bytes [M][N*bits/8], Cs = scale bytes [M][N/32]; fcr = format | rounding << 4
+    if constexpr (CDT == DT_MX) {
+        __syncthreads();   // every wave's direct loads have landed and its operand reads are over: LDS is free
+        const int fc = fcr & 15, rc = fcr >> 4;
+        const int wbits = fmt_bits(fc);
+        uint32_t *patch = reinterpret_cast<uint32_t *>(lds + wave * (32 * EP_PITCH));   // 32 rows x 128 columns of this wave
+        const int64_t c_row_bytes = N * wbits / 8, nsb = N / BLOCK;
+        if (fc <= FP8_E5M2) fp8_saturate_mode(true);   // no matrix instruction follows
+#pragma unroll
+        for (int x = 0; x < 4; x++) {
+#pragma unroll
+            for (int y = 0; y < 4; y++)
+#pragma unroll
+                for (int t = 0; t < 16; t++)
+                    patch[(8 * (t / 4) + 4 * g + (t % 4)) * (EP_PITCH / 4) + 32 * y + li] = __float_as_uint(acc[x][y][t]);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll 1
+            for (int p = 0; p < 2; p++) {
+                const int bq = lane + 64 * p, row = bq >> 2, blk = bq & 3;   // four lanes write one 128-column run
+                const int64_t gr = m0 + wm * 128 + x * 32 + row, gb = (n0 + wn * 128) / BLOCK + blk;
+                const uint32_t sb = quantize_store_block_rt(fc, rc, patch + row * (EP_PITCH / 4) + blk * 32,
+                                                            static_cast<uint8_t *>(C) + gr * c_row_bytes + gb * (4 * wbits));
+                Cs[gr * nsb + gb] = (uint8_t)sb;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // all reads of the patch are over before it is written again
+            __builtin_amdgcn_wave_barrier();
+        }
+        return;
+    }
+
     // ---- epilogue: lane (li, g), register t of tile (x, y) -> C[8*(t/4) + 4g + t%4][li].
     // bf16 output uses the hardware's packed Float32 -> bf16 convert (round to nearest even, two
     // values per instruction): the integer formulation costs some 2000 vector instructions per
@@ -466,7 +626,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
 #pragma unroll
         for (int y = 0; y < 4; y++) {
             const int64_t c = n0 + wn * 128 + y * 32 + li;
-            if constexpr (CDT == DT_F32) {
+            if constexpr (CDT == DT_MX) {
+            } else if constexpr (CDT == DT_F32) {
 #pragma unroll
                 for (int t = 0; t < 16; t++) {
                     const int64_t r = m0 + wm * 128 + x * 32 + 8 * (t / 4) + 4 * g + (t % 4);
@@ -490,13 +651,14 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
 
 template <int FA, int FB, int CDT, bool QA, int RND>
 static hipError_t launch_t(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint16_t *Abf,
-                           int64_t lda, const uint8_t *Be, const uint8_t *Bs, void *C, int64_t ldc, hipStream_t st)
+                           int64_t lda, const uint8_t *Be, const uint8_t *Bs, void *C, int64_t ldc, hipStream_t st,
+                           uint8_t *Cs = nullptr, int fcr = 0)
 {
     auto kern = gemm_tile_kernel<FA, FB, CDT, QA, RND>;
     const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
     const int per_xcd = (tiles_m * tiles_n + 7) / 8;
     hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, M, N, K, Ae, As, Abf, lda, Be, Bs, C, ldc,
-                       tiles_m, tiles_n);
+                       tiles_m, tiles_n, Cs, fcr);
     return hipGetLastError();
 }
 
@@ -512,6 +674,8 @@ struct TileArgs {
     int c_dt;
     int64_t ldc;
     hipStream_t st;
+    uint8_t *Cs = nullptr;   // c_dt == DT_MX: C receives element bytes, Cs scale bytes,
+    int fcr = 0;             // in format fcr & 15 with rounding fcr >> 4
 };
 
 template <int FA, int FB>
@@ -520,6 +684,9 @@ static hipError_t launch_pair(const TileArgs &a)
 #define MX_GO(QA_, RND_)                                                                                                  \
     (a.c_dt == DT_F32 ? launch_t<FA, FB, DT_F32, QA_, RND_>(a.M, a.N, a.K, a.Ae, a.As, a.Abf, a.lda, a.Be, a.Bs, a.C, a.ldc, a.st) \
                       : launch_t<FA, FB, DT_BF16, QA_, RND_>(a.M, a.N, a.K, a.Ae, a.As, a.Abf, a.lda, a.Be, a.Bs, a.C, a.ldc, a.st))
+    if (a.c_dt == DT_MX)
+        return a.Abf ? hipErrorNotSupported
+                     : launch_t<FA, FB, DT_MX, false, ROUND_RNE>(a.M, a.N, a.K, a.Ae, a.As, nullptr, 0, a.Be, a.Bs, a.C, 0, a.st, a.Cs, a.fcr);
     if (!a.Abf) return MX_GO(false, ROUND_RNE);
     // the fused cast exists for 8-bit pairs only
     if constexpr (Fmt<FA>::bits == 8 && Fmt<FB>::bits == 8)

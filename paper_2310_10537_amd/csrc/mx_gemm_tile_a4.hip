@@ -29,4 +29,25 @@ hipError_t launch_gemm_tiled(int64_t M, int64_t N, int64_t K, const uint8_t *Ae,
     }
 }
 
+// C written as an MX tensor by the kernel's epilogue: FP8 / FP6 / FP4 output, round to nearest
+bool gemm_tiled_casts_output(int fmtC, int rndC)
+{
+    return fmtC >= FP8_E4M3 && fmtC <= FP4_E2M1 && (rndC == ROUND_RNE || rndC == ROUND_HALF_AWAY);
+}
+
+hipError_t launch_gemm_tiled_mx(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, int fmtA,
+                                const uint8_t *Be, const uint8_t *Bs, int fmtB, uint8_t *Ce, uint8_t *Cs, int fmtC, int rndC,
+                                hipStream_t st)
+{
+    if (!gemm_tiled_applies(M, N, K, fmtA, fmtB) || !gemm_tiled_casts_output(fmtC, rndC)) return hipErrorNotSupported;
+    TileArgs a{M, N, K, Ae, As, nullptr, 0, ROUND_RNE, Be, Bs, Ce, DT_MX, 0, st};
+    a.Cs = Cs;
+    a.fcr = fmtC | (rndC << 4);
+    switch (fmtA) {
+        case FP8_E4M3: case FP8_E5M2: return launch_gemm_tiled_a8(a, fmtA, fmtB);
+        case FP6_E3M2: case FP6_E2M3: return launch_gemm_tiled_a6(a, fmtA, fmtB);
+        default:                      return launch_gemm_tiled_a4(a, fmtA, fmtB);
+    }
+}
+
 }  // namespace mx

@@ -44,4 +44,15 @@ hipError_t launch_gemm_tiled(int64_t M, int64_t N, int64_t K, const uint8_t *Ae,
                              int64_t lda, int rnd, int fmtA, const uint8_t *Be, const uint8_t *Bs, int fmtB, void *C,
                              int c_dt, int64_t ldc, hipStream_t st);
 
+// The same product with C written as an MX tensor (blocks of 32 along N) by the tiled kernel's
+// epilogue; hipErrorNotSupported when the shape, the formats or the rounding are outside it.
+bool gemm_tiled_casts_output(int fmtC, int rndC);
+hipError_t launch_gemm_tiled_mx(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, int fmtA,
+                                const uint8_t *Be, const uint8_t *Bs, int fmtB, uint8_t *Ce, uint8_t *Cs, int fmtC, int rndC,
+                                hipStream_t st);
+
+// mx_gemm followed by the axis-1 cast of its Float32 result, fused where the tiled kernel applies
+hipError_t launch_gemm_q(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, int fmtA, const uint8_t *Be,
+                         const uint8_t *Bs, int fmtB, uint8_t *Ce, uint8_t *Cs, int fmtC, int rndC, hipStream_t st);
+
 }  // namespace mx

@@ -24,7 +24,7 @@ def test_exports_match_header(L):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(mx_[a-z_]+)\s*\(", text))
     assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_sr", "mx_quantize_dual", "mx_dequantize", "mx_gemm",
-                     "mx_gemm_qa", "mx_strerror"}
+                     "mx_gemm_qa", "mx_gemm_q", "mx_strerror"}
     for n in names:
         assert hasattr(L, n), n
 
@@ -92,6 +92,14 @@ def test_status_codes(L):
     assert ga(16, 16, 32, p, 16, 0, 0, p, p, 0, p, 0, 16, None) == SHAPE  # lda < K
     assert ga(16, 16, 32, p, 36, 0, 0, p, p, 0, p, 0, 16, None) == ALIGN
     assert ga(16, 16, 32, p, 32, 0, 3, p, p, 0, p, 0, 16, None) == ENUM
+    gq = L.mx_gemm_q
+    assert gq(16, 32, 32, p, p, 0, p, p, 0, 0, 0, None, p, None) == NULL
+    assert gq(16, 32, 32, p, p, 0, p, p, 0, 6, 0, p, p, None) == ENUM
+    assert gq(16, 32, 32, p, p, 0, p, p, 0, 0, 3, p, p, None) == ENUM      # no seed here: stochastic is refused
+    assert gq(16, 32, 48, p, p, 0, p, p, 0, 0, 0, p, p, None) == SHAPE
+    assert gq(16, 32, 32, p, p, 5, p, p, 0, 0, 0, p, p, None) == UNSUP
+    assert gq(16, 32, 32, p, p, 0, p, p, 0, 0, 0, p + 8, p, None) == ALIGN
+    assert gq(0, 32, 32, None, None, 0, None, None, 0, 0, 0, None, None, None) == OK
     for s in range(8):
         assert isinstance(L.mx_strerror(s), bytes) and L.mx_strerror(s)
 

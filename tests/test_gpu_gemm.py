@@ -654,3 +654,55 @@ def test_calls_on_a_side_stream(mx, oracle):
     for i, (x, y) in enumerate(zip(ref, got)):
         assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), i
     assert torch.equal(ref[0], ref[1]) and torch.equal(ref[6], ref[7])     # quantize-on-load = cast + GEMM
+
+
+# ---------------------------------------------------------------------------------------------
+# mx_gemm_q: C delivered as an MX tensor = Algorithm 1 applied to the Float32 result of mx_gemm.
+# The decision "which code" is taken on the kernel's own Float32 accumulators on both sides: the
+# reference casts the Float32 C that mx_gemm returns.
+# ---------------------------------------------------------------------------------------------
+def _gemm_q_case(mx, oracle, M, N, K, fa, fb, fc, rnd, special):
+    a = inputs.student_t_f32((M, K), seed=160 + fa)
+    b = inputs.gaussian_f32((N, K), seed=161 + fb, std=0.02)
+    ea, sa = oracle.quantize(a, 1, fa)
+    eb, sb = oracle.quantize(b, 1, fb)
+    if special:
+        sa[3, :] = 0xFF                              # a NaN row of C
+        ea[5, :] = 0                                 # an all-zero row: blocks with no normal value
+        sa[7, :] = 2                                 # a row so small that its C blocks get scale bytes below 18
+        sb[:, :] = np.minimum(sb, 120)
+        sa[9, :] = 250                               # a huge row: saturating products stay finite in Float32? (2^123 * 2^-7)
+        sb[11, 1] = 0xFF                             # a NaN column
+        if fa == 1:
+            ea[13, 4] = 0x7C                         # E5M2 +Inf element -> Inf / NaN entries in C
+    dev = [to_dev(x) for x in (ea, sa, eb, sb)]
+    C32 = to_host(mx.mx_gemm(dev[0], dev[1], fa, dev[2], dev[3], fb, K, dtype=torch.float32))
+    e_ref, s_ref = oracle.quantize(C32, 1, fc, rnd)
+    e, s = mx.mx_gemm_q(dev[0], dev[1], fa, dev[2], dev[3], fb, K, fc, rnd)
+    e, s = to_host(e), to_host(s)
+    assert e.shape == e_ref.shape and s.shape == s_ref.shape
+    bad = np.argwhere(s != s_ref)
+    assert bad.size == 0, f"scale bytes differ at {bad[:4].tolist()}"
+    bad = np.argwhere(e != e_ref)
+    assert bad.size == 0, f"element bytes differ at {bad[:4].tolist()}: {e[tuple(bad[0])]} vs {e_ref[tuple(bad[0])]}"
+    return s_ref
+
+
+@pytest.mark.parametrize("fc", range(5), ids=["e4m3", "e5m2", "e3m2", "e2m3", "e2m1"])
+@pytest.mark.parametrize("rnd", [RNE, AWAY], ids=["rne", "away"])
+@pytest.mark.parametrize("fa,fb", [(0, 0), (1, 4), (2, 2)], ids=["e4m3xe4m3", "e5m2xe2m1", "e3m2xe3m2"])
+def test_gemm_q_epilogue_cast(mx, oracle, fc, rnd, fa, fb):
+    """Whole tiles: the accumulators are cast in the tiled kernel's epilogue.  Plain data, and data
+    with NaN rows and columns, all-zero rows, tiny and huge rows and (E5M2) an Inf element."""
+    _gemm_q_case(mx, oracle, 512, 512, 640, fa, fb, fc, rnd, special=False)
+    s_ref = _gemm_q_case(mx, oracle, 256, 512, 512, fa, fb, fc, rnd, special=True)
+    assert (s_ref < 18).any()                        # the exact path inside the epilogue was taken
+
+
+@pytest.mark.parametrize("case", [(100, 72, 96, 0, 0, 0, RNE), (256, 256, 512, 0, 0, 5, RNE), (256, 256, 512, 2, 4, 4, 2),
+                                  (64, 100, 64, 5, 5, 5, AWAY), (2048, 2048, 256, 5, 5, 0, RNE), (300, 520, 640, 0, 3, 2, AWAY)],
+                         ids=["ragged", "int8_out", "truncated", "int8_all", "int8_split_route", "tiled_interior_plus_fringe"])
+def test_gemm_q_other_routes(mx, oracle, case):
+    """Shapes, formats and modes the epilogue does not take go through a Float32 workspace: same bytes."""
+    M, N, K, fa, fb, fc, rnd = case
+    _gemm_q_case(mx, oracle, M, N, K, fa, fb, fc, rnd, special=False)
