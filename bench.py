@@ -174,6 +174,26 @@ def other_configs(n):
                time_call(lambda: mx.mx_gemm_qa(a, mx.FP8_E4M3, mx.ROUND_RNE, Be, Bs, mx.FP8_E4M3, out=C), n), 8)
     del a, w, Be, Bs, Ae, As, C
 
+    # config 3, first projection with C delivered as MXFP8 (cast in the GEMM epilogue) against GEMM + cast of C
+    M, K, N = 8192, 4096, 4096
+    a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=2))
+    w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=102, std=0.02)).cuda()
+    Be, Bs = mx.mx_quantize(w, 0, mx.FP8_E4M3)
+    Ae, As = mx.mx_quantize(a, 1, mx.FP8_E4M3)
+    C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    qc = mx.mx_quantize(C, 1, mx.FP8_E4M3)
+    time_call(lambda: mx.mx_gemm_q(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, mx.FP8_E4M3, mx.ROUND_RNE, out=qc), n)   # first use
+    gemm_entry("cfg3_gemm_q_8192x4096x4096_e4m3_to_e4m3", M, N, K,
+               time_call(lambda: mx.mx_gemm_q(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, mx.FP8_E4M3, mx.ROUND_RNE, out=qc), n), 8)
+    ms_g = time_call(lambda: mx.mx_gemm(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, out=C), n)
+    ms_c = time_call(lambda: mx.mx_quantize(C, 1, mx.FP8_E4M3, mx.ROUND_RNE, qc[0], qc[1]), n)
+    out["cfg3_gemm_then_cast_of_C_ms"] = round(ms_g + ms_c, 5)
+    # the added rounding modes on the activation tensor of that shape (generic integer kernels)
+    for label, call in (("toward_zero", lambda: mx.mx_quantize(a, 1, mx.FP8_E4M3, mx.ROUND_TOWARD_ZERO, Ae, As)),
+                        ("stochastic", lambda: mx.mx_quantize_sr(a, 1, mx.FP8_E4M3, 1234, Ae, As))):
+        cast_entry("cast_8192x4096_bf16_e4m3_axis1_" + label, M * K, 2, mx.FP8_E4M3, time_call(call, n))
+    del a, w, Be, Bs, Ae, As, C, qc
+
     # config 4: E3M2 activations [4096, 8192] x E2M1 weights (logical 8192 x 28672)
     M, K, N = 4096, 8192, 28672
     act = to_dev_bf16(inputs.student_t_bf16((M, K), seed=3))
