@@ -162,12 +162,14 @@ def test_cast_empty_and_single_block(mx, oracle):
 @pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
 @pytest.mark.parametrize("axis", [1, 0])
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
-def test_dequantize(mx, oracle, fmt, axis, dt):
+@pytest.mark.parametrize("n_out", [72, 192], ids=["lines72", "lines192"])
+def test_dequantize(mx, oracle, fmt, axis, dt, n_out):
     """Every element code at a sweep of scale bytes (including 0, 254 and the NaN
-    scale 0xFF), and cast outputs of heavy-tailed data, both orientations."""
+    scale 0xFF), both orientations; 192 lines x 256 positions are whole 64 x 128 tiles
+    of the LDS-transposing axis-0 kernel, 72 lines take the generic one."""
     w = [8, 8, 6, 6, 4, 8][fmt]
     rng = np.random.default_rng(fmt)
-    n_out, length = 72, 256
+    length = 256
     codes = rng.integers(0, 1 << w, size=(n_out, length), dtype=np.uint32)
     codes[0, : 1 << w] = np.arange(1 << w)[:length]
     bits = ((codes[..., None] >> np.arange(w, dtype=np.uint32)) & 1).astype(np.uint8)
@@ -178,6 +180,10 @@ def test_dequantize(mx, oracle, fmt, axis, dt):
     ref = oracle.dequantize(elems, scales, fmt, rows, cols, axis, dst_dt=0 if dt == torch.float32 else 1)
     got = mx.mx_dequantize(to_dev(elems), to_dev(scales), fmt, rows, cols, axis, dtype=dt)
     assert same_floats(to_host(got), ref)
+    # into a view with a leading dimension: the columns beyond stay untouched
+    wide = torch.full((rows, cols + 8), 7.0, dtype=dt, device="cuda")
+    mx.mx_dequantize(to_dev(elems), to_dev(scales), fmt, rows, cols, axis, out=wide[:, :cols])
+    assert same_floats(to_host(wide[:, :cols].contiguous()), ref) and torch.all(wide[:, cols:] == 7.0)
 
 
 def test_full_size_config2_sampled(mx, oracle):
