@@ -250,6 +250,9 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
         if (valid) {
             uint8_t *o = elems + (col * n_rb + row_blk) * (BLOCK * w / 8);
             if constexpr (w == 8) {
+                // (a transpose inside the quad, so that each of the two stores writes 64 consecutive
+                // bytes of the column's 128-byte line instead of every second 16, changed nothing
+                // measurable: 44.6 against 45.3 us)
                 st16(o, make_uint4(out[0], out[1], out[2], out[3]));
                 st16(o + 16, make_uint4(out[4], out[5], out[6], out[7]));
             } else if constexpr (w == 6) {
