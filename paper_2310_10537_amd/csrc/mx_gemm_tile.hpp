@@ -129,89 +129,6 @@ constexpr int DT_MX = 2;                 // internal output kind next to DT_F32 
 constexpr int EP_PITCH = 544;            // bytes per patch row: 128 Float32 + 32 bytes, so that rows 4 apart
                                          // (the two halves of a wave) start 32 banks apart
 
-// Hardware converts on a whole block of Float32 values (finite, scale byte >= FAST_MIN_SCALE; FP8
-// with the saturate mode set).  Ties away from zero: the lowest significand bit is set first -- a
-// rounding boundary of these grids has that bit (and many above it) clear, so exactly the ties move.
-template <int FMT, int RND>
-__device__ __forceinline__ void convert_f32_fast(const uint32_t (&v)[32], uint32_t s, uint32_t *out)
-{
-    const float sf = __uint_as_float(s << 23);
-    auto f = [](uint32_t b) { return __uint_as_float(RND == ROUND_HALF_AWAY ? (b | 1u) : b); };
-    if constexpr (FMT == FP8_E4M3 || FMT == FP8_E5M2) {
-#pragma unroll
-        for (int j = 0; j < 8; j++) {
-            i16x2_t r = {0, 0};
-            if (FMT == FP8_E4M3) {
-                r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, f(v[4 * j]), f(v[4 * j + 1]), sf, false);
-                r = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(r, f(v[4 * j + 2]), f(v[4 * j + 3]), sf, true);
-            } else {
-                r = __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(r, f(v[4 * j]), f(v[4 * j + 1]), sf, false);
-                r = __builtin_amdgcn_cvt_scalef32_pk_bf8_f32(r, f(v[4 * j + 2]), f(v[4 * j + 3]), sf, true);
-            }
-            out[j] = __builtin_bit_cast(uint32_t, r);
-        }
-    } else if constexpr (FMT == FP4_E2M1) {
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            uint32_t q = 0;
-            q = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q, f(v[8 * j + 0]), f(v[8 * j + 1]), sf, 0);
-            q = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q, f(v[8 * j + 2]), f(v[8 * j + 3]), sf, 1);
-            q = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q, f(v[8 * j + 4]), f(v[8 * j + 5]), sf, 2);
-            q = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(q, f(v[8 * j + 6]), f(v[8 * j + 7]), sf, 3);
-            out[j] = q;
-        }
-    } else {
-        f32x16_t a, b;   // the instruction interleaves its two sources: element 2i from a, 2i+1 from b
-#pragma unroll
-        for (int i = 0; i < 16; i++) { a[i] = f(v[2 * i]); b[i] = f(v[2 * i + 1]); }
-        const u32x6_t r = cvt_2xpk16_fp6_from_f32<FMT == FP6_E2M3>(a, b, sf);
-#pragma unroll
-        for (int i = 0; i < 6; i++) out[i] = r[i];
-    }
-}
-
-// One block of 32 Float32 values at src (LDS, 16-byte aligned) -> scale byte and packed codes.
-template <int FMT, int RND>
-__device__ __forceinline__ uint32_t quantize_block_lds(const uint32_t *src, uint32_t *packed)
-{
-    constexpr int w = Fmt<FMT>::bits;
-    uint32_t v[32];
-#pragma unroll
-    for (int i = 0; i < 8; i++) {
-        const uint4 d = *reinterpret_cast<const uint4 *>(src + 4 * i);
-        v[4 * i] = d.x; v[4 * i + 1] = d.y; v[4 * i + 2] = d.z; v[4 * i + 3] = d.w;
-    }
-    uint32_t amax = 0, raw = 0;
-#pragma unroll
-    for (int i = 0; i < 32; i++) {
-        const uint32_t a = v[i] & 0x7FFFFFFFu, k = amax_key<FMT>(v[i]);
-        raw = raw > a ? raw : a;
-        amax = amax > k ? amax : k;
-    }
-    const uint32_t s = scale_byte<FMT>(amax);
-    if (raw < 0x7F800000u && s >= FAST_MIN_SCALE) {
-        convert_f32_fast<FMT, RND>(v, s, packed);
-        return s;
-    }
-    // rare: a non-finite value, or a scale so small that Float32 subnormals matter.  Exact integer
-    // encoder, one element per trip from LDS, codes shifted into the top of a w-dword register.
-    uint32_t o[w];
-#pragma unroll
-    for (int i = 0; i < w; i++) o[i] = 0;
-    if (Fmt<FMT>::elem_nan || s != SCALE_NAN) {
-#pragma unroll 1
-        for (int it = 0; it < 32; it++) {
-            const uint32_t code = encode_elem<FMT, RND>(src[it], s);
-#pragma unroll
-            for (int j = 0; j < w - 1; j++) o[j] = (o[j] >> w) | (o[j + 1] << (32 - w));
-            o[w - 1] = (o[w - 1] >> w) | (code << (32 - w));
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < w; i++) packed[i] = o[i];
-    return s;
-}
-
 // the same for a run-time format and rounding mode; stores the block (4 * bits bytes at dst, a
 // multiple of 8) and returns the scale byte
 template <int FMT, int RND>
@@ -219,7 +136,7 @@ __device__ __forceinline__ uint32_t quantize_store_block(const uint32_t *src, ui
 {
     constexpr int w = Fmt<FMT>::bits;
     uint32_t pk[w];
-    const uint32_t s = quantize_block_lds<FMT, RND>(src, pk);
+    const uint32_t s = quantize_block_lds<FMT, RND>(src, 1, pk);
     if constexpr (w == 8) {
         st16(dst, make_uint4(pk[0], pk[1], pk[2], pk[3]));
         st16(dst + 16, make_uint4(pk[4], pk[5], pk[6], pk[7]));

@@ -446,3 +446,24 @@ def test_partial_block_tensor_feeds_the_gemm(mx, oracle):
     Bd = oracle.dequantize(*oracle.quantize(b, 1, 2), 2, N, K, 1).astype(np.float64)
     ref = Ad @ Bd.T
     assert np.all(np.abs(C - ref) <= 1e-5 * (np.abs(Ad) @ np.abs(Bd).T) + 14 * 2.0 ** -14 * np.abs(Ad).max() * np.abs(Bd).max() * 16)
+
+
+@pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
+@pytest.mark.parametrize("rnd", [RNE, AWAY], ids=["rne", "away"])
+def test_cast_axis0_f32_whole_tiles(mx, oracle, fmt, rnd):
+    """Float32 sources made of whole 128 x 64 tiles take the LDS-tiled column kernel (weights are cast
+    from Float32 along dimension 0): heavy-tailed data with per-block magnitudes over 2^+-30, exact
+    ties of every element grid, and a view with a leading dimension."""
+    rows, cols = 384, 320
+    rng = np.random.default_rng(fmt)
+    x = inputs.student_t_f32((rows, cols), seed=97 + fmt)
+    x *= np.exp2(rng.integers(-30, 30, (rows // 32, cols))).repeat(32, axis=0).astype(np.float32)
+    # ties: k + 0.5 steps of the finest grid around 1.0 of each format, scaled per column block
+    x[:32, :64] = ((np.arange(32)[:, None] + 0.5) * 2.0 ** -6 * (1 + np.arange(64)[None, :] % 3)).astype(np.float32)
+    x[5, 70] = 0.0
+    check_cast(mx, oracle, x, 0, fmt, rnd)
+    wide = np.zeros((rows, cols + 64), dtype=np.float32)
+    wide[:, :cols] = x
+    e, s = mx.mx_quantize(to_dev(wide)[:, :cols], 0, fmt, rnd)
+    e_ref, s_ref = oracle.quantize(x, 0, fmt, rnd)
+    assert np.array_equal(to_host(e), e_ref) and np.array_equal(to_host(s), s_ref)
