@@ -227,8 +227,8 @@ int mx_gemm_qa(int64_t M, int64_t N, int64_t K,
  * 32*bits/8] and C_scales [M][ceil(N/32)] receive, bit for bit, what
  * mx_quantize(axis 1, fmtC, rnd) writes for the Float32 C of mx_gemm.
  * Problems the LDS-tiled kernel takes (whole 256 x 256 tiles, FP8 / FP6 / FP4
- * operands, K a multiple of 128, at least 512) with an FP8 / FP6 / FP4 fmtC and
- * a round-to-nearest mode cast the accumulators in that kernel's epilogue: C
+ * operands, K a multiple of 128, at least 512) with a round-to-nearest mode
+ * cast the accumulators in that kernel's epilogue, for every fmtC: C
  * never exists in memory at more than fmtC's width.  Everything else computes
  * C as Float32 into a workspace from the stream's memory pool (M*N*4 bytes,
  * see mx_gemm_qa) and casts it.  rnd: not MX_ROUND_STOCHASTIC.  Pointers 16-byte

@@ -183,7 +183,7 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
 }
 
 // C as an MX tensor.  Whole-tile problems cast the accumulators in the tiled kernel's epilogue;
-// every other problem (and MXINT8 or truncated output) writes C as Float32 into a stream-ordered
+// every other problem (MXINT8 operands, truncated output) writes C as Float32 into a stream-ordered
 // workspace and casts that -- the same accumulators and the same Algorithm 1, hence the same bytes.
 hipError_t launch_gemm_q(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, int fmtA, const uint8_t *Be,
                          const uint8_t *Bs, int fmtB, uint8_t *Ce, uint8_t *Cs, int fmtC, int rndC, hipStream_t st)

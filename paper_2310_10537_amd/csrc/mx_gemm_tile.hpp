@@ -157,7 +157,8 @@ __device__ __forceinline__ uint32_t quantize_store_block_rt(int fc, int rc, cons
         case FP8_E5M2: return MX_QS(FP8_E5M2);
         case FP6_E3M2: return MX_QS(FP6_E3M2);
         case FP6_E2M3: return MX_QS(FP6_E2M3);
-        default:       return MX_QS(FP4_E2M1);
+        case FP4_E2M1: return MX_QS(FP4_E2M1);
+        default:       return MX_QS(INT8);
     }
 #undef MX_QS
 }

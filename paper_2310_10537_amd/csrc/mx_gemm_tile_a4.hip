@@ -29,10 +29,10 @@ hipError_t launch_gemm_tiled(int64_t M, int64_t N, int64_t K, const uint8_t *Ae,
     }
 }
 
-// C written as an MX tensor by the kernel's epilogue: FP8 / FP6 / FP4 output, round to nearest
+// C written as an MX tensor by the kernel's epilogue: every element format, round to nearest
 bool gemm_tiled_casts_output(int fmtC, int rndC)
 {
-    return fmtC >= FP8_E4M3 && fmtC <= FP4_E2M1 && (rndC == ROUND_RNE || rndC == ROUND_HALF_AWAY);
+    return fmtC >= FP8_E4M3 && fmtC <= INT8 && (rndC == ROUND_RNE || rndC == ROUND_HALF_AWAY);
 }
 
 hipError_t launch_gemm_tiled_mx(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, int fmtA,

@@ -688,7 +688,7 @@ def _gemm_q_case(mx, oracle, M, N, K, fa, fb, fc, rnd, special):
     return s_ref
 
 
-@pytest.mark.parametrize("fc", range(5), ids=["e4m3", "e5m2", "e3m2", "e2m3", "e2m1"])
+@pytest.mark.parametrize("fc", range(6), ids=["e4m3", "e5m2", "e3m2", "e2m3", "e2m1", "int8"])
 @pytest.mark.parametrize("rnd", [RNE, AWAY], ids=["rne", "away"])
 @pytest.mark.parametrize("fa,fb", [(0, 0), (1, 4), (2, 2)], ids=["e4m3xe4m3", "e5m2xe2m1", "e3m2xe3m2"])
 def test_gemm_q_epilogue_cast(mx, oracle, fc, rnd, fa, fb):
