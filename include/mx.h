@@ -177,6 +177,9 @@ int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt,
  * run of 8 consecutive K products in fixed point with 14 bits below the run's
  * largest product, which is exact for FP6 E2M3 / FP4 E2M1 operands and loses at
  * most 14 * 2^-14 of each run's largest product otherwise.
+ * (Problems with at most 128 rows of A split K over the eight waves of a
+ * work-group and add the eight partial sums in a fixed order: deterministic,
+ * but a different Float32 rounding than the other kernels' K order.)
  * C is row-major [M][N] of type c_dt with leading dimension ldc >= N (elements;
  * any value, a multiple of 16 bytes is fastest); the C pointer is 16-byte
  * aligned; bf16 output is the Float32 accumulator rounded to nearest even.

@@ -108,6 +108,23 @@ static hipError_t launch_gemm_part(int64_t M, int64_t N, int64_t K, const uint8_
         const hipError_t f = hipFreeAsync(ws, st);
         return e != hipSuccess ? e : f;
     }
+    // Few rows of A (a decoding step): the K range is shared by the eight waves of a work-group.
+    // Quantize-on-load casts the few rows into a workspace first (the bytes mx_quantize writes).
+    if (gemm_skinny_applies(M, N, K, fmtA, fmtB)) {
+        if (!a_bf16) return launch_gemm_skinny(M, N, K, A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
+        const size_t bits = fmtA <= FP8_E5M2 ? 8 : fmtA <= FP6_E2M3 ? 6 : 4;
+        const size_t eb = ((size_t)M * (size_t)K * bits / 8 + 15) & ~(size_t)15, sb = (size_t)M * (size_t)K / BLOCK;
+        uint8_t *ws = nullptr;
+        hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), eb + sb, st);
+        if (e == hipSuccess) {
+            e = launch_cast(a_bf16, DT_BF16, M, K, lda, 1, fmtA, rnd, ws, ws + eb, st);
+            if (e == hipSuccess)
+                e = launch_gemm_skinny(M, N, K, ws, ws + eb, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
+            const hipError_t f = hipFreeAsync(ws, st);
+            return e != hipSuccess ? e : f;
+        }
+        (void)hipGetLastError();   // no workspace: the direct kernel casts in registers
+    }
     // Quantize-on-load on whole tiles.  The fused kernel casts each A tile once per column of
     // output tiles and reads it as bf16 that often, so it pays only for narrow outputs (measured:
     // up to two tile columns), and only when there are enough tiles to fill the chip, since the

@@ -48,6 +48,11 @@ hipError_t launch_gemm_tiled(int64_t M, int64_t N, int64_t K, const uint8_t *Ae,
                              int64_t lda, int rnd, int fmtA, const uint8_t *Be, const uint8_t *Bs, int fmtB, void *C,
                              int c_dt, int64_t ldc, hipStream_t st);
 
+// At most 128 rows of A: eight waves per 32 columns of C share the K range (FP8 / FP6 / FP4 operands)
+bool gemm_skinny_applies(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
+hipError_t launch_gemm_skinny(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, int fmtA, const uint8_t *Be,
+                              const uint8_t *Bs, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st);
+
 // The same product with C written as an MX tensor (blocks of 32 along N) by the tiled kernel's
 // epilogue; hipErrorNotSupported when the shape, the formats or the rounding are outside it.
 bool gemm_tiled_casts_output(int fmtC, int rndC);

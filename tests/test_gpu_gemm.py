@@ -706,3 +706,55 @@ def test_gemm_q_other_routes(mx, oracle, case):
     """Shapes, formats and modes the epilogue does not take go through a Float32 workspace: same bytes."""
     M, N, K, fa, fb, fc, rnd = case
     _gemm_q_case(mx, oracle, M, N, K, fa, fb, fc, rnd, special=False)
+
+
+# ---------------------------------------------------------------------------------------------
+# Few rows of A (decoding shapes): the kernel that shares the K range among eight waves.
+# ---------------------------------------------------------------------------------------------
+FEW_ROWS = [(M, N, K) for M in (1, 7, 32, 33, 64, 100, 128) for (N, K) in ((40, 32), (72, 96), (1000, 1056))] + \
+           [(M, 4096, 4128) for M in (1, 33, 128)]
+
+
+@pytest.mark.parametrize("M,N,K", FEW_ROWS, ids=lambda v: str(v))
+@pytest.mark.parametrize("fa,fb", [(0, 0), (1, 4), (3, 2)], ids=["e4m3xe4m3", "e5m2xe2m1", "e2m3xe3m2"])
+def test_gemm_few_rows(mx, oracle, M, N, K, fa, fb):
+    a = inputs.student_t_f32((M, K), seed=170 + M)
+    b = inputs.gaussian_f32((N, K), seed=171 + fb, std=0.02)
+    ea, sa = oracle.quantize(a, 1, fa)
+    eb, sb = oracle.quantize(b, 1, fb)
+    if M > 3 and N > 50 and K > 64:
+        sa[3, 1] = 0xFF                                  # NaN row
+        sb[50, K // 32 - 1] = 0xFF                       # NaN column, in the last (half) K step
+    C_ref, C_abs = oracle.gemm(ea, sa, fa, eb, sb, fb, K, want_abs=True)
+    hw = hw_term_for(oracle, ea, np.where(sa == 0xFF, 0, sa), fa, eb, np.where(sb == 0xFF, 0, sb), fb, K)
+    for dt in (torch.float32, torch.bfloat16):
+        got = to_host(mx.mx_gemm(to_dev(ea), to_dev(sa), fa, to_dev(eb), to_dev(sb), fb, K, dtype=dt))
+        cabs = np.nan_to_num(C_abs)
+        if dt == torch.bfloat16:
+            got = bf16_bits_to_f64(got)
+            cabs = cabs + np.abs(np.nan_to_num(C_ref)) * 2.0 ** -8 / 1e-5
+        check_gemm(got, C_ref, cabs, f"few rows {M}x{N}x{K}", hw)
+
+
+def test_gemm_few_rows_qa_and_one_hot(mx, oracle):
+    """Quantize-on-load on few rows = cast + GEMM bit for bit; one-hot rows pin every K position of
+    every wave's slice (the result must be the selected element of B exactly)."""
+    M, N, K = 48, 200, 2080                               # 65 blocks: 33 K steps over eight waves, a half step last
+    a = inputs.student_t_bf16((M, K), seed=180)
+    b = inputs.gaussian_f32((N, K), seed=181)
+    for fa, fb, rnd in ((0, 0, RNE), (2, 4, AWAY), (4, 3, RNE)):
+        gb = mx.mx_quantize(to_dev(b), 1, fb)
+        ga = mx.mx_quantize(to_dev(a), 1, fa, rnd)
+        C2 = mx.mx_gemm(ga[0], ga[1], fa, gb[0], gb[1], fb, K)
+        C1 = mx.mx_gemm_qa(to_dev(a), fa, rnd, gb[0], gb[1], fb)
+        assert torch.equal(C1.view(torch.int32), C2.view(torch.int32))
+    M = 128
+    hot = np.zeros((M, K), np.float32)
+    pos = (np.arange(M) * 17 + 5) % K
+    hot[np.arange(M), pos] = 1.0
+    for fb in (0, 2, 4):
+        eh, sh = oracle.quantize(hot, 1, 1)
+        eb, sb = oracle.quantize(b, 1, fb)
+        Bd = oracle.dequantize(eb, sb, fb, N, K, 1)
+        C = to_host(mx.mx_gemm(to_dev(eh), to_dev(sh), 1, to_dev(eb), to_dev(sb), fb, K))
+        assert np.array_equal(C, Bd[:, pos].T.astype(np.float32))
