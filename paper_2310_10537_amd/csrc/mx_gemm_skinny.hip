@@ -24,8 +24,10 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(int64_t M, i
 {
     constexpr int wA = Fmt<FA>::bits, wB = Fmt<FB>::bits;
     constexpr int HA = hw_fmt(FA), HB = hw_fmt(FB);   // must reach the builtin as literal constants
-    constexpr int U = MT == 4 ? 2 : 4;                // K steps whose operands are requested together
-    __shared__ float red[SK_WAVES / 2][MT][16][64];   // partial sums of four waves at a time
+    constexpr int U = MT == 4 ? 2 : MT == 2 ? 4 : 8;  // K steps whose operands are requested together
+    // partial sums: of seven waves at once (one barrier) while that fits in 64 KB, else of four at a time
+    constexpr bool FLAT = MT <= 2;
+    __shared__ float red[FLAT ? SK_WAVES - 1 : SK_WAVES / 2][MT][16][64];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 31, g = lane >> 5;
     const int64_t n0 = (int64_t)blockIdx.x * 32, m0 = (int64_t)blockIdx.y * (32 * MT);
@@ -76,7 +78,32 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(int64_t M, i
                 acc[x] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[u][x], b[u], acc[x], HA, HB, 0, sa[u][x], 0, sb[u]);
     }
 
-    // ---- the eight partial sums, always in the order ((w0 + w4) + (w1 + w5)) + ((w2 + w6) + (w3 + w7))
+    // ---- the eight partial sums, always in the same order: w0 + w1 + ... + w7 (one or two row tiles) ...
+    if constexpr (FLAT) {
+        if (wave > 0) {
+#pragma unroll
+            for (int x = 0; x < MT; x++)
+#pragma unroll
+                for (int t = 0; t < 16; t++) red[wave - 1][x][t][lane] = acc[x][t];
+        }
+        __syncthreads();
+        if (wave != 0) return;
+#pragma unroll
+        for (int x = 0; x < MT; x++)
+#pragma unroll
+            for (int t = 0; t < 16; t++) {
+                float v = acc[x][t];
+#pragma unroll
+                for (int w = 0; w < SK_WAVES - 1; w++) v += red[w][x][t][lane];
+                const int64_t r = m0 + 32 * x + 8 * (t / 4) + 4 * g + (t % 4);
+                if (r < M && cv) {
+                    if (CDT == DT_F32) reinterpret_cast<float *>(C)[r * ldc + col] = v;
+                    else reinterpret_cast<uint16_t *>(C)[r * ldc + col] = (uint16_t)f32_to_bf16_bits(v);
+                }
+            }
+        return;
+    }
+    // ... or ((w0 + w4) + (w1 + w5)) + ((w2 + w6) + (w3 + w7)) (four row tiles)
     if (wave >= 4) {
 #pragma unroll
         for (int x = 0; x < MT; x++)
