@@ -194,6 +194,18 @@ def other_configs(n):
         cast_entry("cast_8192x4096_bf16_e4m3_axis1_" + label, M * K, 2, mx.FP8_E4M3, time_call(call, n))
     del a, w, Be, Bs, Ae, As, C, qc
 
+    # decoding shapes: few rows of A against the wide projection's E4M3 weights (one pass over 45 MB)
+    N, K = 11008, 4096
+    w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=112, std=0.02)).cuda()
+    Be, Bs = mx.mx_quantize(w, 0, mx.FP8_E4M3)
+    for M in (1, 16, 128):
+        a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=5))
+        Ae, As = mx.mx_quantize(a, 1, mx.FP8_E4M3)
+        C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        ms = time_call(lambda: mx.mx_gemm(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, out=C), n)
+        out[f"decode_gemm_{M}x{N}x{K}_e4m3"] = {"avg_us": round(1e3 * ms, 2), "weights_GBps": round(N * K * (1 + 1 / 32) / ms / 1e6, 1)}
+    del w, Be, Bs
+
     # config 4: E3M2 activations [4096, 8192] x E2M1 weights (logical 8192 x 28672)
     M, K, N = 4096, 8192, 28672
     act = to_dev_bf16(inputs.student_t_bf16((M, K), seed=3))
