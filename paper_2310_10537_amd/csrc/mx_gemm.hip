@@ -86,6 +86,21 @@ static hipError_t dispatch_b(const GemmArgs &g, int fmtB, int rnd, int c_dt)
     }
 }
 
+// Whether a problem goes to the kernel that shares the K range of 32 columns among eight waves
+// rather than to 256 x 256 tiles: few rows of A (a decoding step), shapes that are not whole tiles,
+// and so few tiles that most compute units would idle.  A tiled launch of fewer than 256 tiles
+// takes as long as its K loop, about 0.0095 us per element of K; the other kernel runs at 400
+// TFLOP/s on the whole chip (600 for long K).  Measured: 256 x 4096 x 4096 24 against 40 us, 256 x
+// 4096 x 11008 40 against 104 us, 512 x 4096 x 11008 77 against 105 us; but 512 x 4096 x 4096 44
+// against 42 us and 256 x 11008 x 4096 65 against 43 us.
+static bool shares_k_among_waves(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB)
+{
+    if (!gemm_skinny_applies(M, N, K, fmtA, fmtB)) return false;
+    if (M <= 128 || !gemm_tiled_applies(M, N, K, fmtA, fmtB)) return true;
+    const int64_t tiles = (M / 256) * (N / 256);
+    return tiles < 32 || (tiles < 44 && K >= 8192);
+}
+
 // whether the fused quantize-on-load tiled kernel beats cast + plain tiled kernel (256 x 256 tiles)
 static bool qa_fused_pays(int64_t M, int64_t N) { return N / 256 <= 2 && (M / 256) * (N / 256) >= 256; }
 
@@ -108,9 +123,8 @@ static hipError_t launch_gemm_part(int64_t M, int64_t N, int64_t K, const uint8_
         const hipError_t f = hipFreeAsync(ws, st);
         return e != hipSuccess ? e : f;
     }
-    // Few rows of A (a decoding step): the K range is shared by the eight waves of a work-group.
-    // Quantize-on-load casts the few rows into a workspace first (the bytes mx_quantize writes).
-    if (gemm_skinny_applies(M, N, K, fmtA, fmtB)) {
+    // Quantize-on-load casts A into a workspace first (the bytes mx_quantize writes).
+    if (shares_k_among_waves(M, N, K, fmtA, fmtB)) {
         if (!a_bf16) return launch_gemm_skinny(M, N, K, A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
         const size_t bits = fmtA <= FP8_E5M2 ? 8 : fmtA <= FP6_E2M3 ? 6 : 4;
         const size_t eb = ((size_t)M * (size_t)K * bits / 8 + 15) & ~(size_t)15, sb = (size_t)M * (size_t)K / BLOCK;
@@ -162,8 +176,9 @@ static hipError_t launch_gemm_part(int64_t M, int64_t N, int64_t K, const uint8_
 
 // A problem whose M or N is not a multiple of the 256 x 256 tile is cut into the largest interior
 // of whole tiles, which takes the tiled kernel, and an L-shaped fringe of fewer than 256 rows /
-// columns, which takes the direct kernel.  Every output entry is computed by exactly one launch
-// and each kernel sums K in the same order, so the result does not depend on the cut.
+// columns, which takes the kernel for shapes that are not whole tiles (or the direct kernel when
+// K is not a multiple of 128).  Every output entry is computed by exactly one launch; which one
+// depends on the shape only, so a result is reproducible, and quantize-on-load follows the same cut.
 hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, const uint8_t *A_scales,
                        const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,
                        const uint8_t *B_scales, int fmtB, void *C, int c_dt, int64_t ldc, hipStream_t st)
@@ -182,6 +197,9 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
         return e != hipSuccess ? e : f;
     }
     const int64_t M0 = M & ~(int64_t)255, N0 = N & ~(int64_t)255;
+    // small ragged problems: one launch of the kernel for such shapes instead of three
+    if (fmtA != INT8 && K % 128 == 0 && (M0 / 256) * (N0 / 256) < 32 && gemm_skinny_applies(M, N, K, fmtA, fmtB))
+        return launch_gemm_part(M, N, K, A_elems, A_scales, a_bf16, lda, rnd, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
     if ((M0 == M && N0 == N) || M0 == 0 || N0 == 0 || fmtA == INT8 || !gemm_tiled_applies(M0, N0, K, fmtA, fmtB))
         return launch_gemm_part(M, N, K, A_elems, A_scales, a_bf16, lda, rnd, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
     const int64_t bitsA = fmtA <= FP8_E5M2 ? 8 : fmtA <= FP6_E2M3 ? 6 : 4, bitsB = fmtB <= FP8_E5M2 ? 8 : fmtB <= FP6_E2M3 ? 6 : 4;
@@ -205,7 +223,8 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
 hipError_t launch_gemm_q(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, int fmtA, const uint8_t *Be,
                          const uint8_t *Bs, int fmtB, uint8_t *Ce, uint8_t *Cs, int fmtC, int rndC, hipStream_t st)
 {
-    if (fmtA != INT8) {
+    // (only where mx_gemm runs the tiled kernel too: the two must see the same accumulators)
+    if (fmtA != INT8 && !shares_k_among_waves(M, N, K, fmtA, fmtB)) {
         const hipError_t e = launch_gemm_tiled_mx(M, N, K, Ae, As, fmtA, Be, Bs, fmtB, Ce, Cs, fmtC, rndC, st);
         if (e != hipErrorNotSupported) return e;
     }

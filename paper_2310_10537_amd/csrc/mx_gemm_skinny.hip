@@ -45,7 +45,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_lds_kernel(int64_t 
     __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_BYTES];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 31, g = lane >> 5;
-    const int64_t n0 = (int64_t)blockIdx.x * 32;
+    const int64_t n0 = (int64_t)blockIdx.x * 32, m0 = (int64_t)blockIdx.y * (32 * MT);
     const int64_t nkb = K / BLOCK, chunks = K / 128;
     const int64_t per_wave = (chunks + SK_WAVES - 1) / SK_WAVES;
     const int64_t c_begin = wave * per_wave, c_end = c_begin + per_wave < chunks ? c_begin + per_wave : chunks;
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_lds_kernel(int64_t 
         for (int x = 0; x < MT; x++)
 #pragma unroll
             for (int j = 0; j < SkStage<WA>::NJ; j++) {
-                const int64_t row = clampi(32 * x + j * (64 / PA) + ar, M - 1);
+                const int64_t row = clampi(m0 + 32 * x + j * (64 / PA) + ar, M - 1);
                 if (a_on) ra[x][j] = ld16(Ae + row * a_rb + c * (128 * WA / 8) + ap * 16);
             }
 #pragma unroll
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_lds_kernel(int64_t 
             if (b_on) rb[j] = ld16(Be + row * b_rb + c * (128 * WB / 8) + bp * 16);
         }
 #pragma unroll
-        for (int x = 0; x < MT; x++) sa_d[x] = *reinterpret_cast<const uint32_t *>(As + clampi(32 * x + i, M - 1) * nkb + c * 4);
+        for (int x = 0; x < MT; x++) sa_d[x] = *reinterpret_cast<const uint32_t *>(As + clampi(m0 + 32 * x + i, M - 1) * nkb + c * 4);
         sb_d = *reinterpret_cast<const uint32_t *>(Bs + clampi(n0 + i, N - 1) * nkb + c * 4);
     };
     auto park = [&]() {
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_lds_kernel(int64_t 
             float v = acc[x][t];
 #pragma unroll
             for (int w = 0; w < SK_WAVES - 1; w++) v += red[((w * MT + x) * 16 + t) * 64 + lane];
-            const int64_t r = 32 * x + 8 * (t / 4) + 4 * g + (t % 4);   // result register t: row 8 (t/4) + 4g + t%4, column i
+            const int64_t r = m0 + 32 * x + 8 * (t / 4) + 4 * g + (t % 4);   // result register t: row 8 (t/4) + 4g + t%4, column i
             if (r < M && col < N) {
                 if (CDT == DT_F32) reinterpret_cast<float *>(C)[r * ldc + col] = v;
                 else reinterpret_cast<uint16_t *>(C)[r * ldc + col] = (uint16_t)f32_to_bf16_bits(v);
@@ -302,7 +302,7 @@ template <int FA, int FB, int MT>
 static hipError_t launch_lds(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint8_t *Be,
                              const uint8_t *Bs, void *C, int c_dt, int64_t ldc, hipStream_t st)
 {
-    const dim3 grid((unsigned)((N + 31) / 32));
+    const dim3 grid((unsigned)((N + 31) / 32), (unsigned)((M + 32 * MT - 1) / (32 * MT)));
     if (c_dt == DT_F32)
         hipLaunchKernelGGL((gemm_skinny_lds_kernel<FA, FB, MT, DT_F32>), grid, dim3(64 * SK_WAVES), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc);
     else
@@ -336,11 +336,12 @@ static hipError_t launch_b(int fmtB, int64_t M, int64_t N, int64_t K, const uint
     }
 }
 
-// at most 128 rows of A (any N, any K multiple of 32), FP8 / FP6 / FP4 operands
+// FP8 / FP6 / FP4 operands; at most 128 rows of A (any N, any K multiple of 32), or any number of rows
+// in groups of 128 when K is a multiple of 128 (the LDS-staged kernel)
 bool gemm_skinny_applies(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB)
 {
-    return M > 0 && M <= 128 && N > 0 && K > 0 && fmtA >= FP8_E4M3 && fmtA <= FP4_E2M1 && fmtB >= FP8_E4M3 && fmtB <= FP4_E2M1 &&
-           (N + 31) / 32 <= 0x7FFFFFFF;
+    return M > 0 && (M <= 128 || (K % 128 == 0 && (M + 127) / 128 <= 65535)) && N > 0 && K > 0 && fmtA >= FP8_E4M3 &&
+           fmtA <= FP4_E2M1 && fmtB >= FP8_E4M3 && fmtB <= FP4_E2M1 && (N + 31) / 32 <= 0x7FFFFFFF;
 }
 
 hipError_t launch_gemm_skinny(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, int fmtA, const uint8_t *Be,

@@ -138,37 +138,33 @@ def test_shapes(mx, oracle, shape):
 
 
 @pytest.mark.parametrize("fa,fb", [(0, 0), (0, 1), (1, 0), (1, 1)])
-@pytest.mark.parametrize("shape,dt", [((512, 256, 384), torch.float32), ((256, 768, 128), torch.bfloat16),
+@pytest.mark.parametrize("shape,dt", [  # few tiles: the kernel that shares the K range among eight waves, rows in groups of 128
+                                      ((512, 256, 384), torch.float32), ((256, 768, 128), torch.bfloat16),
                                       ((256, 512, 1536), torch.float32), ((512, 256, 512), torch.bfloat16),
-                                      # 8, 16 and 32 tile rows: the XCD-banded tile orders (sub-bands of 1, 2, 4 rows)
-                                      ((2048, 768, 512), torch.float32), ((4096, 512, 512), torch.bfloat16),
-                                      ((8192, 256, 512), torch.float32),
+                                      # at least 32 tiles: the LDS-tiled kernel.  8, 16 and 32 tile rows: the XCD-banded
+                                      # tile orders (sub-bands of 1, 2, 4 rows), and a tile count that is no multiple of 8
+                                      ((2048, 1280, 512), torch.float32), ((4096, 512, 512), torch.bfloat16),
+                                      ((8192, 256, 512), torch.float32), ((1792, 1280, 1536), torch.bfloat16),
                                       # K = 5, 6, 7 and 9 steps of 128: a partial last scale group of 1, 2, 3 and 1 steps
-                                      ((256, 256, 640), torch.float32), ((256, 512, 768), torch.bfloat16),
-                                      ((512, 256, 896), torch.float32), ((256, 256, 1152), torch.float32)])
+                                      ((1024, 2048, 640), torch.float32), ((2048, 1024, 768), torch.bfloat16),
+                                      ((1024, 2048, 896), torch.float32), ((2048, 1024, 1152), torch.float32)])
 def test_tiled_kernel_full_tiles(mx, oracle, fa, fb, shape, dt):
-    """Shapes made of whole 256 x 256 x 128 tiles take the LDS-tiled kernel; blocks
-    get very different scales so that a scale byte read for the wrong row, block
-    or K step shows up."""
+    """Shapes made of whole 256 x 256 x 128 tiles; blocks get very different scales so that a scale
+    byte read for the wrong row, block or K step shows up."""
     M, N, K = shape
     rng = np.random.default_rng(M + N + fa)
     a = inputs.student_t_f32((M, K), seed=fa + 60) * np.exp2(rng.integers(-6, 6, (M, K // 32))).repeat(32, axis=1).astype(np.float32)
     b = inputs.gaussian_f32((N, K), seed=fb + 70, std=0.02) * np.exp2(rng.integers(-6, 6, (N, K // 32))).repeat(32, axis=1).astype(np.float32)
     ea, sa = oracle.quantize(a, 1, fa)
     eb, sb = oracle.quantize(b, 1, fb)
-    C_ref, C_abs = oracle.gemm(ea, sa, fa, eb, sb, fb, K, want_abs=True)
     C = mx.mx_gemm(to_dev(ea), to_dev(sa), fa, to_dev(eb), to_dev(sb), fb, K, dtype=dt)
-    got = to_host(C)
-    if dt == torch.bfloat16:
-        got = bf16_bits_to_f64(got)
-        C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5     # half a bf16 ulp of the result on top of the bound
-    check_gemm(got, C_ref, C_abs, str(shape), hw_term_for(oracle, ea, sa, fa, eb, sb, fb, K))
+    check_product(mx, oracle, C, ea, sa, fa, eb, sb, fb, K, str(shape), seed=M + fa)
 
 
 @pytest.mark.parametrize("fa", range(5), ids=NAMES)
 @pytest.mark.parametrize("fb", range(5), ids=NAMES)
-@pytest.mark.parametrize("shape,dt", [((256, 512, 1536), torch.float32), ((512, 256, 512), torch.bfloat16),
-                                      ((256, 256, 896), torch.float32)])
+@pytest.mark.parametrize("shape,dt", [((1024, 2048, 1536), torch.float32), ((2048, 1024, 512), torch.bfloat16),
+                                      ((1024, 2048, 896), torch.float32), ((256, 512, 640), torch.float32)])
 def test_tiled_kernel_all_format_pairs(mx, oracle, fa, fb, shape, dt):
     """Every FP8 / FP6 / FP4 pair on whole tiles: each element width has its own LDS layout and
     direct-load shape, so every (row, K block) must come back from the right slot.  Per-block
@@ -179,20 +175,16 @@ def test_tiled_kernel_all_format_pairs(mx, oracle, fa, fb, shape, dt):
     b = inputs.gaussian_f32((N, K), seed=fb + 90, std=0.02) * np.exp2(rng.integers(-6, 6, (N, K // 32))).repeat(32, axis=1).astype(np.float32)
     ea, sa = oracle.quantize(a, 1, fa)
     eb, sb = oracle.quantize(b, 1, fb)
-    C_ref, C_abs = oracle.gemm(ea, sa, fa, eb, sb, fb, K, want_abs=True)
     C = mx.mx_gemm(to_dev(ea), to_dev(sa), fa, to_dev(eb), to_dev(sb), fb, K, dtype=dt)
-    got = to_host(C)
-    if dt == torch.bfloat16:
-        got = bf16_bits_to_f64(got)
-        C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5     # half a bf16 ulp of the result on top of the bound
-    check_gemm(got, C_ref, C_abs, f"{NAMES[fa]}x{NAMES[fb]} {shape}", hw_term_for(oracle, ea, sa, fa, eb, sb, fb, K))
+    check_product(mx, oracle, C, ea, sa, fa, eb, sb, fb, K, f"{NAMES[fa]}x{NAMES[fb]} {shape}", seed=7 * fa + fb)
 
 
 @pytest.mark.parametrize("fa,fb", [(2, 2), (3, 4), (4, 0), (1, 3)], ids=["e3m2xe3m2", "e2m3xe2m1", "e2m1xe4m3", "e5m2xe2m3"])
-def test_tiled_kernel_one_hot_rows(mx, oracle, fa, fb):
+@pytest.mark.parametrize("M,N,K", [(2048, 1024, 512), (512, 256, 512)], ids=["tiled", "shared_k"])
+def test_tiled_kernel_one_hot_rows(mx, oracle, fa, fb, M, N, K):
     """A is one-hot per row (element k = m mod K is 1.0, scale byte 127): C[m][n] must reproduce
-    B[n][m mod K] exactly, which pins the K position of every element of every LDS slot."""
-    M, N, K = 512, 256, 512
+    B[n][m mod K] exactly, which pins the K position of every element of every LDS slot
+    (32 tiles: the LDS-tiled kernel; 2 tiles: the kernel that shares K among eight waves)."""
     a = np.zeros((M, K), np.float32)
     a[np.arange(M), np.arange(M) % K] = 1.0
     b = inputs.gaussian_f32((N, K), seed=95, std=1.0)
@@ -292,7 +284,7 @@ def test_gemm_qa_equals_quantize_then_gemm(mx, oracle, fa, rnd):
 
 QA_SHAPES = {"fused": (32768, 512, 512),
              "fused_k_tail": (32768, 512, 640),    # five K steps: the fused kernel's partial last scale group    # narrow output, 256 tiles: A is cast inside the tiled kernel's K loop
-             "twopass": (512, 768, 1024)}    # anything else on whole tiles: cast into a workspace, then the tiled kernel
+             "twopass": (2048, 1024, 1024)}    # anything else on whole tiles: cast into a workspace, then the tiled kernel
 
 
 @pytest.mark.parametrize("fa", [0, 1], ids=["e4m3", "e5m2"])
@@ -356,6 +348,23 @@ def sampled_check(mx, oracle, C, A, fa, B, fb, K, seed, n=2048):
         Bd = oracle.dequantize(B[0][un], B[1][un], fb, un.size, K, 1).astype(np.float64)
         hw = run_max_sum_entries(Ad[inv_m], Bd[inv_n])
     return got, C_ref, C_abs, hw
+
+
+def check_product(mx, oracle, C, ea, sa, fa, eb, sb, fb, K, tag, seed=0):
+    """C (device tensor, Float32 or bf16) against the reference: every entry when the output is
+    small, else corners, edges and 2048 random entries (the one-hot tests pin positions)."""
+    M, N = sa.shape[0], sb.shape[0]
+    bf16 = C.dtype == torch.bfloat16
+    if M * N <= 1 << 18:
+        C_ref, C_abs = oracle.gemm(ea, sa, fa, eb, sb, fb, K, want_abs=True)
+        got = to_host(C)
+        got = bf16_bits_to_f64(got) if bf16 else got
+        hw = hw_term_for(oracle, ea, sa, fa, eb, sb, fb, K)
+    else:
+        got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, (ea, sa), fa, (eb, sb), fb, K, seed=seed)
+    if bf16:
+        C_abs = C_abs + np.abs(np.nan_to_num(C_ref)) * 2.0 ** -8 / 1e-5     # half a bf16 ulp of the result on top of the bound
+    check_gemm(got, C_ref, C_abs, tag, hw)
 
 
 def test_config3_sampled(mx, oracle):
@@ -444,7 +453,7 @@ def test_config5_sampled(mx, oracle, rnd):
 def test_tiled_kernel_output_leading_dimension(mx, oracle, dt, pad):
     """C as a view with a leading dimension (the header allows any ldc >= N): the padding columns
     must stay untouched."""
-    M, N, K = 256, 512, 512
+    M, N, K = (2048, 1024, 512) if pad == 2 else (256, 512, 512)      # the LDS-tiled kernel / the shared-K kernel
     a = inputs.gaussian_f32((M, K), seed=120)
     b = inputs.gaussian_f32((N, K), seed=121, std=0.02)
     ea, sa = oracle.quantize(a, 1, 0)
@@ -454,12 +463,7 @@ def test_tiled_kernel_output_leading_dimension(mx, oracle, dt, pad):
     ref = mx.mx_gemm(to_dev(ea), to_dev(sa), 0, to_dev(eb), to_dev(sb), 0, K, dtype=dt)
     assert torch.equal(full[:, :N], ref)
     assert torch.all(full[:, N:] == 7.0)
-    C_ref, C_abs = oracle.gemm(ea, sa, 0, eb, sb, 0, K, want_abs=True)
-    got = to_host(ref)
-    if dt == torch.bfloat16:
-        got = bf16_bits_to_f64(got)
-        C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5
-    check_gemm(got, C_ref, C_abs, "ldc", hw_term_for(oracle, ea, sa, 0, eb, sb, 0, K))
+    check_product(mx, oracle, ref, ea, sa, 0, eb, sb, 0, K, "ldc")
 
 
 # ---------------------------------------------------------------------------------------------
@@ -605,19 +609,21 @@ def test_int8_gemm_full_size_sampled(mx, oracle):
     assert torch.equal(Cq.view(torch.int32), C.view(torch.int32))
 
 
-@pytest.mark.parametrize("shape", [(300, 520, 640), (512, 257, 512), (257, 512, 1024), (700, 300, 512)])
+@pytest.mark.parametrize("shape", [(300, 520, 640), (512, 257, 512), (257, 512, 1024), (700, 300, 512), (2100, 1100, 512),
+                                   (2048, 1030, 640), (2050, 1024, 544)])
 @pytest.mark.parametrize("fa,fb", [(0, 0), (2, 4)], ids=["e4m3xe4m3", "e3m2xe2m1"])
 def test_ragged_shapes_with_a_tiled_interior(mx, oracle, shape, fa, fb):
-    """M or N not a multiple of 256: whole tiles go to the tiled kernel, the fringe to the direct
-    kernel; also with A cast on load."""
+    """M or N not a multiple of 256.  With an interior of at least 32 whole tiles that interior goes
+    to the tiled kernel and the L-shaped fringe to the kernel for other shapes (to the direct kernel
+    when K is not a multiple of 128); smaller problems are one launch of the latter.  Also with A
+    cast on load."""
     M, N, K = shape
     a = inputs.student_t_bf16((M, K), seed=140)
     b = inputs.gaussian_f32((N, K), seed=141, std=0.02)
     ea, sa = oracle.quantize(a, 1, fa)
     eb, sb = oracle.quantize(b, 1, fb)
-    C_ref, C_abs = oracle.gemm(ea, sa, fa, eb, sb, fb, K, want_abs=True)
     C = mx.mx_gemm(to_dev(ea), to_dev(sa), fa, to_dev(eb), to_dev(sb), fb, K)
-    check_gemm(to_host(C), C_ref, C_abs, f"ragged {shape}", hw_term_for(oracle, ea, sa, fa, eb, sb, fb, K))
+    check_product(mx, oracle, C, ea, sa, fa, eb, sb, fb, K, f"ragged {shape}", seed=M)
     Cq = mx.mx_gemm_qa(to_dev(a), fa, RNE, to_dev(eb), to_dev(sb), fb)
     assert torch.equal(C.view(torch.int32), Cq.view(torch.int32))
 
@@ -692,16 +698,18 @@ def _gemm_q_case(mx, oracle, M, N, K, fa, fb, fc, rnd, special):
 @pytest.mark.parametrize("rnd", [RNE, AWAY], ids=["rne", "away"])
 @pytest.mark.parametrize("fa,fb", [(0, 0), (1, 4), (2, 2)], ids=["e4m3xe4m3", "e5m2xe2m1", "e3m2xe3m2"])
 def test_gemm_q_epilogue_cast(mx, oracle, fc, rnd, fa, fb):
-    """Whole tiles: the accumulators are cast in the tiled kernel's epilogue.  Plain data, and data
+    """Whole tiles, 32 of them: the accumulators are cast in the tiled kernel's epilogue.  Plain data, and data
     with NaN rows and columns, all-zero rows, tiny and huge rows and (E5M2) an Inf element."""
-    _gemm_q_case(mx, oracle, 512, 512, 640, fa, fb, fc, rnd, special=False)
-    s_ref = _gemm_q_case(mx, oracle, 256, 512, 512, fa, fb, fc, rnd, special=True)
+    _gemm_q_case(mx, oracle, 1024, 2048, 640, fa, fb, fc, rnd, special=False)
+    s_ref = _gemm_q_case(mx, oracle, 2048, 1024, 512, fa, fb, fc, rnd, special=True)
     assert (s_ref < 18).any()                        # the exact path inside the epilogue was taken
 
 
 @pytest.mark.parametrize("case", [(100, 72, 96, 0, 0, 0, RNE), (256, 256, 512, 0, 0, 5, RNE), (256, 256, 512, 2, 4, 4, 2),
-                                  (64, 100, 64, 5, 5, 5, AWAY), (2048, 2048, 256, 5, 5, 0, RNE), (300, 520, 640, 0, 3, 2, AWAY)],
-                         ids=["ragged", "int8_out", "truncated", "int8_all", "int8_split_route", "tiled_interior_plus_fringe"])
+                                  (64, 100, 64, 5, 5, 5, AWAY), (2048, 2048, 256, 5, 5, 0, RNE), (300, 520, 640, 0, 3, 2, AWAY),
+                                  (2100, 1100, 512, 0, 0, 1, RNE), (512, 512, 640, 2, 4, 0, RNE)],
+                         ids=["ragged", "int8_out", "truncated", "int8_all", "int8_split_route", "small_ragged",
+                              "tiled_interior_plus_fringe", "few_tiles"])
 def test_gemm_q_other_routes(mx, oracle, case):
     """Shapes, formats and modes the epilogue does not take go through a Float32 workspace: same bytes."""
     M, N, K, fa, fb, fc, rnd = case
