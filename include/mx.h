@@ -177,9 +177,13 @@ int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt,
  * run of 8 consecutive K products in fixed point with 14 bits below the run's
  * largest product, which is exact for FP6 E2M3 / FP4 E2M1 operands and loses at
  * most 14 * 2^-14 of each run's largest product otherwise.
- * (Problems with at most 128 rows of A split K over the eight waves of a
- * work-group and add the eight partial sums in a fixed order: deterministic,
- * but a different Float32 rounding than the other kernels' K order.)
+ * Which kernel runs depends on the shape and the formats only, never on the
+ * data or on timing, so a result is reproducible.  Problems with at most 128
+ * rows of A, problems that are not made of whole 256 x 256 tiles (K a multiple
+ * of 128) and problems of fewer than 32 such tiles split K over the eight waves
+ * of a work-group and add the eight partial sums in a fixed order: a different
+ * Float32 rounding than the K order of the LDS-tiled kernel, which takes the
+ * large problems.
  * C is row-major [M][N] of type c_dt with leading dimension ldc >= N (elements;
  * any value, a multiple of 16 bytes is fastest); the C pointer is 16-byte
  * aligned; bf16 output is the Float32 accumulator rounded to nearest even.
@@ -212,8 +216,10 @@ int mx_gemm(int64_t M, int64_t N, int64_t K,
  * memory pool in stream order (hipMallocAsync / hipFreeAsync on hip_stream) --
  * the only kind of allocation the library makes (MX_INT8 takes the same route,
  * and large MX_INT8 products take a workspace of their own, see mx_gemm); if
- * the pool refuses, the fused kernel runs instead.  Every other problem casts in
- * registers in the direct kernel.  The in-kernel casts round to nearest:
+ * the pool refuses, the fused kernel runs instead.  Problems that mx_gemm gives
+ * to its kernel for few rows / few tiles / ragged shapes cast A into such a
+ * workspace as well; what remains (K not a multiple of 128) casts in registers
+ * in the direct kernel.  The in-kernel casts round to nearest:
  * MX_ROUND_TOWARD_ZERO always casts into the workspace first (MX_ERR_LAUNCH if
  * the pool refuses); MX_ROUND_STOCHASTIC is MX_ERR_ENUM.
  */
