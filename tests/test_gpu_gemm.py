@@ -719,8 +719,9 @@ def test_gemm_q_other_routes(mx, oracle, case):
 # ---------------------------------------------------------------------------------------------
 # Few rows of A (decoding shapes): the kernel that shares the K range among eight waves.
 # ---------------------------------------------------------------------------------------------
-FEW_ROWS = [(M, N, K) for M in (1, 7, 32, 33, 64, 100, 128) for (N, K) in ((40, 32), (72, 96), (1000, 1056))] + \
-           [(1, 4096, 4128), (33, 2048, 4128), (128, 1024, 2080)]
+# K a multiple of 128: operands staged through LDS; other K: straight into the instruction's layout
+FEW_ROWS = [(M, N, K) for M in (1, 7, 32, 33, 64, 100, 128) for (N, K) in ((40, 32), (72, 96), (1000, 1056), (200, 1024))] + \
+           [(1, 4096, 4128), (33, 2048, 4128), (128, 1024, 2080), (16, 4096, 4096), (100, 1000, 1920)]
 
 
 @pytest.mark.parametrize("M,N,K", FEW_ROWS, ids=lambda v: str(v))
