@@ -194,8 +194,10 @@ int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt,
  * split every element exactly into two FP6 E2M3 halves (a workspace of
  * (M + N) * K * 3.125 bytes from the stream's memory pool, as described at
  * mx_gemm_qa) and run one E2M3 product of depth 4K, whose products are exact in
- * the block-scaled instruction; both routes differ from the exact sum only by
- * Float32 accumulation rounding.
+ * the block-scaled instruction; with M <= 128 and K >= 256 eight waves share
+ * the blocks of each 32 x 32 tile and their partial tiles are added in a fixed
+ * order.  All routes differ from the exact sum only by Float32 accumulation
+ * rounding.
  */
 int mx_gemm(int64_t M, int64_t N, int64_t K,
             const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,

@@ -141,6 +141,91 @@ __global__ __launch_bounds__(256) void gemm_int8_kernel(int64_t M, int64_t N, in
     }
 }
 
+// Few rows of A (a decoding step): the kernel above gives such a problem N / 32 waves that each walk
+// the whole K range alone, one load-then-multiply after the other.  Here eight waves share 32 rows
+// x 32 columns of C, each a contiguous eighth of the blocks, with the operands of four blocks
+// requested before the first is multiplied; the eight partial sums meet in LDS and are added in
+// the order w0 + w1 + ... + w7.
+constexpr int I8_WAVES = 8, I8_U = 4;
+template <int CDT>
+__global__ __launch_bounds__(64 * I8_WAVES) void gemm_int8_shared_k_kernel(int64_t M, int64_t N, int64_t K,
+                                                                            const uint8_t *__restrict__ Ae, const uint8_t *__restrict__ As,
+                                                                            const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
+                                                                            void *__restrict__ C, int64_t ldc)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[I8_WAVES * 32];
+    __shared__ float red[I8_WAVES - 1][16][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    uint8_t *lds = lds_all + wave * 32;
+    const int64_t m0 = (int64_t)blockIdx.y * 32, n0 = (int64_t)blockIdx.x * 32;
+    const int i = lane & 31, g = lane >> 5;
+    const int64_t nkb = K / BLOCK;
+    const int64_t chunk = (nkb + I8_WAVES - 1) / I8_WAVES;
+    const int64_t kb_begin = wave * chunk, kb_end = kb_begin + chunk < nkb ? kb_begin + chunk : nkb;
+    const int64_t row = m0 + i, col = n0 + i;
+    const bool rv = row < M, cv = col < N;
+    const int64_t rowc = rv ? row : 0, colc = cv ? col : 0;   // keep addresses in range for masked lanes
+
+    float acc[16];
+#pragma unroll
+    for (int t = 0; t < 16; t++) acc[t] = 0.f;
+
+    for (int64_t kb0 = kb_begin; kb0 < kb_end; kb0 += I8_U) {
+        uint4 qa[I8_U], qb[I8_U];
+        uint32_t sa[I8_U], sb[I8_U];
+#pragma unroll
+        for (int u = 0; u < I8_U; u++) {
+            const int64_t kb = kb0 + u < kb_end ? kb0 + u : kb_end - 1;   // past the slice: a valid block, result unused
+            qa[u] = ld16(Ae + rowc * K + kb * BLOCK + 16 * g);
+            qb[u] = ld16(Be + colc * K + kb * BLOCK + 16 * g);
+            sa[u] = As[rowc * nkb + kb];
+            sb[u] = Bs[colc * nkb + kb];
+        }
+#pragma unroll
+        for (int u = 0; u < I8_U; u++) {
+            if (kb0 + u >= kb_end) break;                                 // wave-uniform
+            if (g == 0) lds[i] = (uint8_t)sa[u];
+            wave_lds_sync8();
+            uint32_t sa4[4];
+#pragma unroll
+            for (int q = 0; q < 4; q++) sa4[q] = *reinterpret_cast<const uint32_t *>(lds + 8 * q + 4 * g);
+            const v4i_t a = rv ? v4i_t{(int)qa[u].x, (int)qa[u].y, (int)qa[u].z, (int)qa[u].w} : v4i_t{0, 0, 0, 0};
+            const v4i_t b = cv ? v4i_t{(int)qb[u].x, (int)qb[u].y, (int)qb[u].z, (int)qb[u].w} : v4i_t{0, 0, 0, 0};
+            v16i_t z;
+#pragma unroll
+            for (int t = 0; t < 16; t++) z[t] = 0;
+            const v16i_t p = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, z, 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < 16; t++) {
+                const uint32_t sat = (sa4[t >> 2] >> (8 * (t & 3))) & 0xFFu;
+                const int e = (int)sat + (int)sb[u] - 254 - 12;
+                float term = ldexpf((float)p[t], e);
+                if (sat == SCALE_NAN || sb[u] == SCALE_NAN) term = __uint_as_float(0x7FC00000u);
+                acc[t] += term;
+            }
+            wave_lds_sync8();   // the line is rewritten for the next block
+        }
+    }
+
+    if (wave > 0) {
+#pragma unroll
+        for (int t = 0; t < 16; t++) red[wave - 1][t][lane] = acc[t];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int t = 0; t < 16; t++) {
+        float v = acc[t];
+#pragma unroll
+        for (int w = 0; w < I8_WAVES - 1; w++) v += red[w][t][lane];
+        const int64_t r = m0 + 8 * (t / 4) + 4 * g + (t % 4);
+        if (r < M && cv) {
+            if (CDT == DT_F32) reinterpret_cast<float *>(C)[r * ldc + col] = v;
+            else reinterpret_cast<uint16_t *>(C)[r * ldc + col] = (uint16_t)f32_to_bf16_bits(v);
+        }
+    }
+}
+
 static hipError_t launch_int8_direct(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint8_t *Be,
                                      const uint8_t *Bs, void *C, int c_dt, int64_t ldc, const uint32_t *run_if, hipStream_t st)
 {
@@ -179,6 +264,14 @@ hipError_t launch_gemm_int8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, 
             return e != hipSuccess ? e : f;
         }
         (void)hipGetLastError();   // no workspace: the direct kernel needs none
+    }
+    if (M > 0 && M <= 128 && N > 0 && K >= 8 * BLOCK) {   // few rows: eight waves share the blocks of a tile
+        const dim3 grid((unsigned)((N + 31) / 32), (unsigned)((M + 31) / 32));
+        if (c_dt == DT_F32)
+            hipLaunchKernelGGL((gemm_int8_shared_k_kernel<DT_F32>), grid, dim3(64 * I8_WAVES), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc);
+        else
+            hipLaunchKernelGGL((gemm_int8_shared_k_kernel<DT_BF16>), grid, dim3(64 * I8_WAVES), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc);
+        return hipGetLastError();
     }
     return launch_int8_direct(M, N, K, Ae, As, Be, Bs, C, c_dt, ldc, nullptr, st);
 }

@@ -472,7 +472,9 @@ def test_tiled_kernel_output_leading_dimension(mx, oracle, dt, pad):
 INT8 = 5
 
 
-@pytest.mark.parametrize("shape", [(1, 1, 32), (17, 33, 64), (64, 64, 96), (130, 257, 416), (300, 40, 1024), (256, 512, 1536)])
+@pytest.mark.parametrize("shape", [(1, 1, 32), (17, 33, 64), (64, 64, 96), (130, 257, 416), (300, 40, 1024), (256, 512, 1536),
+                                   # few rows and at least 8 blocks: eight waves share the blocks of a tile
+                                   (1, 200, 512), (33, 100, 1056), (128, 72, 288), (100, 1000, 4096)])
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 def test_int8_gemm_shapes(mx, oracle, shape, dt):
     M, N, K = shape
@@ -507,6 +509,33 @@ def test_int8_gemm_one_hot_and_exact_integers(mx, oracle):
     s = np.full((M, K // 32), 127 + 6, np.uint8)          # X = 2^6: element value = the integer code
     C = to_host(mx.mx_gemm(to_dev(qa.view(np.uint8)), to_dev(s), INT8, to_dev(qb.view(np.uint8)), to_dev(s[:N]), INT8, K))
     assert np.array_equal(C, (qa.astype(np.int64) @ qb.astype(np.int64).T).astype(np.float32))
+
+
+def test_int8_gemm_few_rows_exact(mx, oracle):
+    """Few rows, K shared by eight waves: integer-valued operands at X = 2^6 with |sum| < 2^24 give exactly
+    known integers whatever the order of the partial sums; one-hot rows pin every block of every slice;
+    NaN scales in the first and the last slice."""
+    M, N, K = 48, 200, 1120                                # 35 blocks: slices of 5, the last wave has none
+    rng = np.random.default_rng(15)
+    qa = rng.integers(-20, 21, (M, K)).astype(np.int8)
+    qb = rng.integers(-20, 21, (N, K)).astype(np.int8)
+    sa = np.full((M, K // 32), 127 + 6, np.uint8)
+    sb = np.full((N, K // 32), 127 + 6, np.uint8)
+    C = to_host(mx.mx_gemm(to_dev(qa.view(np.uint8)), to_dev(sa), INT8, to_dev(qb.view(np.uint8)), to_dev(sb), INT8, K))
+    assert np.array_equal(C, (qa.astype(np.float64) @ qb.astype(np.float64).T).astype(np.float32))
+    hot = np.zeros((M, K), np.float32)
+    pos = (np.arange(M) * 23 + 3) % K
+    hot[np.arange(M), pos] = 1.0
+    b = inputs.gaussian_f32((N, K), seed=138)
+    eh, sh = oracle.quantize(hot, 1, INT8)
+    eb, sbb = oracle.quantize(b, 1, INT8)
+    Bd = oracle.dequantize(eb, sbb, INT8, N, K, 1)
+    C = to_host(mx.mx_gemm(to_dev(eh), to_dev(sh), INT8, to_dev(eb), to_dev(sbb), INT8, K))
+    assert np.array_equal(C, Bd[:, pos].T.astype(np.float32))
+    sh[7, 0] = 0xFF
+    sbb[9, K // 32 - 1] = 0xFF
+    C = to_host(mx.mx_gemm(to_dev(eh), to_dev(sh), INT8, to_dev(eb), to_dev(sbb), INT8, K))
+    assert np.isnan(C[7]).all() and np.isnan(C[:, 9]).all() and np.isnan(C).sum() == N + M - 1
 
 
 def test_int8_gemm_nan_scale_and_mixed_pair_refused(mx, oracle):
