@@ -265,7 +265,11 @@ hipError_t launch_gemm_int8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, 
         }
         (void)hipGetLastError();   // no workspace: the direct kernel needs none
     }
-    if (M > 0 && M <= 128 && N > 0 && K >= 8 * BLOCK) {   // few rows: eight waves share the blocks of a tile
+    // few rows: eight waves share the blocks of a tile.  Also where the direct kernel would put at most one
+    // wave on a SIMD and K is long (measured: 256 x 4096 x 4096 81 -> 66 us, 1024 x 1024 x 4096 84 -> 64 us;
+    // with 2048 tiles of 32 x 32 the direct kernel is ahead again, 114 vs 124 us)
+    const int64_t tiles32 = ((M + 31) / 32) * ((N + 31) / 32);
+    if (M > 0 && N > 0 && ((M <= 128 && K >= 8 * BLOCK) || (tiles32 <= 1024 && K >= 4096))) {
         const dim3 grid((unsigned)((N + 31) / 32), (unsigned)((M + 31) / 32));
         if (c_dt == DT_F32)
             hipLaunchKernelGGL((gemm_int8_shared_k_kernel<DT_F32>), grid, dim3(64 * I8_WAVES), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc);

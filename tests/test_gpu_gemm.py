@@ -474,7 +474,7 @@ INT8 = 5
 
 @pytest.mark.parametrize("shape", [(1, 1, 32), (17, 33, 64), (64, 64, 96), (130, 257, 416), (300, 40, 1024), (256, 512, 1536),
                                    # few rows and at least 8 blocks: eight waves share the blocks of a tile
-                                   (1, 200, 512), (33, 100, 1056), (128, 72, 288), (100, 1000, 4096)])
+                                   (1, 200, 512), (33, 100, 1056), (128, 72, 288), (100, 1000, 4096), (200, 130, 4128)])
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 def test_int8_gemm_shapes(mx, oracle, shape, dt):
     M, N, K = shape
