@@ -350,8 +350,7 @@ def test_added_modes_adversarial(mx, oracle, fmt, mode, axis):
 
 def test_stochastic_leading_dimension_and_large_index(mx, oracle):
     """A source view with ld > cols numbers its elements by (row, col), not by address; a tall
-    tensor takes the element counter past 2^25 (64-bit index arithmetic is not exercised below
-    2^32 elements, which would need 8 GiB: the index type is int64 throughout)."""
+    tensor takes the element counter past 2^25."""
     full = inputs.gaussian_f32((128, 160), seed=80)
     view = to_dev(full)[:, :96]
     e, s = mx.mx_quantize_sr(view, 1, 0, 5)

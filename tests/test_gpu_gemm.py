@@ -253,7 +253,9 @@ def test_bf16_output_is_rounded_f32_output(mx, oracle):
     C32 = mx.mx_gemm(ga[0], ga[1], 2, gb[0], gb[1], 2, K, dtype=torch.float32)
     C16 = mx.mx_gemm(ga[0], ga[1], 2, gb[0], gb[1], 2, K, dtype=torch.bfloat16)
     assert torch.equal(C32.to(torch.bfloat16), C16)      # PyTorch's conversion is round-to-nearest-even
-    C_ref = oracle.gemm(to_host(ga[0]), to_host(ga[1]), 2, to_host(gb[0]), to_host(gb[1]), 2, K)
+    (ea, sa), (eb, sb) = oracle.quantize(a, 1, 2), oracle.quantize(b, 1, 2)
+    assert np.array_equal(to_host(ga[0]), ea) and np.array_equal(to_host(gb[0]), eb)
+    C_ref = oracle.gemm(ea, sa, 2, eb, sb, 2, K)
     ref16 = inputs.f32_to_bf16_bits(C_ref.astype(np.float32)).astype(np.int32)
     got16 = to_host(C16).astype(np.int32)
     # within one bf16 ulp of the rounded reference (sign-magnitude bit patterns of equal sign differ by <= 1)
@@ -377,7 +379,7 @@ def test_config3_sampled(mx, oracle):
     gb = mx.mx_quantize(wd, 0, 0)          # logical K x N weight, blocks along K -> stored [N][K]
     C = mx.mx_gemm_qa(ad, 0, RNE, gb[0], gb[1], 0, dtype=torch.float32)
     ea, sa = oracle.quantize(a, 1, 0)
-    B = (to_host(gb[0]), to_host(gb[1]))
+    B = reference_cast(oracle, w, 0, 0, RNE, gb)
     got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, (ea, sa), 0, B, 0, K, seed=3)
     check_gemm(got, C_ref, C_abs, "config3", hw)
 
@@ -390,10 +392,18 @@ def test_config3_wide_sampled(mx, oracle):
     gb = mx.mx_quantize(to_dev(w), 0, 0)
     C = mx.mx_gemm_qa(to_dev(a), 0, RNE, gb[0], gb[1], 0, dtype=torch.bfloat16)
     ea, sa = oracle.quantize(a, 1, 0)
-    B = (to_host(gb[0]), to_host(gb[1]))
+    B = reference_cast(oracle, w, 0, 0, RNE, gb)
     got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, (ea, sa), 0, B, 0, K, seed=5)
     C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5     # bf16 output: half an ulp of the result on top
     check_gemm(got, C_ref, C_abs, "config3 N=11008", hw)
+
+
+def reference_cast(oracle, src, axis, fmt, rnd, gpu):
+    """The reference's own cast of src, which the reference product is computed from; the GPU's
+    bytes must be the same, every one of them."""
+    e, s = oracle.quantize(src, axis, fmt, rnd)
+    assert np.array_equal(to_host(gpu[0]), e) and np.array_equal(to_host(gpu[1]), s)
+    return e, s
 
 
 def cast_sample_matches(oracle, src, axis, fmt, rnd, gpu, lo, hi):
@@ -415,9 +425,9 @@ def test_config4_sampled(mx, oracle):
     assert cast_sample_matches(oracle, act, 1, 2, RNE, ga, 1000, 1256)
     assert cast_sample_matches(oracle, w, 0, 4, RNE, gb, 28672 - 256, 28672)
     C = mx.mx_gemm(ga[0], ga[1], 2, gb[0], gb[1], 4, K, dtype=torch.bfloat16)
+    A = reference_cast(oracle, act, 1, 2, RNE, ga)
+    B = reference_cast(oracle, w, 0, 4, RNE, gb)
     del w
-    A = (to_host(ga[0]), to_host(ga[1]))
-    B = (to_host(gb[0]), to_host(gb[1]))
     got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, A, 2, B, 4, K, seed=6)
     C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5
     check_gemm(got, C_ref, C_abs, "config4", hw)
@@ -440,10 +450,12 @@ def test_config5_sampled(mx, oracle, rnd):
     assert cast_sample_matches(oracle, X, 1, fmt, rnd, X1, 0, 512) and cast_sample_matches(oracle, X, 0, fmt, rnd, X0, 1024, 1536)
     assert cast_sample_matches(oracle, W, 1, fmt, rnd, W1, 0, 2048) and cast_sample_matches(oracle, W, 0, fmt, rnd, W0, 0, 8192)
     assert cast_sample_matches(oracle, dY, 1, fmt, rnd, Y1, 16000, 16384) and cast_sample_matches(oracle, dY, 0, fmt, rnd, Y0, 4096, 4352)
-    h = lambda g: (to_host(g[0]), to_host(g[1]))
-    for name, A, B, K in (("fwd", X1, W0, H), ("dgrad", Y1, W1, F), ("wgrad", X0, Y0, T)):
+    ref = lambda src, axis, g: reference_cast(oracle, src, axis, fmt, rnd, g)
+    for name, A, B, Ah, Bh, K in (("fwd", X1, W0, ref(X, 1, X1), ref(W, 0, W0), H),
+                                  ("dgrad", Y1, W1, ref(dY, 1, Y1), ref(W, 1, W1), F),
+                                  ("wgrad", X0, Y0, ref(X, 0, X0), ref(dY, 0, Y0), T)):
         C = mx.mx_gemm(A[0], A[1], fmt, B[0], B[1], fmt, K, dtype=torch.float32)
-        got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, h(A), fmt, h(B), fmt, K, seed=7, n=1024)
+        got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, Ah, fmt, Bh, fmt, K, seed=7, n=1024)
         check_gemm(got, C_ref, C_abs, f"config5 {name}", hw)
         del C
 
@@ -627,8 +639,8 @@ def test_int8_gemm_full_size_sampled(mx, oracle):
     ga = mx.mx_quantize(to_dev(a), 1, INT8)
     gb = mx.mx_quantize(to_dev(w), 0, INT8)
     C = mx.mx_gemm(ga[0], ga[1], INT8, gb[0], gb[1], INT8, K, dtype=torch.float32)
-    A = (to_host(ga[0]), to_host(ga[1]))
-    B = (to_host(gb[0]), to_host(gb[1]))
+    A = reference_cast(oracle, a, 1, INT8, RNE, ga)
+    B = reference_cast(oracle, w, 0, INT8, RNE, gb)
     rng = np.random.default_rng(8)
     mi, ni = rng.integers(0, M, 2048), rng.integers(0, N, 2048)
     C_ref, C_abs = oracle.gemm_entries(A[0], A[1], INT8, B[0], B[1], INT8, K, mi, ni)

@@ -1,0 +1,144 @@
+"""GPU parity at sizes past the 32-bit limits: tensors of more than 2^31 elements and more than
+2^32 bytes, so that an index or a byte offset computed in 32 bits anywhere on the path lands on
+the wrong bytes.  The CPU reference recomputes sampled rows, columns and entries, chosen at the
+highest addresses and around the 2^31-element line."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2310_10537_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import same_floats, to_dev, to_host  # noqa: E402
+from test_gpu_gemm import check_gemm, sampled_check  # noqa: E402
+
+RNE = 0
+PIECE_ROWS, COLS, PIECES = 2048, 65536, 20          # 40960 x 65536 = 2.68e9 elements, 5.4e9 source bytes
+ROWS = PIECE_ROWS * PIECES
+
+
+@pytest.fixture(scope="module")
+def mx():
+    from paper_2310_10537_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.lib()
+    return binding
+
+
+def piece_shift(p):
+    return p % 7 - 3
+
+
+def scaled_bits(piece_bits, k):
+    """bf16 bit patterns times 2^k; exact for the N(0,1) piece (no overflow, no subnormals reached)."""
+    f = (piece_bits.astype(np.uint32) << 16).view(np.float32) * np.float32(2.0 ** k)
+    out = (f.view(np.uint32) >> 16).astype(np.uint16)
+    assert np.array_equal((out.astype(np.uint32) << 16).view(np.float32), f)
+    return out
+
+
+@pytest.fixture(scope="module")
+def big():
+    """The big bf16 tensor: twenty copies of one seeded 2048 x 65536 N(0,1) piece, copy p scaled
+    by 2^(p % 7 - 3) so that neighbouring copies differ.  Returns (host piece bits, device tensor)."""
+    piece = inputs.gaussian_bf16((PIECE_ROWS, COLS), seed=900)
+    pd = to_dev(piece)
+    x = torch.empty((ROWS, COLS), dtype=torch.bfloat16, device="cuda")
+    for p in range(PIECES):
+        x[p * PIECE_ROWS:(p + 1) * PIECE_ROWS] = pd * (2.0 ** piece_shift(p))
+    torch.cuda.synchronize()
+    yield piece, x
+    del x
+    torch.cuda.empty_cache()
+
+
+def host_rows(piece, r0, r1):
+    out = np.empty((r1 - r0, COLS), np.uint16)
+    for r in range(r0, r1):
+        out[r - r0] = scaled_bits(piece[r % PIECE_ROWS], piece_shift(r // PIECE_ROWS))
+    return out
+
+
+def host_cols(piece, c0, c1):
+    return np.concatenate([scaled_bits(piece[:, c0:c1], piece_shift(p)) for p in range(PIECES)], axis=0)
+
+
+ROW_SAMPLES = [(0, 32), (32768 - 16, 32768 + 16), (ROWS - 64, ROWS)]       # row 32768 starts at element 2^31
+COL_SAMPLES = [(0, 64), (30016, 30080), (COLS - 64, COLS)]
+
+
+@pytest.mark.parametrize("fmt", [0, 4], ids=["fp8_e4m3", "fp4_e2m1"])
+def test_cast_and_dequantize_beyond_2_31_elements(mx, oracle, big, fmt):
+    piece, x = big
+    bits = 8 if fmt == 0 else 4
+    # blocks along the rows' own axis
+    e, s = mx.mx_quantize(x, 1, fmt, RNE)
+    torch.cuda.synchronize()
+    assert e.shape == (ROWS, COLS * bits // 8) and s.shape == (ROWS, COLS // 32)
+    y = mx.mx_dequantize(e, s, fmt, ROWS, COLS, 1, dtype=torch.bfloat16)
+    for r0, r1 in ROW_SAMPLES:
+        src = host_rows(piece, r0, r1)
+        assert np.array_equal(to_host(x[r0:r1]), src)
+        e_ref, s_ref = oracle.quantize(src, 1, fmt, RNE)
+        assert np.array_equal(to_host(e[r0:r1]), e_ref), (fmt, r0)
+        assert np.array_equal(to_host(s[r0:r1]), s_ref), (fmt, r0)
+        y_ref = oracle.dequantize(e_ref, s_ref, fmt, r1 - r0, COLS, 1)
+        assert same_floats(to_host(y[r0:r1]), inputs.f32_to_bf16_bits(y_ref)), (fmt, r0)
+    del e, s, y
+    # blocks along axis 0: output line c holds column c, 40960 elements long
+    e, s = mx.mx_quantize(x, 0, fmt, RNE)
+    torch.cuda.synchronize()
+    assert e.shape == (COLS, ROWS * bits // 8) and s.shape == (COLS, ROWS // 32)
+    y = mx.mx_dequantize(e, s, fmt, ROWS, COLS, 0, dtype=torch.bfloat16)      # back to [ROWS][COLS]
+    assert y.shape == (ROWS, COLS)
+    for c0, c1 in COL_SAMPLES:
+        src = host_cols(piece, c0, c1)
+        e_ref, s_ref = oracle.quantize(src, 0, fmt, RNE)
+        assert np.array_equal(to_host(e[c0:c1]), e_ref), (fmt, c0)
+        assert np.array_equal(to_host(s[c0:c1]), s_ref), (fmt, c0)
+        y_ref = oracle.dequantize(e_ref, s_ref, fmt, ROWS, c1 - c0, 0)
+        assert same_floats(to_host(y[:, c0:c1]), inputs.f32_to_bf16_bits(y_ref)), (fmt, c0)
+    del e, s, y
+    torch.cuda.empty_cache()
+
+
+def test_dual_cast_beyond_2_31_elements(mx, oracle, big):
+    piece, x = big
+    (e1, s1), (e0, s0) = mx.mx_quantize_dual(x, 0, RNE)
+    torch.cuda.synchronize()
+    for r0, r1 in ROW_SAMPLES:
+        e_ref, s_ref = oracle.quantize(host_rows(piece, r0, r1), 1, 0, RNE)
+        assert np.array_equal(to_host(e1[r0:r1]), e_ref) and np.array_equal(to_host(s1[r0:r1]), s_ref)
+    for c0, c1 in COL_SAMPLES:
+        e_ref, s_ref = oracle.quantize(host_cols(piece, c0, c1), 0, 0, RNE)
+        assert np.array_equal(to_host(e0[c0:c1]), e_ref) and np.array_equal(to_host(s0[c0:c1]), s_ref)
+    del e1, s1, e0, s0
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_gemm_output_beyond_2_31_entries(mx, oracle, dt):
+    """49152 x 49152 output (2.4e9 entries; 9.7e9 bytes as Float32), K = 512, on the tiled kernel."""
+    M = N = 49152
+    K = 512
+    a = inputs.gaussian_bf16((M, K), seed=910)
+    b = inputs.gaussian_bf16((N, K), seed=911)
+    Ah, Bh = oracle.quantize(a, 1, 0, RNE), oracle.quantize(b, 1, 0, RNE)
+    C = mx.mx_gemm(to_dev(Ah[0]), to_dev(Ah[1]), 0, to_dev(Bh[0]), to_dev(Bh[1]), 0, K, dtype=dt)
+    torch.cuda.synchronize()
+    assert C.shape == (M, N)
+    got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, Ah, 0, Bh, 0, K, seed=912)
+    if dt == torch.bfloat16:
+        C_abs = C_abs + np.abs(C_ref) * 2.0 ** -8 / 1e-5
+    check_gemm(got, C_ref, C_abs, "large C", hw)
+    # the last rows in full: every column tile of the highest row tile
+    mi = np.repeat(np.arange(M - 2, M), N)
+    ni = np.tile(np.arange(N), 2)
+    ref, ref_abs = oracle.gemm_entries(Ah[0], Ah[1], 0, Bh[0], Bh[1], 0, K, mi, ni)
+    got = C[M - 2:].float().cpu().numpy().astype(np.float64).reshape(-1)
+    if dt == torch.bfloat16:
+        ref_abs = ref_abs + np.abs(ref) * 2.0 ** -8 / 1e-5
+    check_gemm(got, ref, ref_abs, "large C last rows", None)
+    del C
+    torch.cuda.empty_cache()
