@@ -142,3 +142,53 @@ def test_gemm_output_beyond_2_31_entries(mx, oracle, dt):
     check_gemm(got, ref, ref_abs, "large C last rows", None)
     del C
     torch.cuda.empty_cache()
+
+
+def test_stochastic_counter_beyond_2_32(mx, oracle):
+    """286720 x 65536 bf16 (1.9e10 elements): the generator's counter, element number / 4, passes
+    2^32 at row 262144, so its upper word is in use.  Blocks on both sides of that row and at the
+    end are recomputed with offsets drawn per element number."""
+    SR, fmt, seed = 3, 4, 0x1234567890ABCDEF
+    pieces = 140
+    rows = pieces * PIECE_ROWS
+    piece = inputs.gaussian_bf16((PIECE_ROWS, COLS), seed=901)
+    pd = to_dev(piece)
+    x = torch.empty((rows, COLS), dtype=torch.bfloat16, device="cuda")
+    for p in range(pieces):
+        x[p * PIECE_ROWS:(p + 1) * PIECE_ROWS] = pd
+    del pd
+    torch.cuda.synchronize()
+
+    def block(values, numbers):
+        u = np.array([oracle.sr_uniform(seed, int(e)) for e in numbers])
+        v = (values.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        sb, codes = oracle.quantize_block(v, fmt, SR, u=u)
+        c = codes.astype(np.uint8)
+        return sb, c[0::2] | (c[1::2] << 4)                      # FP4: two codes per byte, first in the low half
+
+    sample_rows = (0, 262143, 262144, 262145, rows - 1)
+    e, s = mx.mx_quantize_sr(x, 1, fmt, seed)
+    torch.cuda.synchronize()
+    eh = {r: to_host(e[r]) for r in sample_rows}
+    sh = {r: to_host(s[r]) for r in sample_rows}
+    del e, s
+    for r in sample_rows:
+        for b in (0, 1, 1000, COLS // 32 - 1):
+            cols = np.arange(b * 32, b * 32 + 32)
+            sb, packed = block(piece[r % PIECE_ROWS, cols], r * COLS + cols)
+            assert sh[r][b] == sb, (r, b)
+            assert np.array_equal(eh[r][b * 16:(b + 1) * 16], packed), (r, b)
+
+    sample_cols = (0, 1, 40001, COLS - 1)
+    e, s = mx.mx_quantize_sr(x, 0, fmt, seed)
+    torch.cuda.synchronize()
+    eh = {c: to_host(e[c]) for c in sample_cols}
+    sh = {c: to_host(s[c]) for c in sample_cols}
+    del e, s, x
+    torch.cuda.empty_cache()
+    for c in sample_cols:
+        for rb in (0, 8191, 8192, 8193, rows // 32 - 1):
+            rr = np.arange(rb * 32, rb * 32 + 32)
+            sb, packed = block(piece[rr % PIECE_ROWS, c], rr * COLS + c)
+            assert sh[c][rb] == sb, (c, rb)
+            assert np.array_equal(eh[c][rb * 16:(rb + 1) * 16], packed), (c, rb)
