@@ -190,14 +190,14 @@ int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt,
  * fmtA / fmtB may differ, except that MX_INT8 pairs only with MX_INT8 (anything
  * else is MX_ERR_UNSUPPORTED).  That pair runs the integer matrix instruction
  * block by block -- every block sum is an exact integer -- and adds the scaled
- * block sums in Float32; problems of at least 64 whole 256 x 256 tiles instead
- * split every element exactly into two FP6 E2M3 halves (a workspace of
+ * block sums in Float32; problems of at least 96 whole 256 x 256 tiles (64 when
+ * K < 1024) instead split every element exactly into two FP6 E2M3 halves (a workspace of
  * (M + N) * K * 3.125 bytes from the stream's memory pool, as described at
  * mx_gemm_qa) and run one E2M3 product of depth 4K, whose products are exact in
- * the block-scaled instruction; with M <= 128 and K >= 256 eight waves share
- * the blocks of each 32 x 32 tile and their partial tiles are added in a fixed
- * order.  All routes differ from the exact sum only by Float32 accumulation
- * rounding.
+ * the block-scaled instruction; few rows (M <= 128, K >= 256) and mid-size
+ * problems with a long K let eight waves share the K range of each 32-column
+ * tile and add their partial tiles in a fixed order.  All routes differ from
+ * the exact sum only by Float32 accumulation rounding.
  */
 int mx_gemm(int64_t M, int64_t N, int64_t K,
             const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,

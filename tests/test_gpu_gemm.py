@@ -486,7 +486,10 @@ INT8 = 5
 
 @pytest.mark.parametrize("shape", [(1, 1, 32), (17, 33, 64), (64, 64, 96), (130, 257, 416), (300, 40, 1024), (256, 512, 1536),
                                    # few rows and at least 8 blocks: eight waves share the blocks of a tile
-                                   (1, 200, 512), (33, 100, 1056), (128, 72, 288), (100, 1000, 4096), (200, 130, 4128)])
+                                   (1, 200, 512), (33, 100, 1056), (128, 72, 288), (100, 1000, 4096), (200, 130, 4128),
+                                   # K a multiple of 128: the same with operands staged through LDS
+                                   (33, 100, 1024), (128, 72, 384), (64, 40, 256), (200, 130, 4096), (7, 33, 2176), (300, 520, 1024),
+                                   (2048, 2048, 1024)])
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 def test_int8_gemm_shapes(mx, oracle, shape, dt):
     M, N, K = shape
@@ -523,11 +526,12 @@ def test_int8_gemm_one_hot_and_exact_integers(mx, oracle):
     assert np.array_equal(C, (qa.astype(np.int64) @ qb.astype(np.int64).T).astype(np.float32))
 
 
-def test_int8_gemm_few_rows_exact(mx, oracle):
+@pytest.mark.parametrize("K", [1120, 1152], ids=["k1120", "k1152_staged"])
+def test_int8_gemm_few_rows_exact(mx, oracle, K):
     """Few rows, K shared by eight waves: integer-valued operands at X = 2^6 with |sum| < 2^24 give exactly
     known integers whatever the order of the partial sums; one-hot rows pin every block of every slice;
     NaN scales in the first and the last slice."""
-    M, N, K = 48, 200, 1120                                # 35 blocks: slices of 5, the last wave has none
+    M, N = 48, 200                  # K = 1120: 35 blocks, slices of 5, the last wave has none; 1152: 9 chunks of 128
     rng = np.random.default_rng(15)
     qa = rng.integers(-20, 21, (M, K)).astype(np.int8)
     qb = rng.integers(-20, 21, (N, K)).astype(np.int8)
@@ -548,6 +552,44 @@ def test_int8_gemm_few_rows_exact(mx, oracle):
     sbb[9, K // 32 - 1] = 0xFF
     C = to_host(mx.mx_gemm(to_dev(eh), to_dev(sh), INT8, to_dev(eb), to_dev(sbb), INT8, K))
     assert np.isnan(C[7]).all() and np.isnan(C[:, 9]).all() and np.isnan(C).sum() == N + M - 1
+
+
+@pytest.mark.parametrize("shape", [(40, 48, 96), (40, 200, 544), (40, 200, 512), (200, 130, 4128), (200, 130, 4096)],
+                         ids=["direct", "few_rows", "few_rows_staged", "few_tiles", "few_tiles_staged"])
+def test_int8_gemm_scale_bytes_in_and_out_of_the_factor_range(mx, oracle, shape):
+    """The kernels scale a block sum by a ready-made Float32 factor when all its scale bytes are in
+    [70, 196] and by an exact exponent shift otherwise: blocks of both kinds alternate along K, with the
+    boundary bytes 69 / 70 / 196 / 197 among them."""
+    M, N, K = shape
+    rng = np.random.default_rng(31)
+    qa = rng.integers(-127, 128, (M, K)).astype(np.int8).view(np.uint8)
+    qb = rng.integers(-127, 128, (N, K)).astype(np.int8).view(np.uint8)
+    nb = K // 32
+    sa = np.empty((M, nb), np.uint8)
+    sb = np.empty((N, nb), np.uint8)
+    for b in range(nb):
+        kind = b % 5
+        if kind == 0:                                      # ordinary scales
+            sa[:, b], sb[:, b] = rng.integers(100, 141, M), rng.integers(100, 141, N)
+        elif kind == 1:                                    # small rows, large columns (69 and 197 included)
+            sa[:, b], sb[:, b] = rng.integers(0, 70, M), rng.integers(197, 255, N)
+            sa[0, b], sb[0, b] = 69, 197
+        elif kind == 2:                                    # the ends of the range, rows
+            sa[:, b], sb[:, b] = rng.choice([70, 196], M), 70
+        elif kind == 3:                                    # the ends of the range, columns
+            sa[:, b], sb[:, b] = 70, rng.choice([70, 196], N)
+        else:                                              # large rows, small columns
+            sa[:, b], sb[:, b] = rng.integers(197, 255, M), rng.integers(0, 70, N)
+    for dt in (torch.float32, torch.bfloat16):
+        C = mx.mx_gemm(to_dev(qa), to_dev(sa), INT8, to_dev(qb), to_dev(sb), INT8, K, dtype=dt)
+        check_product(mx, oracle, C, qa, sa, INT8, qb, sb, INT8, K, f"int8 scales {shape}")
+    # one block per product: the smallest and the largest factor of the range, exact results
+    for a_byte, b_byte in ((70, 70), (196, 70), (70, 196), (196, 196 - 20)):
+        sa1, sb1 = np.full((M, 1), a_byte, np.uint8), np.full((N, 1), b_byte, np.uint8)
+        qa1, qb1 = np.ascontiguousarray(qa[:, :32]), np.ascontiguousarray(qb[:, :32])
+        C = to_host(mx.mx_gemm(to_dev(qa1), to_dev(sa1), INT8, to_dev(qb1), to_dev(sb1), INT8, 32))
+        C_ref = oracle.gemm(qa1, sa1, INT8, qb1, sb1, INT8, 32)
+        assert np.array_equal(C.astype(np.float64), C_ref), (a_byte, b_byte)
 
 
 def test_int8_gemm_nan_scale_and_mixed_pair_refused(mx, oracle):
