@@ -196,13 +196,14 @@ def other_configs(n):
     # decoding shapes: few rows of A against the wide projection's E4M3 weights (one pass over 45 MB)
     N, K = 11008, 4096
     w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=112, std=0.02)).cuda()
-    Be, Bs = mx.mx_quantize(w, 0, mx.FP8_E4M3)
-    for M in (1, 16, 128):
-        a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=5))
-        Ae, As = mx.mx_quantize(a, 1, mx.FP8_E4M3)
-        C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-        ms = time_call(lambda: mx.mx_gemm(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, out=C), n)
-        out[f"decode_gemm_{M}x{N}x{K}_e4m3"] = {"avg_us": round(1e3 * ms, 2), "weights_GBps": round(N * K * (1 + 1 / 32) / ms / 1e6, 1)}
+    for fmt, name in ((mx.FP8_E4M3, "e4m3"), (mx.INT8, "int8")):
+        Be, Bs = mx.mx_quantize(w, 0, fmt)
+        for M in (1, 16, 128):
+            a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=5))
+            Ae, As = mx.mx_quantize(a, 1, fmt)
+            C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+            ms = time_call(lambda: mx.mx_gemm(Ae, As, fmt, Be, Bs, fmt, K, out=C), n)
+            out[f"decode_gemm_{M}x{N}x{K}_{name}"] = {"avg_us": round(1e3 * ms, 2), "weights_GBps": round(N * K * (1 + 1 / 32) / ms / 1e6, 1)}
     del w, Be, Bs
 
     # config 4: E3M2 activations [4096, 8192] x E2M1 weights (logical 8192 x 28672)
