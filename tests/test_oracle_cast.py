@@ -162,6 +162,27 @@ def test_idempotent(oracle, fmt, rnd):
     assert np.array_equal(inputs.bf16_bits_to_f32(yb).view(np.uint32), y.view(np.uint32))
 
 
+@pytest.mark.parametrize("fmt", range(6))
+@pytest.mark.parametrize("rnd", [RNE, AWAY])
+@pytest.mark.parametrize("axis", [1, 0])
+def test_power_of_two_equivariance(oracle, fmt, rnd, axis):
+    """Algorithm 1 sees a block only through V / X with X a power of two taken from the block maximum:
+    multiplying the tensor by 2^k moves every scale byte by k and leaves every element code alone (as long
+    as nothing leaves the normal Float32 range or the scale byte's range); a sign flip flips sign bits only."""
+    x = inputs.student_t_f32((64, 96), seed=40 + fmt)
+    x[np.abs(x) < 2.0 ** -20] = 0                      # keep 2^-40 x out of the subnormals
+    e, s = oracle.quantize(x, axis, fmt, rnd)
+    for k in (-40, -1, 3, 57):
+        ek, sk = oracle.quantize(x * np.float32(2.0 ** k), axis, fmt, rnd)
+        assert np.array_equal(ek, e), (fmt, k)
+        assert np.array_equal(sk.astype(np.int32), s.astype(np.int32) + k), (fmt, k)
+    en, sn = oracle.quantize(-x, axis, fmt, rnd)
+    assert np.array_equal(sn, s)
+    rows, cols = x.shape
+    y, yn = oracle.dequantize(e, s, fmt, rows, cols, axis), oracle.dequantize(en, sn, fmt, rows, cols, axis)
+    assert np.array_equal(yn, -y)                      # both roundings are symmetric about zero
+
+
 def test_idempotence_fails_by_design_on_subnormal_results(oracle):
     # E4M3 code 0x01 (2^-9) at scale byte 0 dequantizes to 2^-136, a Float32
     # subnormal, which the cast maps to zero (Section 3)
