@@ -78,6 +78,10 @@ __device__ __forceinline__ void i8_accumulate(float (&acc)[16], const v16i_t &p,
     wave_lds_sync8();   // the line is rewritten for the next block
 }
 
+// Clears the split route's flag word.  A kernel rather than a memset node, so that a caller who captures the
+// stream into a graph replays an ordinary launch.
+__global__ void int8_clear_flag_kernel(uint32_t *flag) { *flag = 0u; }
+
 // MXINT8 [R][K] -> FP6 E2M3 [R][4K]: one lane per source block.  B_SIDE picks the block order.
 template <bool B_SIDE>
 __global__ __launch_bounds__(256) void int8_split_kernel(const uint8_t *__restrict__ elems, const uint8_t *__restrict__ scales,
@@ -393,7 +397,8 @@ hipError_t launch_gemm_int8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, 
         hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), off_sb + nbb * 4, st);
         if (e == hipSuccess) {
             uint32_t *flag = reinterpret_cast<uint32_t *>(ws);
-            e = hipMemsetAsync(flag, 0, 4, st);
+            hipLaunchKernelGGL(int8_clear_flag_kernel, dim3(1), dim3(1), 0, st, flag);
+            e = hipGetLastError();
             if (e == hipSuccess) {
                 hipLaunchKernelGGL((int8_split_kernel<false>), dim3((unsigned)((nba + 255) / 256)), dim3(256), 0, st, Ae, As,
                                    (int64_t)nba, ws + off_ea, ws + off_sa, flag);
