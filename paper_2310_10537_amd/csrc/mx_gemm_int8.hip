@@ -260,14 +260,14 @@ __global__ __launch_bounds__(64 * I8_WAVES) void gemm_int8_lds_kernel(int64_t M,
     constexpr int RED_BYTES = (I8_WAVES - 1) * MT * 16 * 64 * 4;
     static_assert(I8_WAVES * W_BYTES >= RED_BYTES, "the partial sums reuse the staging tiles");
     __shared__ __attribute__((aligned(16))) uint8_t lds[I8_WAVES * W_BYTES];
-    __shared__ __attribute__((aligned(16))) uint32_t lines[I8_WAVES * 32];
+    __shared__ __attribute__((aligned(16))) uint32_t lines[I8_WAVES * MT * 4 * 32];   // per wave, tile and block: 32 row words
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 31, g = lane >> 5;
     const int64_t n0 = (int64_t)blockIdx.x * 32, m0 = (int64_t)blockIdx.y * (32 * MT);
     const int64_t nkb = K / BLOCK, chunks = K / 128;
     const int64_t per_wave = (chunks + I8_WAVES - 1) / I8_WAVES;
     const int64_t c_begin = wave * per_wave, c_end = c_begin + per_wave < chunks ? c_begin + per_wave : chunks;
     uint8_t *tA = lds + wave * W_BYTES, *tB = tA + MT * T_BYTES;
-    uint32_t *line = lines + wave * 32;
+    uint32_t *line = lines + wave * (MT * 4 * 32);
 
     const int lr = lane >> 3, lp = lane & 7;            // a wave-wide load: 8 rows x eight 16-byte pieces
     auto slot = [](int r, int c) { return r * 128 + ((c ^ ((r >> 1) & 7)) << 4); };
@@ -300,10 +300,30 @@ __global__ __launch_bounds__(64 * I8_WAVES) void gemm_int8_lds_kernel(int64_t M,
             for (int j = 0; j < 4; j++) *reinterpret_cast<uint4 *>(tA + x * T_BYTES + slot(8 * j + lr, lp)) = ra[x][j];
 #pragma unroll
         for (int j = 0; j < 4; j++) *reinterpret_cast<uint4 *>(tB + slot(8 * j + lr, lp)) = rb[j];
+        // The four scale bytes of row i (one per block of the chunk) go to the wave's lines next to the
+        // operands, under the same wait: as ready-made Float32 factors when every scale byte of the chunk,
+        // rows and columns, allows it (see i8_accumulate), as plain bytes otherwise.  The lower half-wave
+        // writes blocks 0 and 1, the upper one blocks 2 and 3 (both hold row i's dword).
         uint32_t sa_c[MT];
 #pragma unroll
         for (int x = 0; x < MT; x++) sa_c[x] = sa_d[x];
         const uint32_t sb_c = sb_d;
+        bool plain = true;
+#pragma unroll
+        for (int b = 0; b < 4; b++) {
+            plain = plain && i8_factor_ok((sb_c >> (8 * b)) & 0xFFu);
+#pragma unroll
+            for (int x = 0; x < MT; x++) plain = plain && i8_factor_ok((sa_c[x] >> (8 * b)) & 0xFFu);
+        }
+        const bool fast = __builtin_amdgcn_ballot_w64(!plain) == 0;   // uniform over the wave
+#pragma unroll
+        for (int x = 0; x < MT; x++)
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const int b = 2 * g + h;
+                const uint32_t sbyte = (sa_c[x] >> (8 * b)) & 0xFFu;
+                line[(x * 4 + b) * 32 + i] = fast ? i8_factor_bits(sbyte) : sbyte;
+            }
         wave_lds_sync8();
         if (c + 1 < c_end) request(c + 1);
 #pragma unroll
@@ -311,18 +331,36 @@ __global__ __launch_bounds__(64 * I8_WAVES) void gemm_int8_lds_kernel(int64_t M,
             // lane (i, g) of the instruction: bytes [16 g, 16 g + 16) of block b of row / column i
             const uint4 qb = *reinterpret_cast<const uint4 *>(tB + slot(i, 2 * b + g));
             const v4i_t bv = {(int)qb.x, (int)qb.y, (int)qb.z, (int)qb.w};
+            const uint32_t sbb = (sb_c >> (8 * b)) & 0xFFu;
+            const float fb = __uint_as_float(i8_factor_bits(sbb));
 #pragma unroll
             for (int x = 0; x < MT; x++) {
                 const uint4 qa = *reinterpret_cast<const uint4 *>(tA + x * T_BYTES + slot(i, 2 * b + g));
                 const v4i_t av = {(int)qa.x, (int)qa.y, (int)qa.z, (int)qa.w};
+                uint32_t w[16];
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const uint4 r = *reinterpret_cast<const uint4 *>(line + (x * 4 + b) * 32 + 8 * q + 4 * g);   // rows 8q + 4g .. + 3
+                    w[4 * q] = r.x; w[4 * q + 1] = r.y; w[4 * q + 2] = r.z; w[4 * q + 3] = r.w;
+                }
                 v16i_t z;
 #pragma unroll
                 for (int t = 0; t < 16; t++) z[t] = 0;
                 const v16i_t p = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv, z, 0, 0, 0);
-                i8_accumulate(acc[x], p, (sa_c[x] >> (8 * b)) & 0xFFu, (sb_c >> (8 * b)) & 0xFFu, line, i, g);
+                if (fast) {
+#pragma unroll
+                    for (int t = 0; t < 16; t++) acc[x][t] = fmaf((float)p[t], __uint_as_float(w[t]) * fb, acc[x][t]);
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 16; t++) {
+                        float term = ldexpf((float)p[t], (int)w[t] + (int)sbb - 254 - 12);
+                        if (w[t] == SCALE_NAN || sbb == SCALE_NAN) term = __uint_as_float(0x7FC00000u);
+                        acc[x][t] += term;
+                    }
+                }
             }
         }
-        wave_lds_sync8();   // the tiles are read before the next chunk is parked in them
+        wave_lds_sync8();   // tiles and lines are read before the next chunk is parked in them
     }
 
     // ---- the eight partial sums, always w0 + w1 + ... + w7; the staging tiles are done with
