@@ -250,7 +250,9 @@ __global__ __launch_bounds__(64 * I8_WAVES) void gemm_int8_shared_k_kernel(int64
 // operand reads free of bank conflicts -- and multiplies its four blocks from there while the next 128
 // bytes are in flight.  MT tiles of 32 rows share the B tile of the work-group's 32 columns.  Rows beyond
 // M and columns beyond N read the last valid one instead: their results are never stored.
-template <int MT, int CDT>
+// QN: groups of 8 rows of a tile that are scaled and stored (result registers 4q .. 4q + 3 are rows
+// 8q + 4g .. + 3); a decoding step of at most 8 or 16 rows skips the rest.
+template <int MT, int QN, int CDT>
 __global__ __launch_bounds__(64 * I8_WAVES) void gemm_int8_lds_kernel(int64_t M, int64_t N, int64_t K,
                                                                        const uint8_t *__restrict__ Ae, const uint8_t *__restrict__ As,
                                                                        const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
@@ -337,9 +339,9 @@ __global__ __launch_bounds__(64 * I8_WAVES) void gemm_int8_lds_kernel(int64_t M,
             for (int x = 0; x < MT; x++) {
                 const uint4 qa = *reinterpret_cast<const uint4 *>(tA + x * T_BYTES + slot(i, 2 * b + g));
                 const v4i_t av = {(int)qa.x, (int)qa.y, (int)qa.z, (int)qa.w};
-                uint32_t w[16];
+                uint32_t w[4 * QN];
 #pragma unroll
-                for (int q = 0; q < 4; q++) {
+                for (int q = 0; q < QN; q++) {
                     const uint4 r = *reinterpret_cast<const uint4 *>(line + (x * 4 + b) * 32 + 8 * q + 4 * g);   // rows 8q + 4g .. + 3
                     w[4 * q] = r.x; w[4 * q + 1] = r.y; w[4 * q + 2] = r.z; w[4 * q + 3] = r.w;
                 }
@@ -349,10 +351,10 @@ __global__ __launch_bounds__(64 * I8_WAVES) void gemm_int8_lds_kernel(int64_t M,
                 const v16i_t p = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv, z, 0, 0, 0);
                 if (fast) {
 #pragma unroll
-                    for (int t = 0; t < 16; t++) acc[x][t] = fmaf((float)p[t], __uint_as_float(w[t]) * fb, acc[x][t]);
+                    for (int t = 0; t < 4 * QN; t++) acc[x][t] = fmaf((float)p[t], __uint_as_float(w[t]) * fb, acc[x][t]);
                 } else {
 #pragma unroll
-                    for (int t = 0; t < 16; t++) {
+                    for (int t = 0; t < 4 * QN; t++) {
                         float term = ldexpf((float)p[t], (int)w[t] + (int)sbb - 254 - 12);
                         if (w[t] == SCALE_NAN || sbb == SCALE_NAN) term = __uint_as_float(0x7FC00000u);
                         acc[x][t] += term;
@@ -370,7 +372,7 @@ __global__ __launch_bounds__(64 * I8_WAVES) void gemm_int8_lds_kernel(int64_t M,
 #pragma unroll
         for (int x = 0; x < MT; x++)
 #pragma unroll
-            for (int t = 0; t < 16; t++) red[(((wave - 1) * MT + x) * 16 + t) * 64 + lane] = acc[x][t];
+            for (int t = 0; t < 4 * QN; t++) red[(((wave - 1) * MT + x) * 16 + t) * 64 + lane] = acc[x][t];
     }
     __syncthreads();
     if (wave != 0) return;
@@ -378,7 +380,7 @@ __global__ __launch_bounds__(64 * I8_WAVES) void gemm_int8_lds_kernel(int64_t M,
 #pragma unroll
     for (int x = 0; x < MT; x++)
 #pragma unroll
-        for (int t = 0; t < 16; t++) {
+        for (int t = 0; t < 4 * QN; t++) {
             float v = acc[x][t];
 #pragma unroll
             for (int w = 0; w < I8_WAVES - 1; w++) v += red[((w * MT + x) * 16 + t) * 64 + lane];
@@ -390,15 +392,15 @@ __global__ __launch_bounds__(64 * I8_WAVES) void gemm_int8_lds_kernel(int64_t M,
         }
 }
 
-template <int MT>
+template <int MT, int QN>
 static hipError_t launch_int8_lds(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint8_t *Be,
                                   const uint8_t *Bs, void *C, int c_dt, int64_t ldc, hipStream_t st)
 {
     const dim3 grid((unsigned)((N + 31) / 32), (unsigned)((M + 32 * MT - 1) / (32 * MT)));
     if (c_dt == DT_F32)
-        hipLaunchKernelGGL((gemm_int8_lds_kernel<MT, DT_F32>), grid, dim3(64 * I8_WAVES), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc);
+        hipLaunchKernelGGL((gemm_int8_lds_kernel<MT, QN, DT_F32>), grid, dim3(64 * I8_WAVES), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc);
     else
-        hipLaunchKernelGGL((gemm_int8_lds_kernel<MT, DT_BF16>), grid, dim3(64 * I8_WAVES), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc);
+        hipLaunchKernelGGL((gemm_int8_lds_kernel<MT, QN, DT_BF16>), grid, dim3(64 * I8_WAVES), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc);
     return hipGetLastError();
 }
 
@@ -454,8 +456,10 @@ hipError_t launch_gemm_int8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, 
         (void)hipGetLastError();   // no workspace: the direct kernel needs none
     }
     if (M > 0 && N > 0 && K % 128 == 0 && (M <= 128 ? K >= 8 * BLOCK : K >= 1024) && (M + 63) / 64 <= 65535)
-        return M <= 32 ? launch_int8_lds<1>(M, N, K, Ae, As, Be, Bs, C, c_dt, ldc, st)
-                       : launch_int8_lds<2>(M, N, K, Ae, As, Be, Bs, C, c_dt, ldc, st);
+        return M <= 8    ? launch_int8_lds<1, 1>(M, N, K, Ae, As, Be, Bs, C, c_dt, ldc, st)
+               : M <= 16 ? launch_int8_lds<1, 2>(M, N, K, Ae, As, Be, Bs, C, c_dt, ldc, st)
+               : M <= 32 ? launch_int8_lds<1, 4>(M, N, K, Ae, As, Be, Bs, C, c_dt, ldc, st)
+                         : launch_int8_lds<2, 4>(M, N, K, Ae, As, Be, Bs, C, c_dt, ldc, st);
     // K not in whole 128-byte pieces: few rows, or so few tiles that the direct kernel would put at most one
     // wave on a SIMD while K is long (256 x 4096 x 4096 81 -> 66 us; with 2048 tiles of 32 x 32 the direct
     // kernel is ahead again, 114 vs 124 us)

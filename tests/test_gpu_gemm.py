@@ -488,7 +488,7 @@ INT8 = 5
                                    # few rows and at least 8 blocks: eight waves share the blocks of a tile
                                    (1, 200, 512), (33, 100, 1056), (128, 72, 288), (100, 1000, 4096), (200, 130, 4128),
                                    # K a multiple of 128: the same with operands staged through LDS
-                                   (33, 100, 1024), (128, 72, 384), (64, 40, 256), (200, 130, 4096), (7, 33, 2176), (300, 520, 1024),
+                                   (33, 100, 1024), (128, 72, 384), (64, 40, 256), (200, 130, 4096), (7, 33, 2176), (8, 64, 384), (9, 70, 640), (16, 40, 1152), (17, 40, 1152), (300, 520, 1024),
                                    (2048, 2048, 1024)])
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 def test_int8_gemm_shapes(mx, oracle, shape, dt):
