@@ -321,9 +321,10 @@ __device__ __forceinline__ void convert_f32_fast(const uint32_t (&v)[32], uint32
             out[j] = q;
         }
     } else if constexpr (FMT == INT8) {
-        // q = round(V / X * 64) clamped to +-127, two's complement.  V * 2^(133 - s) is exact; ties
-        // away: adding half and truncating is right although the sum may round in its last place
-        // (integers are exact, so the rounding cannot cross one); ties to even: the magic-number add
+        // q = round(V / X * 64) clamped to +-127, two's complement.  V * 2^(133 - s) is exact.  Ties
+        // away: the integer part and the fraction are split first (both exact), and the fraction
+        // alone decides -- adding a half to the whole value would round 0.5 - 2^-25 up to 1.
+        // Ties to even: the magic-number add.
         const float c = __uint_as_float((260u - s) << 23);
 #pragma unroll
         for (int j = 0; j < 8; j++) {
@@ -331,7 +332,10 @@ __device__ __forceinline__ void convert_f32_fast(const uint32_t (&v)[32], uint32
 #pragma unroll
             for (int e = 0; e < 4; e++) {
                 float y = __uint_as_float(v[4 * j + e]) * c;
-                if (RND == ROUND_HALF_AWAY) y = truncf(y + copysignf(0.5f, y));
+                if (RND == ROUND_HALF_AWAY) {
+                    const float t = truncf(y);
+                    y = t + copysignf(fabsf(y - t) >= 0.5f ? 1.0f : 0.0f, y);
+                }
                 y = __builtin_amdgcn_fmed3f(y, -127.0f, 127.0f);
                 z[e] = __float_as_uint(y + 12582912.0f);
             }

@@ -125,6 +125,13 @@ def test_cast_fp32_midpoints(mx, oracle, fmt):
     x = np.ascontiguousarray(x.reshape(-1, 256))
     for rnd in (RNE, AWAY):
         check_cast(mx, oracle, x, 1, fmt, rnd)
+    # the same blocks running down the columns of a tensor made of whole 128 x 64 tiles: the
+    # Float32 column kernel, whose block quantizer is the one the GEMM epilogue uses as well
+    x = np.concatenate([x, np.zeros(((-x.shape[0]) % 64, 256), dtype=np.float32)])
+    xt = np.ascontiguousarray(x.T)
+    assert xt.shape[0] % 128 == 0 and xt.shape[1] % 64 == 0
+    for rnd in (RNE, AWAY):
+        check_cast(mx, oracle, xt, 0, fmt, rnd, "axis 0 tiles")
 
 
 def test_cast_random_bits_fp32(mx, oracle):
@@ -441,10 +448,16 @@ def test_partial_block_tensor_feeds_the_gemm(mx, oracle):
     ga = mx.mx_quantize(dev_view(a), 1, 0)
     gb = mx.mx_quantize(dev_view(b), 1, 2)
     C = to_host(mx.mx_gemm(ga[0], ga[1], 0, gb[0], gb[1], 2, 128))
-    Ad = oracle.dequantize(*oracle.quantize(a, 1, 0), 0, M, K, 1).astype(np.float64)
-    Bd = oracle.dequantize(*oracle.quantize(b, 1, 2), 2, N, K, 1).astype(np.float64)
-    ref = Ad @ Bd.T
-    assert np.all(np.abs(C - ref) <= 1e-5 * (np.abs(Ad) @ np.abs(Bd).T) + 14 * 2.0 ** -14 * np.abs(Ad).max() * np.abs(Bd).max() * 16)
+    ea, sa = oracle.quantize(a, 1, 0)
+    eb, sb = oracle.quantize(b, 1, 2)
+    assert np.array_equal(to_host(ga[0]), ea) and np.array_equal(to_host(gb[0]), eb)
+    # the reference product over the 100 real positions = the product over the 128 stored ones
+    Ad = oracle.dequantize(ea, sa, 0, M, K, 1).astype(np.float64)
+    Bd = oracle.dequantize(eb, sb, 2, N, K, 1).astype(np.float64)
+    ref128, abs128 = oracle.gemm(ea, sa, 0, eb, sb, 2, 128, want_abs=True)
+    assert np.allclose(ref128, Ad @ Bd.T, rtol=1e-12, atol=0)
+    from test_gpu_gemm import check_gemm, hw_term_for
+    check_gemm(C, ref128, abs128, "partial block operand", hw_term_for(oracle, ea, sa, 0, eb, sb, 2, 128))
 
 
 @pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
