@@ -74,7 +74,7 @@ def check_gemm(C_gpu, C_ref, C_abs, tag="", hw_term=None, ceiling=None):
 
 
 def hw_term_for(oracle, ea, sa, fa, eb, sb, fb, K):
-    if fa in EXACT_IN_HW and fb in EXACT_IN_HW:
+    if (fa in EXACT_IN_HW and fb in EXACT_IN_HW) or fa == 5:      # (MXINT8 block sums are exact integers)
         return None
     # a NaN scale byte makes the entry NaN; its bound is never looked at
     return hwm.run_cut_bound_full(ea, np.where(sa == 0xFF, 127, sa), fa, eb, np.where(sb == 0xFF, 127, sb), fb, K)
@@ -334,7 +334,7 @@ def sampled_check(mx, oracle, C, A, fa, B, fb, K, seed, n=2048):
     C_ref, C_abs = oracle.gemm_entries(A[0], A[1], fa, B[0], B[1], fb, K, mi, ni)
     got = C[torch.from_numpy(mi).cuda(), torch.from_numpy(ni).cuda()].float().cpu().numpy().astype(np.float64)
     hw = None
-    if not (fa in EXACT_IN_HW and fb in EXACT_IN_HW):
+    if not ((fa in EXACT_IN_HW and fb in EXACT_IN_HW) or fa == 5):
         hw = hwm.run_cut_bound(A[0], A[1], fa, B[0], B[1], fb, K, mi, ni)
     return got, C_ref, C_abs, hw
 
@@ -781,6 +781,35 @@ def test_gemm_q_epilogue_cast(mx, oracle, fc, rnd, fa, fb):
     _gemm_q_case(mx, oracle, 1024, 2048, 640, fa, fb, fc, rnd, special=False)
     s_ref = _gemm_q_case(mx, oracle, 2048, 1024, 512, fa, fb, fc, rnd, special=True)
     assert (s_ref < 18).any()                        # the exact path inside the epilogue was taken
+
+
+def test_gemm_q_epilogue_int8_ties_away_one_ulp_below_a_tie(mx, oracle):
+    """Accumulators that sit one Float32 ulp below (and above) the INT8 grid's first rounding
+    boundary, X * 2^-7: built from two products 24 binades apart in different K steps, so that
+    the accumulator is exactly X * 2^-7 * (1 -+ 2^-24 / 2^-23).  One ulp below a tie rounds
+    toward zero also in the ties-away mode; adding a half before truncating would not."""
+    M, N, K = 2048, 1024, 512
+    A = np.zeros((M, K), np.int64); B = np.zeros((N, K), np.int64)
+    A[:, 0] = 0x38; A[:, 64] = 0x38                      # 1.0 at K = 0 and K = 64 (E4M3)
+    sa = np.full((M, K // 32), 127, np.uint8); sb = np.full((N, K // 32), 127, np.uint8)
+    n = np.arange(N)
+    B[:, 0] = 0x38                                       # column n: 1.0 * 2^(sb - 127) ...
+    B[n % 32 == 1, 64] = 0xB8; B[n % 32 == 2, 64] = 0x38     # ... minus / plus a term 24 binades below
+    B[n % 32 == 3, 64] = 0x38; B[n % 32 == 3, 0] = 0xB8      # the mirrored sign
+    sb[n % 32 != 0, 0] = 127 - 7                         # columns 1.. of each block: 2^-7 of the block maximum 1.0
+    sb[:, 2] = 127 - 7 - 24                              # one ulp of the binade below X * 2^-7 ...
+    sb[n % 32 == 2, 2] = 127 - 7 - 23                    # ... and one ulp of the binade above it
+    def pack8(c): return c.astype(np.uint8)
+    dev = [to_dev(x) for x in (pack8(A), sa, pack8(B), sb)]
+    C32 = to_host(mx.mx_gemm(dev[0], dev[1], 0, dev[2], dev[3], 0, K, dtype=torch.float32))
+    assert C32[0, 0] == 1.0 and C32.view(np.uint32)[0, 1] == 0x3BFFFFFF and C32.view(np.uint32)[0, 2] == 0x3C000001
+    assert C32.view(np.uint32)[0, 3] == 0xBBFFFFFF
+    for rnd in (RNE, AWAY):
+        e_ref, s_ref = oracle.quantize(C32, 1, 5, rnd)
+        e, s = mx.mx_gemm_q(dev[0], dev[1], 0, dev[2], dev[3], 0, K, 5, rnd)
+        assert np.array_equal(to_host(s), s_ref) and np.array_equal(to_host(e), e_ref), rnd
+        # just below the tie, just above it, mirrored, and the tie itself (column 4: to even = 0, away = 1)
+        assert e_ref[0, 1] == 0 and e_ref[0, 2] == 1 and e_ref[0, 3] == 0 and e_ref[0, 4] == (1 if rnd == AWAY else 0)
 
 
 @pytest.mark.parametrize("case", [(100, 72, 96, 0, 0, 0, RNE), (256, 256, 512, 0, 0, 5, RNE), (256, 256, 512, 2, 4, 4, 2),
