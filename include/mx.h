@@ -78,7 +78,8 @@ typedef enum {
                                where whole blocks are required (GEMM K, dual cast) */
     MX_ERR_ALIGN = 4,       /* pointer or leading dimension not 16-byte aligned  */
     MX_ERR_UNSUPPORTED = 5, /* MX_INT8 paired with another format in a GEMM      */
-    MX_ERR_LAUNCH = 6       /* the HIP runtime refused the launch                */
+    MX_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                */
+    MX_ERR_TOO_LARGE = 7    /* mx_gemm_qa_noalloc: the static scratch is too small */
 } mx_status_t;
 
 /* Size in bytes of the elems array for a [rows, cols] source cast along axis:
@@ -230,7 +231,34 @@ int mx_gemm_qa(int64_t M, int64_t N, int64_t K,
                const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB,
                void *C, mx_dtype_t c_dt, int64_t ldc, void *hip_stream);
 
-/* Static, human-readable text for a status code. */
+/*
+ * mx_gemm_qa for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and the same result, bit for bit, as mx_gemm_qa; the difference is where the MX
+ * form of A lives between the cast and the product: in a static device array of
+ * MX_NOALLOC_SCRATCH_BYTES bytes inside the library (one copy per GPU, held until
+ * the process ends) instead of a workspace from the memory pool.  The call makes
+ * no hipMalloc / hipFree / pool request of any kind; it launches the row cast of A
+ * into that array and then the kernel mx_gemm would pick for the shape.
+ *   - M * K * bits(fmtA) / 8 (rounded up to 256) + M * K / 32 bytes must fit in
+ *     MX_NOALLOC_SCRATCH_BYTES (36 MiB: an 8192 x 4096 8-bit operand fits);
+ *     otherwise MX_ERR_TOO_LARGE and nothing is launched.
+ *   - MX_INT8 operands are MX_ERR_UNSUPPORTED here (their kernels use pool
+ *     workspaces of their own); rnd may be any mode mx_gemm_qa takes.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap in time on
+ *     one GPU (different streams, or different host threads) race on it.  Calls on
+ *     one stream are ordered and safe.  Nothing in the array has to be cleared:
+ *     each call overwrites the part it reads.
+ *   - The array's address is looked up on the first call on a device
+ *     (hipGetSymbolAddress: no allocation); make that first call outside a graph
+ *     capture.
+ */
+#define MX_NOALLOC_SCRATCH_BYTES (36u << 20)
+int mx_gemm_qa_noalloc(int64_t M, int64_t N, int64_t K,
+                       const void *A_bf16, int64_t lda, mx_format_t fmtA, mx_round_t rnd,
+                       const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB,
+                       void *C, mx_dtype_t c_dt, int64_t ldc, void *hip_stream);
+
 /*
  * The product of mx_gemm with C delivered as an MX tensor: Algorithm 1 (Section
  * 3) applied to the Float32 result along N, which is how the output of one
@@ -251,6 +279,7 @@ int mx_gemm_q(int64_t M, int64_t N, int64_t K,
               mx_format_t fmtC, mx_round_t rnd,
               void *C_elems, uint8_t *C_scales, void *hip_stream);
 
+/* Static, human-readable text for a status code. */
 const char *mx_strerror(int status);
 
 #ifdef __cplusplus

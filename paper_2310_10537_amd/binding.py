@@ -15,6 +15,8 @@ FORMAT_BITS = (8, 8, 6, 6, 4, 8)
 ROUND_RNE, ROUND_HALF_AWAY, ROUND_TOWARD_ZERO, ROUND_STOCHASTIC = 0, 1, 2, 3
 DT_F32, DT_BF16 = 0, 1
 MX_OK = 0
+MX_ERR_TOO_LARGE = 7
+NOALLOC_SCRATCH_BYTES = 36 << 20
 BLOCK = 32
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmx.so")
@@ -48,6 +50,7 @@ def lib() -> ctypes.CDLL:
         L.mx_gemm.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, ci, i64, vp]
         L.mx_gemm_qa.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
         L.mx_gemm_q.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, ci, ci, vp, vp, vp]
+        L.mx_gemm_qa_noalloc.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
         L.mx_strerror.argtypes = [ci]
         L.mx_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -203,4 +206,23 @@ def mx_gemm_qa(A_bf16, fmtA, rnd, B_elems, B_scales, fmtB, dtype=torch.float32, 
     _check(lib().mx_gemm_qa(M, N, K, A_bf16.data_ptr(), lda, fmtA, rnd,
                             B_elems.data_ptr(), B_scales.data_ptr(), fmtB,
                             out.data_ptr(), _dt(out), ldc, _stream(stream)))
+    return out
+
+
+def mx_gemm_qa_noalloc(A_bf16, fmtA, rnd, B_elems, B_scales, fmtB, out, stream=None):
+    """mx_gemm_qa without any device allocation by the library: the MX form of A lives in the
+    library's static scratch array (NOALLOC_SCRATCH_BYTES).  `out` is required: this wrapper
+    allocates nothing either."""
+    _dev(A_bf16, "A_bf16")
+    _dev(B_elems, "B_elems")
+    _dev(B_scales, "B_scales")
+    _dev(out, "out")
+    assert A_bf16.dtype == torch.bfloat16 and A_bf16.dim() == 2
+    M, K = A_bf16.shape
+    N = B_scales.shape[0]
+    lda = A_bf16.stride(0) if M > 1 else K
+    ldc = out.stride(0) if M > 1 else N
+    _check(lib().mx_gemm_qa_noalloc(M, N, K, A_bf16.data_ptr(), lda, fmtA, rnd,
+                                    B_elems.data_ptr(), B_scales.data_ptr(), fmtB,
+                                    out.data_ptr(), _dt(out), ldc, _stream(stream)))
     return out

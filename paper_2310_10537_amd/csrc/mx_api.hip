@@ -1,6 +1,10 @@
-// C ABI of the MX library (see include/mx.h): argument validation and
-// dispatch.  No state, no allocation; every call enqueues on the caller's stream.
+// C ABI of the MX library (see include/mx.h): argument validation and dispatch.  Every call
+// enqueues on the caller's stream.  The library keeps no tensor pointers; the routes that need
+// a workspace are named in include/mx.h, and mx_gemm_qa_noalloc below keeps its workspace in a
+// static device array instead of taking it from the memory pool.
 #include "../../include/mx.h"
+
+#include <atomic>
 
 #include "mx_device.hpp"
 #include "mx_launch.hpp"
@@ -153,6 +157,63 @@ int mx_gemm_q(int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_
     return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
 }
 
+// ---------------------------------------------------------------------------------------------
+// mx_gemm_qa for callers that cannot allocate.  The MX form of A goes into a static device array
+// instead of a pool workspace.  Host code never uses the array's name as an address: the address
+// is looked up once per device with hipGetSymbolAddress and kept per device.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[MX_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::atomic<unsigned char *> scratch_ptr[MAX_DEVICES];
+
+// device address of this device's copy of the array (nullptr on failure); the current device
+// must be `dev`.  Looking the symbol up allocates nothing.
+unsigned char *scratch_of(int dev)
+{
+    if (dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    unsigned char *p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void *sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    scratch_ptr[dev].store(static_cast<unsigned char *>(sym), std::memory_order_release);
+    return static_cast<unsigned char *>(sym);
+}
+}  // namespace
+
+int mx_gemm_qa_noalloc(int64_t M, int64_t N, int64_t K, const void *A_bf16, int64_t lda, mx_format_t fmtA, mx_round_t rnd,
+                       const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB, void *C, mx_dtype_t c_dt, int64_t ldc,
+                       void *hip_stream)
+{
+    if (!fmt_ok(fmtA) || !fmt_ok(fmtB) || !dt_ok(c_dt) || !rnd_ok(rnd)) return MX_ERR_ENUM;
+    if (M < 0 || N < 0 || K < 0 || K % mx::BLOCK || ldc < N || lda < K) return MX_ERR_SHAPE;
+    if (fmtA == MX_INT8 || fmtB == MX_INT8) return MX_ERR_UNSUPPORTED;   // the MXINT8 routes take pool workspaces
+    if (M == 0 || N == 0) return MX_OK;
+    if (!C || (K > 0 && (!A_bf16 || !B_elems || !B_scales))) return MX_ERR_NULL;
+    if (!aligned16(B_elems) || !aligned16(B_scales) || !aligned16(C) || !aligned16(A_bf16) || (lda * 2) % 16) return MX_ERR_ALIGN;
+    // A as an MX tensor: element bytes (rounded up to 256), then scale bytes
+    const size_t eb = ((size_t)M * (size_t)K * (size_t)mx::fmt_bits(fmtA) / 8 + 255) & ~(size_t)255;
+    const size_t sbytes = (size_t)M * (size_t)(K / mx::BLOCK);
+    if (eb + sbytes > (size_t)MX_NOALLOC_SCRATCH_BYTES) return MX_ERR_TOO_LARGE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (K == 0)
+        return mx::launch_gemm(M, N, 0, nullptr, nullptr, nullptr, 0, MX_ROUND_RNE, fmtA, nullptr, nullptr, fmtB, C, c_dt, ldc, st) ==
+                       hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return MX_ERR_LAUNCH;
+    unsigned char *ws = scratch_of(dev);
+    if (!ws) return MX_ERR_LAUNCH;
+    hipError_t e = mx::launch_cast(A_bf16, MX_DT_BF16, M, K, lda, 1, fmtA, rnd, ws, ws + eb, st);
+    if (e == hipSuccess)
+        e = mx::launch_gemm(M, N, K, ws, ws + eb, nullptr, 0, MX_ROUND_RNE, fmtA, static_cast<const uint8_t *>(B_elems), B_scales,
+                            fmtB, C, c_dt, ldc, st);
+    return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+}
+
 const char *mx_strerror(int status)
 {
     switch (status) {
@@ -163,6 +224,7 @@ const char *mx_strerror(int status)
         case MX_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
         case MX_ERR_UNSUPPORTED: return "the GEMM pairs MX_INT8 only with MX_INT8";
         case MX_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+        case MX_ERR_TOO_LARGE: return "the problem needs more scratch memory than the entry point's static buffer holds";
         default: return "unknown status";
     }
 }

@@ -24,7 +24,7 @@ def test_exports_match_header(L):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(mx_[a-z_]+)\s*\(", text))
     assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_sr", "mx_quantize_dual", "mx_dequantize", "mx_gemm",
-                     "mx_gemm_qa", "mx_gemm_q", "mx_strerror"}
+                     "mx_gemm_qa", "mx_gemm_q", "mx_gemm_qa_noalloc", "mx_strerror"}
     for n in names:
         assert hasattr(L, n), n
 
@@ -109,3 +109,19 @@ def test_binding_refuses_host_tensors():
     from paper_2310_10537_amd import binding
     with pytest.raises(ValueError):
         binding.mx_quantize(torch.zeros(32, 32), 1, 0)
+
+
+def test_noalloc_entry_point_validation(L):
+    """mx_gemm_qa_noalloc refuses what does not fit its static scratch array, and MXINT8, before any HIP call."""
+    p = 0x1000
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    f = L.mx_gemm_qa_noalloc
+    f.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
+    assert f(8192, 256, 4096, p, 4096, 0, 0, p, p, 0, None, 0, 256, None) == 1          # fits; C is NULL
+    assert f(8192 + 1024, 256, 4096, p, 4096, 0, 0, p, p, 0, p, 0, 256, None) == 7       # 37.1 MiB > 36 MiB
+    assert f(16384, 256, 4096, p, 4096, 4, 0, p, p, 0, None, 0, 256, None) == 1          # 4-bit: 34 MiB fits
+    assert f(256, 256, 512, p, 512, 5, 0, p, p, 5, p, 0, 256, None) == 5                 # MXINT8
+    assert f(256, 256, 500, p, 512, 0, 0, p, p, 0, p, 0, 256, None) == 3
+    assert f(256, 256, 512, p, 512, 0, 3, p, p, 0, p, 0, 256, None) == 2                 # stochastic rounding
+    assert f(0, 256, 512, None, 512, 0, 0, None, None, 0, None, 0, 256, None) == 0
+    assert b"scratch" in L.mx_strerror(7)
