@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the MX hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--quick] [--all-configs] [--no-cpu-baseline]
 
 One step = one pass of the whole hot path over seeded synthetic tensors that are
 already resident in HBM:
@@ -12,17 +12,29 @@ already resident in HBM:
   * the transformer projection GEMM 8192 x 4096 x 4096, MXFP8 E4M3 x E4M3, bf16
     output, once from pre-quantized operands (mx_gemm) and once with the bf16
     activations cast on load (mx_gemm_qa).
-Inputs rotate over three copies so that no call finds its source in the 256 MB
-Infinity Cache.  K steps are timed as a whole (ms_per_step).  Each call's own
-average duration is then measured the same way: K launches of that call back to
-back on the stream it runs on, between two events, with the same buffer rotation.
-The headline value is the cast throughput (algorithmic bytes of the 12 casts
-divided by their summed average durations); GEMM TFLOP/s are reported beside it.
+Sources and destinations rotate over three / two copies so that no call finds its
+input in the 256 MB Infinity Cache.  K steps are timed as a whole (ms_per_step).
+Each call's own average duration is then measured the same way: K launches of
+that call back to back on the stream it runs on, between two events, with the same
+buffer rotation.  The headline value is the cast throughput (algorithmic bytes of
+the 12 casts divided by their summed average durations); GEMM TFLOP/s are reported
+beside it.
 
-With --all-configs the other full-size workloads are timed as well (per call, same protocol)
-and reported under "other_configs": the 4096 x 11008 projection of config 3, the mixed-format
-inference GEMM of config 4 with its two casts, and the MXFP6 training triple of config 5 (six
-casts, three GEMMs).  They are not part of the step or of the headline value.
+Also in the default run, per call and with the same protocol:
+  "ceilings"       what the cast's access pattern reaches on this machine with no arithmetic
+                   (mx_stream_pattern: pure read, pure write, copy, 2 and 4 bytes read per byte
+                   written), and each cast as a fraction of the ceiling of its read : write ratio;
+  "other_configs"  the other full-size workloads: the 4096 x 11008 projection of config 3, the
+                   mixed-format inference GEMM of config 4 with its two casts, the MXFP6 training
+                   triple of config 5 (six casts, three GEMMs, the dual-axis casts), and config 1
+                   in microseconds -- every GEMM with its fraction of the matrix peak, every cast
+                   with its fraction of the HBM peak;
+  "gemm_zero_operands"  the headline GEMM launch on all-zero operands: what the same kernel
+                   does when operand switching activity does not hold the clock down;
+  "gemm_max_rel_err"    (with the CPU baseline leg) max |dC| / sum |a||b| of sampled entries
+                   against the double-precision reference, per GEMM workload.
+--quick leaves out "other_configs"; --all-configs adds decoding shapes, MXINT8, the added
+rounding modes and the GEMM-epilogue cast.
 
 Prints ONE JSON line.
 """
@@ -46,25 +58,40 @@ MFMA_PEAK_TFLOPS = {8: 5000.0, 6: 10100.0, 4: 10100.0}
 ROWS = COLS = 8192
 GM, GK, GN = 8192, 4096, 4096
 NCOPY = 3
-# HBM bytes per launch (read + write) from hardware counters of a profiled run of this file,
-# scaled by what the same counters read for the 128 MiB copy above; the profiles directory holds
-# the summaries these come from (bench_hot_path_hbm_traffic.txt).  Labels without a measurement
-# report null (the E4M3 row cast shares its kernel with launches of another size in that run).
-MEASURED_TRAFFIC_BYTES = {
-    "cast_fp4_e2m1_axis0": 170152434,
-    "cast_fp4_e2m1_axis1": 169953913,
-    "cast_fp6_e2m3_axis0": 188225329,
-    "cast_fp6_e2m3_axis1": 186680914,
-    "cast_fp6_e3m2_axis0": 187918375,
-    "cast_fp6_e3m2_axis1": 186674759,
-    "cast_fp8_e4m3_axis0": 203642934,
-    "cast_fp8_e5m2_axis0": 203656862,
-    "cast_fp8_e5m2_axis1": 203513963,
-    "cast_int8_axis0": 203587215,
-    "cast_int8_axis1": 203513976,
-    "dequantize_fp8_e4m3_bf16": 205567193,
-    "gemm_fp8_e4m3": 275307200,
-}
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "bench_hot_path_hbm_traffic.txt")
+FORMAT_INDEX = {"fp8_e4m3": 0, "fp8_e5m2": 1, "fp6_e3m2": 2, "fp6_e2m3": 3, "fp4_e2m1": 4, "int8": 5}
+
+
+def measured_traffic():
+    """HBM bytes per launch (read + write) of this file's kernels, from the committed hardware
+    counter summary (FETCH_SIZE / WRITE_SIZE scaled by a copy of known size; the file names its
+    commands).  label -> bytes; empty when the summary is missing or a kernel is not in it."""
+    out = {}
+    try:
+        lines = open(TRAFFIC_SUMMARY).read().splitlines()
+    except OSError:
+        return out
+    for ln in lines:
+        f = ln.split()
+        if len(f) < 8 or not f[0].isdigit():
+            continue
+        try:
+            rd, wr = float(f[3]), float(f[4])
+        except ValueError:
+            continue
+        kern = " ".join(f[7:])
+        label = None
+        for kname, axis in (("cast_row_bf16_kernel<", 1), ("cast_col_bf16_kernel<", 0)):
+            if kern.startswith(kname):
+                fmt = int(kern[len(kname):].split(",")[0])
+                label = f"cast_{mx.FORMAT_NAMES[fmt]}_axis{axis}"
+        if kern.startswith("dequant_kernel"):
+            label = "dequantize_fp8_e4m3_bf16"
+        if kern.startswith("gemm_tile_kernel<0, 0, 1, false"):
+            label = "gemm_fp8_e4m3"
+        if label and label not in out and label != "cast_fp8_e4m3_axis1":   # (that kernel also serves the 8192 x 4096 cast of mx_gemm_qa)
+            out[label] = int((rd + wr) * 2 ** 20)
+    return out
 
 
 def cast_bytes(fmt, n_elem):
@@ -103,10 +130,16 @@ class Timed:
         return out
 
 
-def cpu_baseline(x_bits):
-    """The CPU reference as it stands, timed on the host cores on one pass of
-    the cast workload: all 12 casts (6 formats x 2 axes) of the whole tensor,
-    a few seconds on 16 threads."""
+def sample_entries(M, N, n, seed):
+    rng = np.random.default_rng(seed)
+    return rng.integers(0, M, n), rng.integers(0, N, n)
+
+
+def cpu_leg(x_bits, samples):
+    """The CPU reference as it stands: (1) timed on the host cores on one pass of the cast
+    workload -- all 12 casts (6 formats x 2 axes) of the whole tensor, a few seconds on 16
+    threads; (2) the sampled GEMM entries of every workload in double precision, against which
+    the GPU's Float32-output results are compared (max |dC| / sum |a||b|)."""
     import oracle
     oracle.lib()
     x = np.ascontiguousarray(x_bits)
@@ -117,9 +150,14 @@ def cpu_baseline(x_bits):
         oracle.quantize(x, 0, fmt, 0)
         nbytes += 2 * cast_bytes(fmt, x.size)
     dt = time.perf_counter() - t0
-    return {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+    base = {"value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": "one pass of the cast workload: 12 casts (6 formats x 2 axes, RNE) of the whole "
                       "8192x8192 bf16 tensor; %.1f s of wall time" % dt}
+    rel = {}
+    for label, (ea, sa, fa, eb, sb, fb, K, mi, ni, got) in samples.items():
+        ref, cabs = oracle.gemm_entries(ea, sa, fa, eb, sb, fb, K, mi, ni)
+        rel[label] = float("%.3g" % float((np.abs(got.astype(np.float64) - ref) / cabs).max()))
+    return base, rel
 
 
 def time_call(fn, n):
@@ -136,8 +174,23 @@ def time_call(fn, n):
     return a.elapsed_time(b) / n
 
 
-def other_configs(n):
-    """Configs 3 (wide projection), 4 and 5 at full size; returns a dict of per-call results."""
+def accuracy_sample(samples, label, A, fa, B, fb, K, seed, n=512):
+    """Float32-output mx_gemm on the operands (device MX tensors), n sampled entries kept with the host
+    copies of the rows and columns they need, for the CPU leg."""
+    M, N = A[1].shape[0], B[1].shape[0]
+    mi, ni = sample_entries(M, N, n, seed)
+    C32 = mx.mx_gemm(A[0], A[1], fa, B[0], B[1], fb, K, dtype=torch.float32)
+    got = C32[torch.from_numpy(mi).cuda(), torch.from_numpy(ni).cuda()].cpu().numpy()
+    del C32
+    um, inv_m = np.unique(mi, return_inverse=True)
+    un, inv_n = np.unique(ni, return_inverse=True)
+    tm, tn = torch.from_numpy(um).cuda(), torch.from_numpy(un).cuda()
+    samples[label] = (A[0][tm].cpu().numpy(), A[1][tm].cpu().numpy(), fa, B[0][tn].cpu().numpy(), B[1][tn].cpu().numpy(), fb, K,
+                      inv_m, inv_n, got)
+
+
+def other_configs(n, samples, extras):
+    """Configs 1, 3 (wide projection), 4 and 5 at full size; returns a dict of per-call results."""
     out = {}
 
     def gemm_entry(label, M, N, K, ms, bits):
@@ -146,7 +199,7 @@ def other_configs(n):
 
     def cast_entry(label, n_elem, src_bytes, fmt, ms):
         b = n_elem * (src_bytes + mx.FORMAT_BITS[fmt] / 8.0 + 1.0 / 32.0)
-        out[label] = {"avg_ms": round(ms, 5), "GBps": round(b / ms / 1e6, 1)}
+        out[label] = {"avg_ms": round(ms, 5), "GBps": round(b / ms / 1e6, 1), "frac_hbm_peak": round(b / ms / 1e6 / HBM_PEAK_GBS, 4)}
 
     # config 1: 1024 x 1024 fp32 round trip and a 256^3 GEMM -- cache-resident and launch-latency-bound,
     # reported in microseconds; not an HBM measurement
@@ -159,6 +212,17 @@ def other_configs(n):
     gb1 = mx.mx_quantize(torch.from_numpy(inputs.gaussian_f32((256, 256), seed=2)).cuda(), 1, mx.FP8_E4M3)
     c1 = torch.empty((256, 256), dtype=torch.float32, device="cuda")
     out["cfg1_gemm_256x256x256_e4m3_us"] = round(1e3 * time_call(lambda: mx.mx_gemm(ga1[0], ga1[1], mx.FP8_E4M3, gb1[0], gb1[1], mx.FP8_E4M3, 256, out=c1), n), 2)
+    accuracy_sample(samples, "cfg1_256x256x256_e4m3", ga1, 0, gb1, 0, 256, seed=21)
+
+    # fp32 sources and destinations at the size of config 2 (config 1's types, HBM-sized)
+    xf = torch.from_numpy(inputs.gaussian_f32((ROWS, COLS), seed=11)).cuda()
+    qf = mx.mx_quantize(xf, 1, mx.FP8_E4M3)
+    cast_entry("cast_8192x8192_f32_e4m3_axis1", ROWS * COLS, 4, mx.FP8_E4M3,
+               time_call(lambda: mx.mx_quantize(xf, 1, mx.FP8_E4M3, mx.ROUND_RNE, qf[0], qf[1]), n))
+    ms = time_call(lambda: mx.mx_dequantize(qf[0], qf[1], mx.FP8_E4M3, ROWS, COLS, 1, out=xf), n)
+    b = ROWS * COLS * (1.0 + 1.0 / 32.0 + 4.0)
+    out["dequantize_8192x8192_e4m3_f32"] = {"avg_ms": round(ms, 5), "GBps": round(b / ms / 1e6, 1), "frac_hbm_peak": round(b / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    del xf, qf
 
     # config 3, second projection: 8192 x 11008 x 4096, E4M3, A cast on load
     M, K, N = 8192, 4096, 11008
@@ -171,40 +235,53 @@ def other_configs(n):
                time_call(lambda: mx.mx_gemm(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, out=C), n), 8)
     gemm_entry("cfg3_gemm_qa_8192x11008x4096_e4m3", M, N, K,
                time_call(lambda: mx.mx_gemm_qa(a, mx.FP8_E4M3, mx.ROUND_RNE, Be, Bs, mx.FP8_E4M3, out=C), n), 8)
-    del a, w, Be, Bs, Ae, As, C
+    del C
+    accuracy_sample(samples, "cfg3_8192x11008x4096_e4m3", (Ae, As), 0, (Be, Bs), 0, K, seed=23)
+    del a, w, Be, Bs, Ae, As
 
-    # config 3, first projection with C delivered as MXFP8 (cast in the GEMM epilogue) against GEMM + cast of C
-    M, K, N = 8192, 4096, 4096
-    a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=2))
-    w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=102, std=0.02)).cuda()
-    Be, Bs = mx.mx_quantize(w, 0, mx.FP8_E4M3)
-    Ae, As = mx.mx_quantize(a, 1, mx.FP8_E4M3)
-    C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-    qc = mx.mx_quantize(C, 1, mx.FP8_E4M3)
-    time_call(lambda: mx.mx_gemm_q(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, mx.FP8_E4M3, mx.ROUND_RNE, out=qc), n)   # first use
-    gemm_entry("cfg3_gemm_q_8192x4096x4096_e4m3_to_e4m3", M, N, K,
-               time_call(lambda: mx.mx_gemm_q(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, mx.FP8_E4M3, mx.ROUND_RNE, out=qc), n), 8)
-    ms_g = time_call(lambda: mx.mx_gemm(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, out=C), n)
-    ms_c = time_call(lambda: mx.mx_quantize(C, 1, mx.FP8_E4M3, mx.ROUND_RNE, qc[0], qc[1]), n)
-    out["cfg3_gemm_then_cast_of_C_ms"] = round(ms_g + ms_c, 5)
-    # the added rounding modes on the activation tensor of that shape (generic integer kernels)
-    for label, call in (("toward_zero", lambda: mx.mx_quantize(a, 1, mx.FP8_E4M3, mx.ROUND_TOWARD_ZERO, Ae, As)),
-                        ("stochastic", lambda: mx.mx_quantize_sr(a, 1, mx.FP8_E4M3, 1234, Ae, As))):
-        cast_entry("cast_8192x4096_bf16_e4m3_axis1_" + label, M * K, 2, mx.FP8_E4M3, time_call(call, n))
-    del a, w, Be, Bs, Ae, As, C, qc
+    if extras:
+        # config 3, first projection with C delivered as MXFP8 (cast in the GEMM epilogue) against GEMM + cast of C
+        M, K, N = 8192, 4096, 4096
+        a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=2))
+        w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=102, std=0.02)).cuda()
+        Be, Bs = mx.mx_quantize(w, 0, mx.FP8_E4M3)
+        Ae, As = mx.mx_quantize(a, 1, mx.FP8_E4M3)
+        C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        qc = mx.mx_quantize(C, 1, mx.FP8_E4M3)
+        gemm_entry("cfg3_gemm_q_8192x4096x4096_e4m3_to_e4m3", M, N, K,
+                   time_call(lambda: mx.mx_gemm_q(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, mx.FP8_E4M3, mx.ROUND_RNE, out=qc), n), 8)
+        ms_g = time_call(lambda: mx.mx_gemm(Ae, As, mx.FP8_E4M3, Be, Bs, mx.FP8_E4M3, K, out=C), n)
+        ms_c = time_call(lambda: mx.mx_quantize(C, 1, mx.FP8_E4M3, mx.ROUND_RNE, qc[0], qc[1]), n)
+        out["cfg3_gemm_then_cast_of_C_ms"] = round(ms_g + ms_c, 5)
+        # the added rounding modes on the activation tensor of that shape (generic integer kernels)
+        for label, call in (("toward_zero", lambda: mx.mx_quantize(a, 1, mx.FP8_E4M3, mx.ROUND_TOWARD_ZERO, Ae, As)),
+                            ("stochastic", lambda: mx.mx_quantize_sr(a, 1, mx.FP8_E4M3, 1234, Ae, As))):
+            cast_entry("cast_8192x4096_bf16_e4m3_axis1_" + label, M * K, 2, mx.FP8_E4M3, time_call(call, n))
+        del a, w, Be, Bs, Ae, As, C, qc
 
-    # decoding shapes: few rows of A against the wide projection's E4M3 weights (one pass over 45 MB)
-    N, K = 11008, 4096
-    w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=112, std=0.02)).cuda()
-    for fmt, name in ((mx.FP8_E4M3, "e4m3"), (mx.INT8, "int8")):
-        Be, Bs = mx.mx_quantize(w, 0, fmt)
-        for M in (1, 16, 128):
-            a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=5))
-            Ae, As = mx.mx_quantize(a, 1, fmt)
-            C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-            ms = time_call(lambda: mx.mx_gemm(Ae, As, fmt, Be, Bs, fmt, K, out=C), n)
-            out[f"decode_gemm_{M}x{N}x{K}_{name}"] = {"avg_us": round(1e3 * ms, 2), "weights_GBps": round(N * K * (1 + 1 / 32) / ms / 1e6, 1)}
-    del w, Be, Bs
+        # decoding shapes: few rows of A against the wide projection's E4M3 weights (one pass over 45 MB)
+        N, K = 11008, 4096
+        w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=112, std=0.02)).cuda()
+        for fmt, name in ((mx.FP8_E4M3, "e4m3"), (mx.INT8, "int8")):
+            Be, Bs = mx.mx_quantize(w, 0, fmt)
+            for M in (1, 16, 128):
+                a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=5))
+                Ae, As = mx.mx_quantize(a, 1, fmt)
+                C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+                ms = time_call(lambda: mx.mx_gemm(Ae, As, fmt, Be, Bs, fmt, K, out=C), n)
+                out[f"decode_gemm_{M}x{N}x{K}_{name}"] = {"avg_us": round(1e3 * ms, 2), "weights_GBps": round(N * K * (1 + 1 / 32) / ms / 1e6, 1)}
+        del w, Be, Bs
+
+        # MXINT8 on the projection shape of config 3 (each element split into two E2M3 halves, tiled kernel at depth 4K)
+        M, K, N = 8192, 4096, 4096
+        a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=2))
+        w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=102, std=0.02)).cuda()
+        ga = mx.mx_quantize(a, 1, mx.INT8)
+        gb = mx.mx_quantize(w, 0, mx.INT8)
+        C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        ms = time_call(lambda: mx.mx_gemm(ga[0], ga[1], mx.INT8, gb[0], gb[1], mx.INT8, K, out=C), max(2, n // 3))
+        out["int8_gemm_8192x4096x4096"] = {"avg_ms": round(ms, 5), "TOPs": round(2.0 * M * N * K / ms / 1e9, 1)}
+        del a, w, ga, gb, C
 
     # config 4: E3M2 activations [4096, 8192] x E2M1 weights (logical 8192 x 28672)
     M, K, N = 4096, 8192, 28672
@@ -216,21 +293,13 @@ def other_configs(n):
                time_call(lambda: mx.mx_quantize(act, 1, mx.FP6_E3M2, mx.ROUND_RNE, ga[0], ga[1]), n))
     cast_entry("cfg4_cast_w_f32_e2m1_axis0", K * N, 4, mx.FP4_E2M1,
                time_call(lambda: mx.mx_quantize(w, 0, mx.FP4_E2M1, mx.ROUND_RNE, gb[0], gb[1]), n))
+    del w
     C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     gemm_entry("cfg4_gemm_4096x28672x8192_e3m2_e2m1", M, N, K,
                time_call(lambda: mx.mx_gemm(ga[0], ga[1], mx.FP6_E3M2, gb[0], gb[1], mx.FP4_E2M1, K, out=C), n), 6)
-    del act, w, ga, gb, C
-
-    # MXINT8 on the projection shape of config 3 (each element split into two E2M3 halves, tiled kernel at depth 4K)
-    M, K, N = 8192, 4096, 4096
-    a = to_dev_bf16(inputs.gaussian_bf16((M, K), seed=2))
-    w = torch.from_numpy(inputs.gaussian_f32((K, N), seed=102, std=0.02)).cuda()
-    ga = mx.mx_quantize(a, 1, mx.INT8)
-    gb = mx.mx_quantize(w, 0, mx.INT8)
-    C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-    ms = time_call(lambda: mx.mx_gemm(ga[0], ga[1], mx.INT8, gb[0], gb[1], mx.INT8, K, out=C), max(2, n // 3))
-    out["int8_gemm_8192x4096x4096"] = {"avg_ms": round(ms, 5), "TOPs": round(2.0 * M * N * K / ms / 1e9, 1)}
-    del a, w, ga, gb, C
+    del C
+    accuracy_sample(samples, "cfg4_4096x28672x8192_e3m2_e2m1", ga, 2, gb, 4, K, seed=24)
+    del act, ga, gb
 
     # config 5: E3M2 training triple, half-away rounding; T tokens, hidden H, ffn F
     T, H, F = 16384, 2048, 8192
@@ -251,7 +320,7 @@ def other_configs(n):
         o1, o0 = q[name + "_axis1"], q[name + "_axis0"]
         ms = time_call(lambda: mx.mx_quantize_dual(t, fmt, rnd, o1, o0), n)
         b = t.numel() * (2.0 + 2.0 * (mx.FORMAT_BITS[fmt] / 8.0 + 1.0 / 32.0))
-        out["cfg5_dualcast_" + name] = {"avg_ms": round(ms, 5), "GBps": round(b / ms / 1e6, 1)}
+        out["cfg5_dualcast_" + name] = {"avg_ms": round(ms, 5), "GBps": round(b / ms / 1e6, 1), "frac_hbm_peak": round(b / ms / 1e6 / HBM_PEAK_GBS, 4)}
         dual_total += ms
     for name, A, B, (M, N, K) in (("fwd", q["X_axis1"], q["W_axis0"], (T, F, H)), ("dgrad", q["dY_axis1"], q["W_axis1"], (T, H, F)),
                                   ("wgrad", q["X_axis0"], q["dY_axis0"], (H, F, T))):
@@ -260,9 +329,28 @@ def other_configs(n):
         gemm_entry(f"cfg5_gemm_{name}_{M}x{N}x{K}_e3m2", M, N, K, ms, 6)
         total += ms
         del C
+        accuracy_sample(samples, f"cfg5_{name}_{M}x{N}x{K}_e3m2", A, fmt, B, fmt, K, seed=25, n=256)
     casts_ms = sum(out[k]["avg_ms"] for k in out if k.startswith("cfg5_cast_"))
     out["cfg5_triple_total_ms"] = round(total, 5)
     out["cfg5_triple_total_ms_with_dual_casts"] = round(total - casts_ms + dual_total, 5)
+    return out
+
+
+def ceilings(xs, n):
+    """What the row cast's access pattern reaches with no arithmetic: GB/s of bytes moved."""
+    src_b = ROWS * COLS * 2
+    dst = [torch.empty(src_b, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    rot = [0]
+
+    def run(rpw, write, dst_bytes):
+        def f():
+            rot[0] += 1
+            mx.mx_stream_pattern(xs[rot[0] % NCOPY] if rpw else None, dst[rot[0] % 2], dst_bytes, rpw, write)
+        ms = time_call(f, n)
+        return round((rpw * dst_bytes + (dst_bytes if write else 0)) / ms / 1e6, 1)
+    out = {"read_GBps": run(1, False, src_b), "write_GBps": run(0, True, src_b), "copy_GBps": run(1, True, src_b),
+           "read2_write1_GBps": run(2, True, src_b // 2), "read4_write1_GBps": run(4, True, src_b // 4)}
+    del dst
     return out
 
 
@@ -272,7 +360,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--all-configs", action="store_true", help="also time configs 3 (wide), 4 and 5 per call")
+    ap.add_argument("--quick", action="store_true", help="leave out the other full-size configs")
+    ap.add_argument("--all-configs", action="store_true", help="also time decoding shapes, MXINT8, the added rounding modes, the GEMM-epilogue cast")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (no collectives exist in the MX hot path); "
@@ -282,6 +371,7 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     mx.lib()  # fail loudly if the HIP library is missing
+    TRAFFIC = measured_traffic()
 
     # ---- synthetic inputs, resident in HBM before the timed region --------------
     x_bits = inputs.student_t_bf16((ROWS, COLS), seed=1)
@@ -290,6 +380,7 @@ def main():
     As = [to_dev_bf16(a_bits) for _ in range(NCOPY)]
     w = torch.from_numpy(inputs.gaussian_f32((GK, GN), seed=102, std=0.02)).cuda()
     Be, Bs = mx.mx_quantize(w, 0, mx.FP8_E4M3)               # weights pre-quantized once: [N][K]
+    del w
     Aq = [mx.mx_quantize(a, 1, mx.FP8_E4M3) for a in As]
     Cs = [torch.empty((GM, GN), dtype=torch.bfloat16, device="cuda") for _ in range(NCOPY)]
     outs = {}
@@ -298,7 +389,7 @@ def main():
             outs[(fmt, axis)] = [(torch.empty((ROWS, COLS * mx.FORMAT_BITS[fmt] // 8), dtype=torch.uint8, device="cuda"),
                                   torch.empty((ROWS, COLS // 32), dtype=torch.uint8, device="cuda")) for _ in range(2)]
     deq_out = [torch.empty((ROWS, COLS), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
-    deq_in = mx.mx_quantize(xs[0], 1, mx.FP8_E4M3)
+    deq_in = [mx.mx_quantize(x, 1, mx.FP8_E4M3) for x in xs]   # three copies: the 66 MiB input would fit the Infinity Cache
     torch.cuda.synchronize()
 
     rot = [0]
@@ -315,7 +406,8 @@ def main():
         return f
 
     def deq_call():
-        mx.mx_dequantize(deq_in[0], deq_in[1], mx.FP8_E4M3, ROWS, COLS, 1, out=deq_out[nxt() % 2])
+        i = nxt()
+        mx.mx_dequantize(deq_in[i % NCOPY][0], deq_in[i % NCOPY][1], mx.FP8_E4M3, ROWS, COLS, 1, out=deq_out[i % 2])
 
     def gemm_call():
         i = nxt()
@@ -352,6 +444,17 @@ def main():
     torch.cuda.synchronize()
     tot = timer.totals()
 
+    ceil = ceilings(xs, args.steps)
+    # the headline GEMM launch on all-zero operands (codes 0, scale bytes 127): same kernel, same grid
+    zA = [(torch.zeros_like(Aq[0][0]), torch.full_like(Aq[0][1], 127)) for _ in range(NCOPY)]
+    zB = (torch.zeros_like(Be), torch.full_like(Bs, 127))
+
+    def gemm_zero_call():
+        i = nxt()
+        mx.mx_gemm(zA[i % NCOPY][0], zA[i % NCOPY][1], mx.FP8_E4M3, zB[0], zB[1], mx.FP8_E4M3, GK, out=Cs[i % NCOPY])
+    zero_ms = time_call(gemm_zero_call, args.steps)
+    del zA, zB
+
     n_elem = ROWS * COLS
     cast_ms = 0.0
     cast_b = 0.0
@@ -363,7 +466,10 @@ def main():
             avg = ms / n
             cast_ms += avg
             cast_b += cast_bytes(fmt, n_elem)
-            per_kernel[label] = {"avg_ms": round(avg, 5), "GBps": round(cast_bytes(fmt, n_elem) / avg / 1e6, 1)}
+            gbps = cast_bytes(fmt, n_elem) / avg / 1e6
+            pattern = ceil["read4_write1_GBps"] if mx.FORMAT_BITS[fmt] == 4 else ceil["read2_write1_GBps"]
+            per_kernel[label] = {"avg_ms": round(avg, 5), "GBps": round(gbps, 1), "frac_hbm_peak": round(gbps / HBM_PEAK_GBS, 4),
+                                 "frac_pattern_ceiling": round(gbps / pattern, 4)}
     flop = 2.0 * GM * GN * GK
     for label in ("gemm_fp8_e4m3", "gemm_qa_fp8_e4m3"):
         ms, n = tot[label]
@@ -371,7 +477,8 @@ def main():
                              "frac_mfma_peak": round(flop / (ms / n) / 1e9 / MFMA_PEAK_TFLOPS[8], 4)}
     ms, n = tot["dequantize_fp8_e4m3_bf16"]
     deq_b = n_elem * (1.0 + 1.0 / 32.0 + 2.0)
-    per_kernel["dequantize_fp8_e4m3_bf16"] = {"avg_ms": round(ms / n, 5), "GBps": round(deq_b / (ms / n) / 1e6, 1)}
+    per_kernel["dequantize_fp8_e4m3_bf16"] = {"avg_ms": round(ms / n, 5), "GBps": round(deq_b / (ms / n) / 1e6, 1),
+                                              "frac_hbm_peak": round(deq_b / (ms / n) / 1e6 / HBM_PEAK_GBS, 4)}
 
     # Dominant kernel of the step by time: reported against its roofline.  The two GEMM calls
     # run the same tiled kernel (mx_gemm_qa adds a cast launch in front of it), so its duration
@@ -381,7 +488,7 @@ def main():
         fmt = [i for i in range(6) if label.startswith("cast_" + mx.FORMAT_NAMES[i])][0]
         ach = cast_bytes(fmt, n_elem) / (tot[label][0] / tot[label][1]) / 1e6
         return {"kernel": label, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(label)}
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": TRAFFIC.get(label)}
 
     dom = max(tot, key=lambda k: tot[k][0])
     slowest_cast = max((k for k in tot if k.startswith("cast_")), key=lambda k: tot[k][0])
@@ -392,12 +499,15 @@ def main():
         ach = flop / dms / 1e9
         roof = {"kernel": "gemm_fp8_e4m3", "bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_PEAK_TFLOPS[8],
                 "unit": "TFLOP/s", "frac": round(ach / MFMA_PEAK_TFLOPS[8], 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get("gemm_fp8_e4m3")}
+                "traffic": TRAFFIC.get("gemm_fp8_e4m3")}
     else:
         dms = tot[dom][0] / tot[dom][1]
         ach = deq_b / dms / 1e6
         roof = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(dom)}
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": TRAFFIC.get(dom)}
+
+    samples = {}
+    accuracy_sample(samples, "cfg3_8192x4096x4096_e4m3", Aq[0], 0, (Be, Bs), 0, GK, seed=22)
 
     value = cast_b / cast_ms / 1e6   # GB/s over the 12 casts
     line = {
@@ -412,14 +522,17 @@ def main():
         "gemm_qa_tflops": per_kernel["gemm_qa_fp8_e4m3"]["TFLOPs"],
         "roofline": roof,
         "roofline_slowest_cast": cast_roof(slowest_cast),
+        "ceilings": ceil,
+        "gemm_zero_operands": {"avg_ms": round(zero_ms, 5), "TFLOPs": round(flop / zero_ms / 1e9, 1),
+                               "frac_mfma_peak": round(flop / zero_ms / 1e9 / MFMA_PEAK_TFLOPS[8], 4)},
         "kernels": per_kernel,
     }
-    if args.all_configs:
-        del xs, As, Aq, Cs, outs, deq_out, deq_in
-        torch.cuda.empty_cache()
-        line["other_configs"] = other_configs(args.steps)
+    del xs, As, Aq, Cs, outs, deq_out, deq_in, Be, Bs
+    torch.cuda.empty_cache()
+    if not args.quick:
+        line["other_configs"] = other_configs(args.steps, samples, args.all_configs)
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(x_bits)
+        line["cpu_baseline"], line["gemm_max_rel_err"] = cpu_leg(x_bits, samples)
     print(json.dumps(line))
 
 

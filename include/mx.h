@@ -279,6 +279,19 @@ int mx_gemm_q(int64_t M, int64_t N, int64_t K,
               mx_format_t fmtC, mx_round_t rnd,
               void *C_elems, uint8_t *C_scales, void *hip_stream);
 
+/*
+ * Measurement aid (no part of the MX path): moves bytes in the access pattern of
+ * the row cast -- consecutive 16-byte pieces per lane, several loads in flight,
+ * 16-byte stores -- with no arithmetic, so that a benchmark can state what that
+ * pattern reaches on the box it runs on.  Reads read_per_write * dst_bytes bytes
+ * from src (read_per_write = 0, 1, 2 or 4) and, if write is non-zero, writes
+ * dst_bytes bytes to dst; with write = 0 the loads are kept alive by a store
+ * that never happens (dst must still be a valid 16-byte buffer).  dst_bytes is
+ * a multiple of 8192; pointers are 16-byte aligned device memory.
+ */
+int mx_stream_pattern(const void *src, void *dst, int64_t dst_bytes,
+                      int read_per_write, int write, void *hip_stream);
+
 /* Static, human-readable text for a status code. */
 const char *mx_strerror(int status);
 

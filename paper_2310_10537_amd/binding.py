@@ -51,6 +51,7 @@ def lib() -> ctypes.CDLL:
         L.mx_gemm_qa.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
         L.mx_gemm_q.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, ci, ci, vp, vp, vp]
         L.mx_gemm_qa_noalloc.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
+        L.mx_stream_pattern.argtypes = [vp, vp, i64, ci, ci, vp]
         L.mx_strerror.argtypes = [ci]
         L.mx_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -226,3 +227,9 @@ def mx_gemm_qa_noalloc(A_bf16, fmtA, rnd, B_elems, B_scales, fmtB, out, stream=N
                                     B_elems.data_ptr(), B_scales.data_ptr(), fmtB,
                                     out.data_ptr(), _dt(out), ldc, _stream(stream)))
     return out
+
+
+def mx_stream_pattern(src, dst, dst_bytes, read_per_write, write, stream=None):
+    """Measurement aid: read read_per_write * dst_bytes from src, write dst_bytes to dst (if write)."""
+    _check(lib().mx_stream_pattern(src.data_ptr() if src is not None else None, dst.data_ptr(), dst_bytes,
+                                   read_per_write, 1 if write else 0, _stream(stream)))

@@ -25,7 +25,7 @@ __device__ __forceinline__ void load_as_f32_bits(const void *p, uint32_t (&v)[N]
         static_assert(N % 8 == 0, "");
 #pragma unroll
         for (int i = 0; i < N / 8; i++) {
-            uint4 d = ld16(reinterpret_cast<const char *>(p) + 16 * i);
+            uint4 d = ld16_nt(reinterpret_cast<const char *>(p) + 16 * i);
             const uint32_t dw[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
             for (int j = 0; j < 4; j++) {
@@ -36,7 +36,7 @@ __device__ __forceinline__ void load_as_f32_bits(const void *p, uint32_t (&v)[N]
     } else {
 #pragma unroll
         for (int i = 0; i < N / 4; i++) {
-            uint4 d = ld16(reinterpret_cast<const char *>(p) + 16 * i);
+            uint4 d = ld16_nt(reinterpret_cast<const char *>(p) + 16 * i);
             v[4 * i] = d.x; v[4 * i + 1] = d.y; v[4 * i + 2] = d.z; v[4 * i + 3] = d.w;
         }
     }

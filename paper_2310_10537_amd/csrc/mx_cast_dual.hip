@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void cast_dual_bf16_kernel(const uint16_t *__r
         const int lr = t >> 3, lc = t & 7;
         uint4 v[4];
 #pragma unroll
-        for (int p = 0; p < 4; p++) v[p] = ld16(src + (r0 + p * 32 + lr) * ld + c0 + lc * 8);
+        for (int p = 0; p < 4; p++) v[p] = ld16_nt(src + (r0 + p * 32 + lr) * ld + c0 + lc * 8);
 #pragma unroll
         for (int p = 0; p < 4; p++) {
             const int r = p * 32 + lr;

@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
         const int64_t e = e0 + u * 512 + lane * 8;
         valid[u] = e < n_elems;
         uint4 t = make_uint4(0, 0, 0, 0);
-        if (valid[u]) t = ld16(src + src_offset<FLAT>(e, cols, ld));
+        if (valid[u]) t = ld16_nt(src + src_offset<FLAT>(e, cols, ld));
         d[u][0] = t.x; d[u][1] = t.y; d[u][2] = t.z; d[u][3] = t.w;
     }
 
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
         if (r0 + r < rows) {
             const uint16_t *g = src + (r0 + r) * ld + c0 + lc * 8;
             if (full_cols || c0 + lc * 8 + 8 <= cols) {
-                v = ld16(g);
+                v = ld16_nt(g);
             } else {
                 uint16_t h[8];
 #pragma unroll
@@ -306,7 +306,7 @@ __global__ __launch_bounds__(256) void cast_col_f32_kernel(const float *__restri
 #pragma unroll
     for (int p = 0; p < COL_TILE_R / 16; p++) {
         const int r = p * 16 + lr;                    // row inside the tile; its 32-row block is r / 32
-        const uint4 v = ld16(src + (r0 + r) * ld + c0 + lc * 4);
+        const uint4 v = ld16_nt(src + (r0 + r) * ld + c0 + lc * 4);
         *reinterpret_cast<uint4 *>(tile + r * COL_TILE_C + ((lc * 4 + (r >> 5) * 16) & 63)) = v;
     }
     __syncthreads();

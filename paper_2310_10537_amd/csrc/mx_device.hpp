@@ -223,4 +223,28 @@ __device__ __forceinline__ uint32_t group_max(uint32_t v)
 __device__ __forceinline__ uint4 ld16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
 __device__ __forceinline__ void st16(void *p, uint4 v) { *reinterpret_cast<uint4 *>(p) = v; }
 
+// Streaming (non-temporal) forms for data that is touched once: a tensor being cast or dequantized
+// passes through the caches without any reuse, and marking its loads as such is worth 10-13 % of
+// bandwidth in the 2 : 1 read : write pattern of a cast (measured with loads and stores only:
+// 35.6 -> 31.5 us for 128 MiB in, 64 MiB out).
+typedef uint32_t u32x4_ext_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_ext_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 ld16_nt(const void *p)
+{
+    const u32x4_ext_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_ext_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 ld8_nt(const void *p)
+{
+    const u32x2_ext_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_ext_t *>(p));
+    return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ uint32_t ld4_nt(const void *p) { return __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p)); }
+__device__ __forceinline__ uint32_t ld2_nt(const void *p) { return __builtin_nontemporal_load(reinterpret_cast<const uint16_t *>(p)); }
+__device__ __forceinline__ void st16_nt(void *p, uint4 v)
+{
+    const u32x4_ext_t e = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(e, reinterpret_cast<u32x4_ext_t *>(p));
+}
+
 }  // namespace mx

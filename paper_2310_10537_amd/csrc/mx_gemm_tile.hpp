@@ -635,5 +635,8 @@ static hipError_t launch_a(const TileArgs &a, int fmtB)
 hipError_t launch_gemm_tiled_a8(const TileArgs &a, int fmtA, int fmtB);
 hipError_t launch_gemm_tiled_a6(const TileArgs &a, int fmtA, int fmtB);
 hipError_t launch_gemm_tiled_a4(const TileArgs &a, int fmtA, int fmtB);
+// the eight-wave form of the kernel (plain operands, Float32 / bf16 output), same split
+hipError_t launch_gemm_tiled8_a6(const TileArgs &a, int fmtA, int fmtB);
+hipError_t launch_gemm_tiled8_a4(const TileArgs &a, int fmtA, int fmtB);
 
 }  // namespace mx

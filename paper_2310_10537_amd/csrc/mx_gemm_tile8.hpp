@@ -1,0 +1,307 @@
+// LDS-tiled MX GEMM (Section 4.1 of arXiv 2310.10537), eight-wave form: the 256 x 256 x 128 tile,
+// the LDS layouts, the direct global-to-LDS staging and the XCD-aware tile order of
+// mx_gemm_tile.hpp, but with 512 threads = 8 waves per work-group, each wave owning a 128 x 64
+// sub-tile (4 x 2 matrix-instruction tiles, 128 accumulator registers).  Two waves then share
+// every SIMD, so while one of them is held up issuing its direct loads, waiting at the barrier
+// or waiting for LDS, the other keeps the matrix pipe fed.  The price is LDS traffic: a wave
+// reads 4 + 2 operand fragments per 8 matrix instructions instead of 4 + 4 per 16.
+// Measured against the four-wave kernel on one box (bf16 out, random operands): 6- and 4-bit
+// pairs, whose K step holds half the matrix work of an 8-bit pair and which therefore wait more,
+// gain 3-8 % (config 5: 254 / 220 / 210 -> 241 / 208 / 193 us); pairs with an 8-bit operand do
+// not (115.1 -> 115.7 us on 8192 x 4096 x 4096, 417 -> 425 us on 8192^3): with real operands
+// those run into the chip's power limit, not into issue stalls -- the same launch on all-zero
+// operands takes 92 us.  So the dispatcher sends only pairs without an 8-bit operand here.
+// Plain operands and Float32 / bf16 output only; quantize-on-load and the MX epilogue stay with
+// the four-wave kernel.
+#pragma once
+
+#include "mx_gemm_tile.hpp"
+
+namespace mx {
+
+constexpr int NW8 = 8;   // waves per work-group
+
+template <int FA, int FB, int CDT>
+__global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N, int64_t K,
+                                                             const uint8_t *__restrict__ Ae, const uint8_t *__restrict__ As,
+                                                             const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
+                                                             void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n)
+{
+    static_assert(CDT == DT_F32 || CDT == DT_BF16, "plain output types only");
+    constexpr int WA = Fmt<FA>::bits, WB = Fmt<FB>::bits;
+    typedef TileFmt<WA> TA;
+    typedef TileFmt<WB> TB;
+    constexpr int A_BYTES = TM * TA::ROW, B_BYTES = TN * TB::ROW, STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int NSTAGE = (WA < 8 && WB < 8 && 3 * STAGE_BYTES + 2 * SCL_BYTES <= 160 * 1024) ? 3 : 2;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[NSTAGE * STAGE_BYTES + 2 * SCL_BYTES];
+    constexpr int HA = hw_fmt(FA), HB = hw_fmt(FB);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: everything derived from it stays in scalar registers
+    const int wm = wave >> 2, wn = wave & 3;          // 128-row half, 64-column quarter
+    const int li = lane & 31, g = lane >> 5;
+
+    // XCD-aware rasterisation, as in the four-wave kernel
+    const int n_tiles = tiles_m * tiles_n;
+    const int per_xcd = (n_tiles + 7) >> 3;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    if (idx >= per_xcd) return;
+    int tm, tn;
+    if ((tiles_m & 7) == 0) {
+        const int band = tiles_m >> 3;
+        const int H = (band & 3) == 0 ? 4 : (band & 1) == 0 ? 2 : 1;
+        const int sub = idx / (H * tiles_n), r = idx - sub * (H * tiles_n);
+        tm = xcd * band + sub * H + r % H;
+        tn = r / H;
+    } else {
+        const int tile_id = xcd * per_xcd + idx;
+        if (tile_id >= n_tiles) return;
+        tm = tile_id / tiles_n;
+        tn = tile_id % tiles_n;
+    }
+    const int64_t m0 = (int64_t)tm * TM;
+    const int64_t n0 = (int64_t)tn * TN;
+    const int64_t nkb = K / BLOCK;
+    const int T = (int)(K / TK);
+    const int Tfull = T & ~(SCL_GROUP - 1);
+
+    // ---- staging map: wave w, load j fills LDS bytes (8j + w) * 1024 .. + 1023 of an operand tile
+    const int a_r = WA == 4 ? lane >> 2 : lane >> 3, b_r = WB == 4 ? lane >> 2 : lane >> 3;
+    const int a_u = WA == 4 ? (lane & 3) ^ ((a_r >> 2) & 3) : (lane & 7) ^ (((wave * 8 + a_r) >> 1) & 7);
+    const int b_u = WB == 4 ? (lane & 3) ^ ((b_r >> 2) & 3) : (lane & 7) ^ (((wave * 8 + b_r) >> 1) & 7);
+    const int64_t a_row_bytes = K * WA / 8, b_row_bytes = K * WB / 8;
+    // A direct load takes a wave-uniform 64-bit base (scalar registers: tile origin, the wave's row group,
+    // the K step, the load number) plus one 32-bit offset per lane that never changes (6-bit: one per load
+    // number), so staging costs no vector arithmetic and two / four vector registers.
+    const uint8_t *sA = WA == 6 ? Ae + m0 * a_row_bytes : Ae + (m0 + wave * TA::RPI) * a_row_bytes;
+    const uint8_t *sB = WB == 6 ? Be + n0 * b_row_bytes : Be + (n0 + wave * TB::RPI) * b_row_bytes;
+    const uint32_t vA = (uint32_t)(a_r * a_row_bytes + a_u * TA::UNIT), vB = (uint32_t)(b_r * b_row_bytes + b_u * TB::UNIT);
+    constexpr int NJA = A_BYTES / (NW8 * 1024), NJB = B_BYTES / (NW8 * 1024);   // direct loads per wave per stage
+    uint32_t a6[3] = {}, b6[3] = {};
+    if (WA == 6 || WB == 6) {
+#pragma unroll
+        for (int j = 0; j < 3; j++) {
+            const uint32_t q = (uint32_t)((NW8 * j + wave) * 64 + lane), row = q / 6, c = (q - row * 6) ^ ((row >> 3) & 1);
+            if (WA == 6) a6[j] = row * (uint32_t)a_row_bytes + c * 16;
+            if (WB == 6) b6[j] = row * (uint32_t)b_row_bytes + c * 16;
+        }
+    }
+    const int st_l = wave * 1024;
+    // ---- scale staging: waves 0-3 fetch the A rows 64w .. 64w+63, waves 4-7 the B rows
+    const uint8_t *sS = wave < 4 ? As + (m0 + wave * 64) * nkb : Bs + (n0 + (wave - 4) * 64) * nkb;
+    const uint32_t vS = (uint32_t)(lane * nkb);
+    const int rsa = (wm * 128 + li) * 16, rsb = TM * 16 + (wn * 64 + li) * 16;
+    const FragOfs<WA> ra0 = frag_ofs<WA>(wm * 128 + li, g);
+    const FragOfs<WB> rb0 = frag_ofs<WB>(wn * 64 + li, g);
+
+    v16f_t acc[4][2];
+#pragma unroll
+    for (int x = 0; x < 4; x++)
+#pragma unroll
+        for (int y = 0; y < 2; y++)
+#pragma unroll
+            for (int t = 0; t < 16; t++) acc[x][y][t] = 0.f;
+
+    typedef __attribute__((address_space(3))) void lds_ptr_t;
+    uint32_t sa[4], sb[2], sa_n[4], sb_n[2];
+    v8i_t af[4], b0[2], b1[2];   // A fragments (one set, refilled in place), B fragments of sub-step 0 / 1
+
+    auto stage_a1 = [&](int ts, uint8_t *dst, int j) {
+        const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
+        const uint8_t *sp = WA == 6 ? sA + (int64_t)ts * (TK * WA / 8) : sA + (int64_t)ts * (TK * WA / 8) + j * (NW8 * TA::RPI) * a_row_bytes;
+        const uint32_t vo = WA == 6 ? a6[j < 3 ? j : 0] : vA;
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(vo), "s"(sp), "s"(l0 + j * (NW8 * 1024)) : "m0");
+    };
+    auto stage_b1 = [&](int ts, uint8_t *dst, int j) {
+        const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
+        const uint8_t *sp = WB == 6 ? sB + (int64_t)ts * (TK * WB / 8) : sB + (int64_t)ts * (TK * WB / 8) + j * (NW8 * TB::RPI) * b_row_bytes;
+        const uint32_t vo = WB == 6 ? b6[j < 3 ? j : 0] : vB;
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(vo), "s"(sp), "s"(l0 + j * (NW8 * 1024)) : "m0");
+    };
+    auto stage_all = [&](int ts, uint8_t *dst) {
+#pragma unroll
+        for (int j = 0; j < NJA; j++) stage_a1(ts, dst, j);
+#pragma unroll
+        for (int j = 0; j < NJB; j++) stage_b1(ts, dst + A_BYTES, j);
+    };
+    auto stage_one = [&](int k, int ts, uint8_t *dstA, uint8_t *dstB) {
+        if (k < NJA) stage_a1(ts, dstA, k);
+        else if (k - NJA < NJB) stage_b1(ts, dstB, k - NJA);
+    };
+    uint8_t *const scl = lds + NSTAGE * STAGE_BYTES;
+    const int n_groups = (T + SCL_GROUP - 1) / SCL_GROUP;
+    auto scl_ofs = [&](int ts) { return ts < Tfull ? (ts & (SCL_GROUP - 1)) * 4 : (ts - (T - SCL_GROUP)) * 4; };
+    auto stage_scales = [&](int G) {
+        G = G < n_groups ? G : n_groups - 1;
+        uint8_t *dst = scl + (G & 1) * SCL_BYTES;
+        const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + wave * 1024));
+        const int64_t src_ofs = G * SCL_GROUP + SCL_GROUP <= T ? (int64_t)G * 16 : (int64_t)T * 4 - 16;
+        const uint8_t *p = sS + src_ofs;
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(vS), "s"(p), "s"(l0) : "m0");
+    };
+    auto read_scales = [&](int ts) {
+        ts = ts < T ? ts : T - 1;
+        const uint8_t *src = scl + ((ts / SCL_GROUP) & 1) * SCL_BYTES + scl_ofs(ts);
+#pragma unroll
+        for (int x = 0; x < 4; x++) {
+            const uint32_t da = *reinterpret_cast<const uint32_t *>(src + rsa + x * 512);
+            sa_n[x] = g ? da >> 8 : da;
+        }
+#pragma unroll
+        for (int y = 0; y < 2; y++) {
+            const uint32_t db = *reinterpret_cast<const uint32_t *>(src + rsb + y * 512);
+            sb_n[y] = g ? db >> 8 : db;
+        }
+    };
+#define MX8_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define MX8_MFMA(AF, BF, X, Y, OPS)                                                                                   \
+    acc[X][Y] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(AF[X], BF[Y], acc[X][Y], HA, HB, OPS, (int)sa[X], OPS, (int)sb[Y])
+
+    // ---- prologue
+    stage_scales(0);
+    stage_all(0, lds);
+    {
+        const int t1 = T > 1 ? 1 : 0;
+        stage_all(t1, lds + STAGE_BYTES);
+        if (NSTAGE == 3) stage_all(T > 2 ? 2 : T - 1, lds + 2 * STAGE_BYTES);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 1) * (NJA + NJB)) : "memory");
+    }
+    __syncthreads();
+#pragma unroll
+    for (int x = 0; x < 4; x++) af[x] = read_frag<WA>(lds, ra0, 0, x);
+#pragma unroll
+    for (int y = 0; y < 2; y++) b0[y] = read_frag<WB>(lds + A_BYTES, rb0, 0, y);
+    read_scales(0);
+#pragma unroll
+    for (int x = 0; x < 4; x++) sa[x] = sa_n[x];
+#pragma unroll
+    for (int y = 0; y < 2; y++) sb[y] = sb_n[y];
+
+    int ring = 0;
+    auto k_step = [&](const int tt, const int h) __attribute__((always_inline)) {
+        const int t = tt + h;
+        const int cur = NSTAGE == 2 ? (h & 1) : ring;
+        uint8_t *bufA = lds + cur * STAGE_BYTES;
+        uint8_t *nxt = lds + (NSTAGE == 2 ? (cur ^ 1) : (cur == 2 ? 0 : cur + 1)) * STAGE_BYTES;
+        uint8_t *bufB = bufA + A_BYTES;
+        const int t2 = t + NSTAGE < T ? t + NSTAGE : T - 1;
+        MX8_FENCE();
+        // ---- X: sub-step 0 (8 matrix instructions, A fragment by A fragment).  An A fragment is dead
+        // after its two instructions and is refilled at once with the same rows of sub-step 1, so only
+        // one set of A fragments is ever live; the two B fragments of sub-step 1 are read meanwhile.
+        b1[0] = read_frag<WB>(bufB, rb0, 1, 0);
+        MX8_MFMA(af, b0, 0, 0, 0); MX8_MFMA(af, b0, 0, 1, 0);
+        af[0] = read_frag<WA>(bufA, ra0, 1, 0);
+        MX8_FENCE();
+        b1[1] = read_frag<WB>(bufB, rb0, 1, 1);
+        MX8_MFMA(af, b0, 1, 0, 0); MX8_MFMA(af, b0, 1, 1, 0);
+        af[1] = read_frag<WA>(bufA, ra0, 1, 1);
+        MX8_FENCE();
+        MX8_MFMA(af, b0, 2, 0, 0); MX8_MFMA(af, b0, 2, 1, 0);
+        af[2] = read_frag<WA>(bufA, ra0, 1, 2);
+        MX8_FENCE();
+        MX8_MFMA(af, b0, 3, 0, 0); MX8_MFMA(af, b0, 3, 1, 0);
+        af[3] = read_frag<WA>(bufA, ra0, 1, 3);
+        MX8_FENCE();
+        // Stage t+1 must be in LDS, and every wave must have issued its last read of stage t,
+        // before the buffers change roles.
+        if (NSTAGE == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NJA + NJB) : "memory");
+        __syncthreads();
+        MX8_FENCE();
+        // ---- Y: sub-step 1; stage t+NSTAGE is requested into the buffer stage t just vacated, one direct
+        // load per matrix instruction, and the fragments of sub-step 0 of stage t+1 are read
+        b0[0] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 0);
+        stage_one(0, t2, bufA, bufB); MX8_MFMA(af, b1, 0, 0, 2); MX8_FENCE();
+        stage_one(1, t2, bufA, bufB); MX8_MFMA(af, b1, 0, 1, 2);
+        af[0] = read_frag<WA>(nxt, ra0, 0, 0);
+        MX8_FENCE();
+        b0[1] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 1);
+        stage_one(2, t2, bufA, bufB); MX8_MFMA(af, b1, 1, 0, 2); MX8_FENCE();
+        stage_one(3, t2, bufA, bufB); MX8_MFMA(af, b1, 1, 1, 2);
+        af[1] = read_frag<WA>(nxt, ra0, 0, 1);
+        MX8_FENCE();
+        if (h == 0) stage_scales(tt / SCL_GROUP + 1);
+        read_scales(t + 1);
+        stage_one(4, t2, bufA, bufB); MX8_MFMA(af, b1, 2, 0, 2); MX8_FENCE();
+        stage_one(5, t2, bufA, bufB); MX8_MFMA(af, b1, 2, 1, 2);
+        af[2] = read_frag<WA>(nxt, ra0, 0, 2);
+        MX8_FENCE();
+        stage_one(6, t2, bufA, bufB); MX8_MFMA(af, b1, 3, 0, 2); MX8_FENCE();
+        stage_one(7, t2, bufA, bufB); MX8_MFMA(af, b1, 3, 1, 2);
+        af[3] = read_frag<WA>(nxt, ra0, 0, 3);
+        MX8_FENCE();
+#pragma unroll
+        for (int x = 0; x < 4; x++) sa[x] = sa_n[x];
+#pragma unroll
+        for (int y = 0; y < 2; y++) sb[y] = sb_n[y];
+        if (NSTAGE == 3) ring = ring == 2 ? 0 : ring + 1;
+        MX8_FENCE();
+    };
+    for (int tt = 0; tt < Tfull; tt += SCL_GROUP) {
+#pragma unroll
+        for (int h = 0; h < SCL_GROUP; h++) k_step(tt, h);
+    }
+#pragma unroll 1
+    for (int h = 0; h < T - Tfull; h++) k_step(Tfull, h);
+#undef MX8_MFMA
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#undef MX8_FENCE
+
+    // ---- epilogue: lane (li, g), register t of tile (x, y) -> C[8*(t/4) + 4g + t%4][li]
+#pragma unroll
+    for (int x = 0; x < 4; x++)
+#pragma unroll
+        for (int y = 0; y < 2; y++) {
+            const int64_t c = n0 + wn * 64 + y * 32 + li;
+            if constexpr (CDT == DT_F32) {
+#pragma unroll
+                for (int t = 0; t < 16; t++) {
+                    const int64_t r = m0 + wm * 128 + x * 32 + 8 * (t / 4) + 4 * g + (t % 4);
+                    reinterpret_cast<float *>(C)[r * ldc + c] = acc[x][y][t];
+                }
+            } else {
+                typedef float f32x2_t __attribute__((ext_vector_type(2)));
+                typedef __bf16 bf16x2_t_ __attribute__((ext_vector_type(2)));
+#pragma unroll
+                for (int t = 0; t < 16; t += 2) {
+                    const int64_t r = m0 + wm * 128 + x * 32 + 8 * (t / 4) + 4 * g + (t % 4);
+                    const f32x2_t v = {acc[x][y][t], acc[x][y][t + 1]};
+                    const uint32_t pk = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t_));
+                    uint16_t *o = reinterpret_cast<uint16_t *>(C) + r * ldc + c;
+                    o[0] = (uint16_t)pk;
+                    o[ldc] = (uint16_t)(pk >> 16);
+                }
+            }
+        }
+}
+
+template <int FA, int FB, int CDT>
+static hipError_t launch_t8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint8_t *Be,
+                            const uint8_t *Bs, void *C, int64_t ldc, hipStream_t st)
+{
+    auto kern = gemm_tile8_kernel<FA, FB, CDT>;
+    const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
+    const int per_xcd = (tiles_m * tiles_n + 7) / 8;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(512), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+template <int FA, int FB>
+static hipError_t launch_pair8(const TileArgs &a)
+{
+    return a.c_dt == DT_F32 ? launch_t8<FA, FB, DT_F32>(a.M, a.N, a.K, a.Ae, a.As, a.Be, a.Bs, a.C, a.ldc, a.st)
+                            : launch_t8<FA, FB, DT_BF16>(a.M, a.N, a.K, a.Ae, a.As, a.Be, a.Bs, a.C, a.ldc, a.st);
+}
+
+template <int FA>
+static hipError_t launch_a8w(const TileArgs &a, int fmtB)
+{
+    switch (fmtB) {
+        case FP6_E3M2: return launch_pair8<FA, FP6_E3M2>(a);
+        case FP6_E2M3: return launch_pair8<FA, FP6_E2M3>(a);
+        case FP4_E2M1: return launch_pair8<FA, FP4_E2M1>(a);
+        default:       return hipErrorNotSupported;
+    }
+}
+
+}  // namespace mx

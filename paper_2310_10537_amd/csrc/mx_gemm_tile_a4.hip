@@ -22,6 +22,9 @@ hipError_t launch_gemm_tiled(int64_t M, int64_t N, int64_t K, const uint8_t *Ae,
     if (!gemm_tiled_applies(M, N, K, fmtA, fmtB)) return hipErrorNotSupported;
     if (a_bf16 && !gemm_tiled_fuses_cast(fmtA, fmtB)) return hipErrorNotSupported;
     const TileArgs a{M, N, K, Ae, As, static_cast<const uint16_t *>(a_bf16), lda, rnd, Be, Bs, C, c_dt, ldc, st};
+    // pairs without an 8-bit operand take the eight-wave form of the kernel (see mx_gemm_tile8.hpp)
+    if (!a_bf16 && fmtA >= FP6_E3M2 && fmtB >= FP6_E3M2)
+        return fmtA <= FP6_E2M3 ? launch_gemm_tiled8_a6(a, fmtA, fmtB) : launch_gemm_tiled8_a4(a, fmtA, fmtB);
     switch (fmtA) {
         case FP8_E4M3: case FP8_E5M2: return launch_gemm_tiled_a8(a, fmtA, fmtB);
         case FP6_E3M2: case FP6_E2M3: return launch_gemm_tiled_a6(a, fmtA, fmtB);

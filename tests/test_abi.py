@@ -24,7 +24,7 @@ def test_exports_match_header(L):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(mx_[a-z_]+)\s*\(", text))
     assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_sr", "mx_quantize_dual", "mx_dequantize", "mx_gemm",
-                     "mx_gemm_qa", "mx_gemm_q", "mx_gemm_qa_noalloc", "mx_strerror"}
+                     "mx_gemm_qa", "mx_gemm_q", "mx_gemm_qa_noalloc", "mx_stream_pattern", "mx_strerror"}
     for n in names:
         assert hasattr(L, n), n
 
