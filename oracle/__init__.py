@@ -47,6 +47,7 @@ def lib():
         L.mxo_philox4x32_words.restype = None
         L.mxo_sr_uniform.argtypes = [ctypes.c_uint64, i64]
         L.mxo_sr_uniform.restype = ctypes.c_double
+        L.mxo_quantize_3d.argtypes = [vp, ci, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, vp]
         L.mxo_dequantize.argtypes = [vp, vp, ci, i64, i64, ci, vp, ci, i64]
         L.mxo_gemm.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, vp]
         L.mxo_gemm_entries.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, i64, vp, vp, vp, vp]
@@ -139,6 +140,37 @@ def quantize(src, axis, fmt, rnd=ROUND_RNE, seed=None):
                                    int(seed or 0), _ptr(elems), _ptr(scales))
     if st != 0:
         raise ValueError("mxo_quantize rejected its arguments")
+    return elems, scales
+
+
+def quantize_3d(src, axis, fmt, rnd=ROUND_RNE, keep_order=False, strides=None):
+    """src: 3-D float32 array or uint16 array of bf16 bits; strides (stride0, stride1) in elements
+    when src is a flat buffer holding a strided tensor of shape `strides[2:]` (else C-contiguous).
+    Returns (elems, scales) shaped as mxo_quantize_3d documents."""
+    if strides is None:
+        src = np.ascontiguousarray(src)
+        d0, d1, d2 = src.shape
+        s0, s1 = d1 * d2, d2
+    else:
+        s0, s1, (d0, d1, d2) = strides[0], strides[1], strides[2]
+        src = np.ascontiguousarray(src).reshape(-1)
+        assert (d0 - 1) * s0 + (d1 - 1) * s1 + d2 <= src.size
+    w = elem_bits(fmt)
+    dim = (d0, d1, d2)
+    nblk = -(-dim[axis] // BLOCK)
+    if keep_order:
+        elems = np.zeros((d0, d1, d2 * w // 8), dtype=np.uint8)
+        sshape = list(dim)
+        sshape[axis] = nblk
+        scales = np.zeros(sshape, dtype=np.uint8)
+    else:
+        rest = [dim[i] for i in range(3) if i != axis]
+        elems = np.zeros((rest[0], rest[1], nblk * BLOCK * w // 8), dtype=np.uint8)
+        scales = np.zeros((rest[0], rest[1], nblk), dtype=np.uint8)
+    st = lib().mxo_quantize_3d(_ptr(src), _src_dt(src), d0, d1, d2, s0, s1, axis, fmt, rnd, 1 if keep_order else 0,
+                               _ptr(elems), _ptr(scales))
+    if st != 0:
+        raise ValueError("mxo_quantize_3d rejected its arguments")
     return elems, scales
 
 

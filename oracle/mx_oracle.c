@@ -410,6 +410,68 @@ int mxo_quantize_seeded(const void *src, int src_dt, int64_t rows, int64_t cols,
     return MXO_OK;
 }
 
+/* Section 3, "principal axis" of a multi-dimensional tensor: Algorithm 1 applied to every
+ * 1-D fibre of a 3-D tensor [d0][d1][d2] along `axis`, one block of 32 after the other.
+ * Element (i0, i1, i2) lives at src[i0*stride0 + i1*stride1 + i2].
+ * keep_order = 0: the block axis is moved last and the other two keep their order; with
+ *     (o1, o2) the two remaining indices in source order and L the block-axis length,
+ *     elems [o1][o2][ceil(L/32)*32*w/8], scales [o1][o2][ceil(L/32)]  (fill = code 0).
+ * keep_order = 1: codes stay in source order, densely packed along d2 (d2*w a multiple of 8):
+ *     elems [d0][d1][d2*w/8]; the scales array is the source shape with the block axis
+ *     replaced by its block count: [d0][d1][ceil(d2/32)], [d0][ceil(d1/32)][d2] or
+ *     [ceil(d0/32)][d1][d2]. */
+int mxo_quantize_3d(const void *src, int src_dt, int64_t d0, int64_t d1, int64_t d2,
+                    int64_t stride0, int64_t stride1, int axis, int fmt, int rnd,
+                    int keep_order, uint8_t *elems_out, uint8_t *scales_out)
+{
+    if (!src || !elems_out || !scales_out || !fmt_ok(fmt)) return MXO_ERR_ARG;
+    if (src_dt != MXO_DT_F32 && src_dt != MXO_DT_BF16) return MXO_ERR_ARG;
+    if (rnd < MXO_ROUND_RNE || rnd > MXO_ROUND_TOWARD_ZERO) return MXO_ERR_ARG;
+    if (d0 <= 0 || d1 <= 0 || d2 <= 0 || axis < 0 || axis > 2) return MXO_ERR_ARG;
+    int w = FMT[fmt].bits;
+    if (keep_order && (d2 * w) % 8) return MXO_ERR_ARG;
+    const int64_t dim[3] = {d0, d1, d2};
+    const int64_t L = dim[axis], nblk = (L + MXO_BLOCK - 1) / MXO_BLOCK;
+    /* the two axes that are not blocked, in source order */
+    const int a1 = axis == 0 ? 1 : 0, a2 = axis == 2 ? 1 : 2;
+    const int64_t n1 = dim[a1], n2 = dim[a2];
+    const int64_t line_bytes = nblk * MXO_BLOCK * w / 8, row_bytes = d2 * w / 8;
+
+    for (int64_t o1 = 0; o1 < n1; o1++)
+        for (int64_t o2 = 0; o2 < n2; o2++)
+            for (int64_t b = 0; b < nblk; b++) {
+                double v[MXO_BLOCK];
+                unsigned codes[MXO_BLOCK];
+                int64_t idx[3];
+                uint8_t sc;
+                idx[a1] = o1; idx[a2] = o2;
+                for (int i = 0; i < MXO_BLOCK; i++) {
+                    int64_t l = b * MXO_BLOCK + i;
+                    if (l >= L) { v[i] = 0.0; continue; }
+                    idx[axis] = l;
+                    v[i] = load_scalar(src, src_dt, idx[0] * stride0 + idx[1] * stride1 + idx[2]);
+                }
+                mxo_quantize_block(v, fmt, rnd, &sc, codes);
+                if (!keep_order) {
+                    uint8_t *line = elems_out + (o1 * n2 + o2) * line_bytes;
+                    for (int i = 0; i < MXO_BLOCK; i++) put_code(line, b * MXO_BLOCK + i, w, codes[i]);
+                    scales_out[(o1 * n2 + o2) * nblk + b] = sc;
+                } else {
+                    for (int i = 0; i < MXO_BLOCK; i++) {
+                        int64_t l = b * MXO_BLOCK + i;
+                        if (l >= L) break;
+                        idx[axis] = l;
+                        put_code(elems_out + (idx[0] * d1 + idx[1]) * row_bytes, idx[2], w, codes[i]);
+                    }
+                    /* the scale sits where the block sits: the block axis index is b */
+                    idx[axis] = b;
+                    int64_t sd1 = axis == 1 ? nblk : d1, sd2 = axis == 2 ? nblk : d2;
+                    scales_out[(idx[0] * sd1 + idx[1]) * sd2 + idx[2]] = sc;
+                }
+            }
+    return MXO_OK;
+}
+
 /* X * P as a double; X = NaN gives NaN (Section 2) */
 static double block_value(int fmt, unsigned code, uint8_t s)
 {

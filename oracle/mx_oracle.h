@@ -119,6 +119,17 @@ int mxo_quantize_seeded(const void *src, int src_dt, int64_t rows, int64_t cols,
                         int64_t ld, int axis, int fmt, int rnd, uint64_t seed,
                         uint8_t *elems_out, uint8_t *scales_out);
 
+/* Algorithm 1 along any axis of a 3-D tensor [d0][d1][d2] (Section 3: the principal axis
+ * of a multi-dimensional tensor); element (i0, i1, i2) at src[i0*stride0 + i1*stride1 + i2].
+ * keep_order = 0: block axis moved last, the other two axes keep their order:
+ *     elems [o1][o2][ceil(L/32)*32*bits/8], scales [o1][o2][ceil(L/32)].
+ * keep_order = 1: codes in source order packed along d2 (d2*bits a multiple of 8):
+ *     elems [d0][d1][d2*bits/8], scales = source shape with the block axis replaced by its
+ *     block count.  Rounding: not the stochastic mode. */
+int mxo_quantize_3d(const void *src, int src_dt, int64_t d0, int64_t d1, int64_t d2,
+                    int64_t stride0, int64_t stride1, int axis, int fmt, int rnd,
+                    int keep_order, uint8_t *elems_out, uint8_t *scales_out);
+
 /* Inverse: v = X * P (Section 2), X = NaN makes the whole block NaN, results
  * beyond Float32 range become +-Inf.  Writes row-major [rows, cols]; with a
  * block-axis length that is not a multiple of 32 the stored rows hold whole
