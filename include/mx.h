@@ -157,6 +157,38 @@ int mx_quantize_dual(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t c
                      void *elems_axis0, uint8_t *scales_axis0, void *hip_stream);
 
 /*
+ * Algorithm 1 along any axis of a 3-D tensor (Section 3: each tensor has a
+ * principal axis along which its blocks run; for a multi-dimensional tensor
+ * that can be any of its axes).  src holds [d0][d1][d2] with element (i0, i1,
+ * i2) at src + i0*stride0 + i1*stride1 + i2 (strides in elements, the last
+ * axis contiguous, stride1 >= d2, stride0 >= d1*stride1; src 16-byte aligned
+ * and both strides a multiple of 16 bytes) -- a batch of matrices, a slice of
+ * a larger tensor, or with d0 = 1 a plain matrix.  axis = 0, 1 or 2 names the
+ * block axis, of length L.  Two output layouts:
+ *   keep_order = 0  the block axis is moved last and the other two keep their
+ *       order, i.e. the 2-D cast of the permuted tensor: with (o1, o2) the two
+ *       remaining indices,  elems [o1][o2][ceil(L/32)*32*bits/8],
+ *       scales [o1][o2][ceil(L/32)].  Each [o1] slice is what mx_quantize writes
+ *       for the matching 2-D problem (axis = 2: rows of the slice; axis = 1:
+ *       its axis-0 cast), so a slice is a valid mx_gemm operand.
+ *   keep_order = 1  the untransposed form: codes stay at their element's place,
+ *       packed along the last axis (d2*bits must be a multiple of 8):
+ *       elems [d0][d1][d2*bits/8]; scales has the source's shape with the block
+ *       axis replaced by its block count: [d0][d1][ceil(d2/32)],
+ *       [d0][ceil(d1/32)][d2] or [ceil(d0/32)][d1][d2].  A partial last block
+ *       is cast as if filled up with zeros; nothing is stored for the fill.
+ * rnd: not MX_ROUND_STOCHASTIC.  Outputs 16-byte aligned device memory.
+ * keep_order = 0 with axis 1, or with axis 0 and stride1 != d2, issues one
+ * launch per slice (d0 or d1 of them); everything else is a single launch
+ * (MX_ERR_UNSUPPORTED beyond 65535 * 32 rows along the block axis with
+ * keep_order = 1).
+ */
+int mx_quantize_3d(const void *src, mx_dtype_t src_dt,
+                   int64_t d0, int64_t d1, int64_t d2, int64_t stride0, int64_t stride1,
+                   int axis, mx_format_t fmt, mx_round_t rnd, int keep_order,
+                   void *elems_out, uint8_t *scales_out, void *hip_stream);
+
+/*
  * v = X * P (Section 2) for an MX tensor produced by mx_quantize with the same
  * rows, cols and axis; writes row-major dst [rows, cols] with leading
  * dimension ld (elements).  Scale byte 0xFF gives NaN for the whole block;

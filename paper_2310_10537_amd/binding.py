@@ -51,6 +51,7 @@ def lib() -> ctypes.CDLL:
         L.mx_gemm_qa.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
         L.mx_gemm_q.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, ci, ci, vp, vp, vp]
         L.mx_gemm_qa_noalloc.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
+        L.mx_quantize_3d.argtypes = [vp, ci, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, vp, vp]
         L.mx_stream_pattern.argtypes = [vp, vp, i64, ci, ci, vp]
         L.mx_strerror.argtypes = [ci]
         L.mx_strerror.restype = ctypes.c_char_p
@@ -233,3 +234,29 @@ def mx_stream_pattern(src, dst, dst_bytes, read_per_write, write, stream=None):
     """Measurement aid: read read_per_write * dst_bytes from src, write dst_bytes to dst (if write)."""
     _check(lib().mx_stream_pattern(src.data_ptr() if src is not None else None, dst.data_ptr(), dst_bytes,
                                    read_per_write, 1 if write else 0, _stream(stream)))
+
+
+def mx_quantize_3d(src, axis, fmt, rnd=ROUND_RNE, keep_order=False, stream=None):
+    """src: 3-D device tensor (float32 / bfloat16), last dim contiguous, any strides on the first two.
+    Returns (elems, scales) in the layout mx_quantize_3d documents."""
+    _dev(src, "src")
+    assert src.dim() == 3 and (src.shape[2] == 0 or src.stride(2) == 1)
+    d0, d1, d2 = src.shape
+    s1 = src.stride(1) if d1 > 1 else d2
+    s0 = src.stride(0) if d0 > 1 else d1 * s1
+    w = FORMAT_BITS[fmt] if 0 <= fmt < 6 else 8
+    dim = (d0, d1, d2)
+    nblk = -(-dim[axis] // BLOCK) if 0 <= axis < 3 else 1
+    if keep_order:
+        elems = torch.empty((d0, d1, d2 * w // 8), dtype=torch.uint8, device=src.device)
+        sshape = list(dim)
+        if 0 <= axis < 3:
+            sshape[axis] = nblk
+        scales = torch.empty(sshape, dtype=torch.uint8, device=src.device)
+    else:
+        rest = [dim[i] for i in range(3) if i != axis][:2] if 0 <= axis < 3 else [d0, d1]
+        elems = torch.empty((rest[0], rest[1], nblk * BLOCK * w // 8), dtype=torch.uint8, device=src.device)
+        scales = torch.empty((rest[0], rest[1], nblk), dtype=torch.uint8, device=src.device)
+    _check(lib().mx_quantize_3d(src.data_ptr(), _dt(src), d0, d1, d2, s0, s1, axis, fmt, rnd, 1 if keep_order else 0,
+                                elems.data_ptr(), scales.data_ptr(), _stream(stream)))
+    return elems, scales

@@ -92,6 +92,21 @@ int mx_quantize_dual(const void *src, mx_dtype_t src_dt, int64_t rows, int64_t c
     return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
 }
 
+int mx_quantize_3d(const void *src, mx_dtype_t src_dt, int64_t d0, int64_t d1, int64_t d2, int64_t stride0, int64_t stride1,
+                   int axis, mx_format_t fmt, mx_round_t rnd, int keep_order, void *elems_out, uint8_t *scales_out, void *hip_stream)
+{
+    if (!fmt_ok(fmt) || !dt_ok(src_dt) || !rnd_ok(rnd) || axis < 0 || axis > 2 || (keep_order != 0 && keep_order != 1)) return MX_ERR_ENUM;
+    if (d0 < 0 || d1 < 0 || d2 < 0 || stride1 < d2 || stride0 < d1 * stride1) return MX_ERR_SHAPE;
+    if (keep_order && (d2 * mx::fmt_bits(fmt)) % 8) return MX_ERR_SHAPE;
+    if (d0 == 0 || d1 == 0 || d2 == 0) return MX_OK;
+    if (!src || !elems_out || !scales_out) return MX_ERR_NULL;
+    if (!aligned16(src) || !aligned16(elems_out) || !aligned16(scales_out) || (stride0 * esize(src_dt)) % 16 || (stride1 * esize(src_dt)) % 16)
+        return MX_ERR_ALIGN;
+    hipError_t e = mx::launch_cast_3d(src, src_dt, d0, d1, d2, stride0, stride1, axis, fmt, rnd, keep_order != 0,
+                                      static_cast<uint8_t *>(elems_out), scales_out, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MX_OK : e == hipErrorNotSupported ? MX_ERR_UNSUPPORTED : MX_ERR_LAUNCH;
+}
+
 int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt, int64_t rows, int64_t cols, int axis,
                   void *dst, mx_dtype_t dst_dt, int64_t ld, void *hip_stream)
 {

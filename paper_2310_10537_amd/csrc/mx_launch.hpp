@@ -11,6 +11,11 @@ namespace mx {
 hipError_t launch_cast(const void *src, int src_dt, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,
                        uint8_t *elems, uint8_t *scales, hipStream_t st, uint64_t seed = 0);
 
+// Algorithm 1 along axis 0, 1 or 2 of a 3-D tensor [d0][d1][d2] with element strides (stride0, stride1, 1);
+// keep_order = false: block axis moved last; true: codes in source order packed along d2
+hipError_t launch_cast_3d(const void *src, int src_dt, int64_t d0, int64_t d1, int64_t d2, int64_t stride0, int64_t stride1,
+                          int axis, int fmt, int rnd, bool keep_order, uint8_t *elems, uint8_t *scales, hipStream_t st);
+
 // bf16 sources and the two round-to-nearest modes only; hipErrorNotSupported when the shape is
 // outside what the fast kernels take
 hipError_t launch_cast_bf16_fast(const void *src, int64_t rows, int64_t cols, int64_t ld, int axis, int fmt, int rnd,

@@ -22,8 +22,8 @@ def L():
 def test_exports_match_header(L):
     text = open(os.path.join(ROOT, "include", "mx.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(mx_[a-z_]+)\s*\(", text))
-    assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_sr", "mx_quantize_dual", "mx_dequantize", "mx_gemm",
+    names = set(re.findall(r"\b(mx_[a-z0-9_]+)\s*\(", text))
+    assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_sr", "mx_quantize_dual", "mx_quantize_3d", "mx_dequantize", "mx_gemm",
                      "mx_gemm_qa", "mx_gemm_q", "mx_gemm_qa_noalloc", "mx_stream_pattern", "mx_strerror"}
     for n in names:
         assert hasattr(L, n), n
@@ -125,3 +125,18 @@ def test_noalloc_entry_point_validation(L):
     assert f(256, 256, 512, p, 512, 0, 3, p, p, 0, p, 0, 256, None) == 2                 # stochastic rounding
     assert f(0, 256, 512, None, 512, 0, 0, None, None, 0, None, 0, 256, None) == 0
     assert b"scratch" in L.mx_strerror(7)
+
+
+def test_quantize_3d_validation(L):
+    p = 0x1000
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    f = L.mx_quantize_3d
+    f.argtypes = [vp, ci, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, vp, vp]
+    assert f(p, 1, 2, 32, 64, 2048, 64, 3, 0, 0, 0, p, p, None) == 2        # axis
+    assert f(p, 1, 2, 32, 64, 2048, 64, 1, 0, 3, 0, p, p, None) == 2        # stochastic rounding
+    assert f(p, 1, 2, 32, 64, 2048, 32, 1, 0, 0, 0, p, p, None) == 3        # stride1 < d2
+    assert f(p, 1, 2, 32, 64, 1024, 64, 1, 0, 0, 0, p, p, None) == 3        # stride0 < d1 * stride1
+    assert f(p, 1, 2, 32, 6, 2048, 64, 1, 2, 0, 1, p, p, None) == 3         # 6 codes of 6 bits do not end on a byte
+    assert f(p, 1, 2, 32, 6, 2048, 64, 1, 2, 0, 0, None, p, None) == 1      # fine in the block-major layout
+    assert f(p, 1, 2, 32, 64, 4352, 68, 1, 0, 0, 0, p, p, None) == 4        # 68 bf16 = 136 bytes per row
+    assert f(None, 1, 0, 32, 64, 2048, 64, 1, 0, 0, 0, None, None, None) == 0
