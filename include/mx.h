@@ -14,12 +14,18 @@
  *
  * Conventions common to all entry points
  *   - Every tensor pointer is DEVICE memory owned by the caller; the library
- *     keeps no pointer after the call returns.  No entry point allocates,
- *     with one exception stated at mx_gemm_qa (a stream-ordered workspace).
+ *     keeps no pointer after the call returns.  The casts and mx_dequantize
+ *     never allocate.  Some GEMM routes need scratch memory: the plain entry
+ *     points take it from the memory pool in stream order, the _ws forms from
+ *     a caller-owned workspace (see "Scratch memory of the GEMM entry points").
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default
  *     stream).  Work is enqueued on it asynchronously; no call synchronises.
- *   - The return value is an mx_status_t.  On any value other than MX_OK
- *     nothing was launched and no output byte was written.
+ *   - The return value is an mx_status_t.  Argument errors (every status but
+ *     MX_ERR_LAUNCH and a pool refusal reported as MX_ERR_WORKSPACE) are found
+ *     before anything is launched: no output byte was written.  Calls that issue
+ *     several launches (a ragged GEMM = interior + fringe, cast + product) can
+ *     fail with MX_ERR_LAUNCH after earlier launches have written part of the
+ *     output.
  *   - A zero-sized problem (rows, cols, M or N equal to 0) is MX_OK and a no-op.
  *   - Block size is 32 and the scale format is E8M0 for every element format.
  *
@@ -79,7 +85,9 @@ typedef enum {
     MX_ERR_ALIGN = 4,       /* pointer or leading dimension not 16-byte aligned  */
     MX_ERR_UNSUPPORTED = 5, /* MX_INT8 paired with another format in a GEMM      */
     MX_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                */
-    MX_ERR_TOO_LARGE = 7    /* mx_gemm_qa_noalloc: the static scratch is too small */
+    MX_ERR_TOO_LARGE = 7,   /* mx_gemm_qa_noalloc: the static scratch is too small */
+    MX_ERR_WORKSPACE = 8    /* a GEMM route could not get its scratch memory: caller
+                               workspace too small, or the memory pool refused      */
 } mx_status_t;
 
 /* Size in bytes of the elems array for a [rows, cols] source cast along axis:
@@ -224,9 +232,9 @@ int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt,
  * else is MX_ERR_UNSUPPORTED).  That pair runs the integer matrix instruction
  * block by block -- every block sum is an exact integer -- and adds the scaled
  * block sums in Float32; problems of at least 96 whole 256 x 256 tiles (64 when
- * K < 1024) instead split every element exactly into two FP6 E2M3 halves (a workspace of
- * (M + N) * K * 3.125 bytes from the stream's memory pool, as described at
- * mx_gemm_qa) and run one E2M3 product of depth 4K, whose products are exact in
+ * K < 1024) instead split every element exactly into two FP6 E2M3 halves (scratch
+ * memory of (M + N) * K * 3.125 bytes, see "Scratch memory of the GEMM entry
+ * points" below) and run one E2M3 product of depth 4K, whose products are exact in
  * the block-scaled instruction; few rows (M <= 128, K >= 256) and mid-size
  * problems with a long K let eight waves share the K range of each 32-column
  * tile and add their partial tiles in a fixed order.  All routes differ from
@@ -246,22 +254,61 @@ int mx_gemm(int64_t M, int64_t N, int64_t K,
  * output tiles with FP8 / FP6 / FP4 formats and K a multiple of 128 (at least
  * 512) run the LDS-tiled kernel: with 8-bit formats, at most two tile columns
  * and at least 256 tiles the cast happens inside its K loop (one launch, no
- * workspace); otherwise A is first cast into a workspace of
- * M*K*(bits/8 + 1/32) bytes taken from and returned to the device's default
- * memory pool in stream order (hipMallocAsync / hipFreeAsync on hip_stream) --
- * the only kind of allocation the library makes (MX_INT8 takes the same route,
- * and large MX_INT8 products take a workspace of their own, see mx_gemm); if
- * the pool refuses, the fused kernel runs instead.  Problems that mx_gemm gives
- * to its kernel for few rows / few tiles / ragged shapes cast A into such a
- * workspace as well; what remains (K not a multiple of 128) casts in registers
+ * scratch); otherwise A is first cast into scratch memory of
+ * M*K*(bits/8 + 1/32) bytes (MX_INT8 takes the same route, and large MX_INT8
+ * products take scratch of their own, see mx_gemm).  Problems that mx_gemm
+ * gives to its kernel for few rows / few tiles / ragged shapes cast A into
+ * scratch as well; what remains (K not a multiple of 128) casts in registers
  * in the direct kernel.  The in-kernel casts round to nearest:
- * MX_ROUND_TOWARD_ZERO always casts into the workspace first (MX_ERR_LAUNCH if
- * the pool refuses); MX_ROUND_STOCHASTIC is MX_ERR_ENUM.
+ * MX_ROUND_TOWARD_ZERO always casts into scratch first; MX_ROUND_STOCHASTIC is
+ * MX_ERR_ENUM.  Where the scratch comes from, and what happens when there is
+ * none, is stated under "Scratch memory of the GEMM entry points" below.
  */
 int mx_gemm_qa(int64_t M, int64_t N, int64_t K,
                const void *A_bf16, int64_t lda, mx_format_t fmtA, mx_round_t rnd,
                const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB,
                void *C, mx_dtype_t c_dt, int64_t ldc, void *hip_stream);
+
+/*
+ * Scratch memory of the GEMM entry points.  Some routes need device scratch:
+ *   mx_gemm     MX_INT8 problems of at least 96 whole 256 x 256 tiles (the two
+ *               E2M3 halves of both operands);
+ *   mx_gemm_qa  every route that casts A ahead of the product (all but the
+ *               narrow-output fused kernel and the direct kernel);
+ *   mx_gemm_q   every route that does not cast in the tiled kernel's epilogue
+ *               (a Float32 C).
+ * mx_gemm / mx_gemm_qa / mx_gemm_q take it from the device's default memory
+ * pool in stream order (hipMallocAsync / hipFreeAsync on hip_stream).  The _ws
+ * forms below take it from the CALLER instead: `workspace` is device memory of
+ * at least mx_*_workspace_bytes(...) bytes (an upper bound over the routes the
+ * shape can take; 0 means the call never needs scratch), 16-byte aligned, owned
+ * by the caller, and in use until the call's work on hip_stream has finished.
+ * With a non-NULL workspace the library allocates nothing at all; a workspace
+ * smaller than the bound is MX_ERR_WORKSPACE and nothing is launched.
+ * workspace = NULL makes a _ws form behave exactly like the plain one.
+ * In either form a request that cannot be met is an error (MX_ERR_WORKSPACE);
+ * no route falls back to a slower kernel on its account.  Results are
+ * bit-identical between the two forms.
+ */
+size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, mx_format_t fmtA, mx_format_t fmtB);
+size_t mx_gemm_qa_workspace_bytes(int64_t M, int64_t N, int64_t K, mx_format_t fmtA, mx_format_t fmtB);
+size_t mx_gemm_q_workspace_bytes(int64_t M, int64_t N, int64_t K, mx_format_t fmtA, mx_format_t fmtB);
+int mx_gemm_ws(int64_t M, int64_t N, int64_t K,
+               const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
+               const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB,
+               void *C, mx_dtype_t c_dt, int64_t ldc,
+               void *workspace, size_t workspace_bytes, void *hip_stream);
+int mx_gemm_qa_ws(int64_t M, int64_t N, int64_t K,
+                  const void *A_bf16, int64_t lda, mx_format_t fmtA, mx_round_t rnd,
+                  const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB,
+                  void *C, mx_dtype_t c_dt, int64_t ldc,
+                  void *workspace, size_t workspace_bytes, void *hip_stream);
+int mx_gemm_q_ws(int64_t M, int64_t N, int64_t K,
+                 const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
+                 const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB,
+                 mx_format_t fmtC, mx_round_t rnd,
+                 void *C_elems, uint8_t *C_scales,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * mx_gemm_qa for callers that cannot allocate device memory: code under HIP graph
@@ -301,8 +348,8 @@ int mx_gemm_qa_noalloc(int64_t M, int64_t N, int64_t K,
  * operands, K a multiple of 128, at least 512) with a round-to-nearest mode
  * cast the accumulators in that kernel's epilogue, for every fmtC: C
  * never exists in memory at more than fmtC's width.  Everything else computes
- * C as Float32 into a workspace from the stream's memory pool (M*N*4 bytes,
- * see mx_gemm_qa) and casts it.  rnd: not MX_ROUND_STOCHASTIC.  Pointers 16-byte
+ * C as Float32 into scratch memory (M*N*4 bytes, see "Scratch memory of the GEMM
+ * entry points") and casts it.  rnd: not MX_ROUND_STOCHASTIC.  Pointers 16-byte
  * aligned, device memory, caller-owned; errors as mx_gemm.
  */
 int mx_gemm_q(int64_t M, int64_t N, int64_t K,

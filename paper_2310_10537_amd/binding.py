@@ -16,6 +16,7 @@ ROUND_RNE, ROUND_HALF_AWAY, ROUND_TOWARD_ZERO, ROUND_STOCHASTIC = 0, 1, 2, 3
 DT_F32, DT_BF16 = 0, 1
 MX_OK = 0
 MX_ERR_TOO_LARGE = 7
+MX_ERR_WORKSPACE = 8
 NOALLOC_SCRATCH_BYTES = 36 << 20
 BLOCK = 32
 
@@ -51,6 +52,13 @@ def lib() -> ctypes.CDLL:
         L.mx_gemm_qa.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
         L.mx_gemm_q.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, ci, ci, vp, vp, vp]
         L.mx_gemm_qa_noalloc.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp]
+        sz = ctypes.c_size_t
+        for name in ("mx_gemm_workspace_bytes", "mx_gemm_qa_workspace_bytes", "mx_gemm_q_workspace_bytes"):
+            getattr(L, name).argtypes = [i64, i64, i64, ci, ci]
+            getattr(L, name).restype = sz
+        L.mx_gemm_ws.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, ci, i64, vp, sz, vp]
+        L.mx_gemm_qa_ws.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp, sz, vp]
+        L.mx_gemm_q_ws.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, ci, ci, vp, vp, vp, sz, vp]
         L.mx_quantize_3d.argtypes = [vp, ci, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, vp, vp]
         L.mx_stream_pattern.argtypes = [vp, vp, i64, ci, ci, vp]
         L.mx_strerror.argtypes = [ci]
@@ -260,3 +268,54 @@ def mx_quantize_3d(src, axis, fmt, rnd=ROUND_RNE, keep_order=False, stream=None)
     _check(lib().mx_quantize_3d(src.data_ptr(), _dt(src), d0, d1, d2, s0, s1, axis, fmt, rnd, 1 if keep_order else 0,
                                 elems.data_ptr(), scales.data_ptr(), _stream(stream)))
     return elems, scales
+
+
+def _ws_args(workspace):
+    if workspace is None:
+        return None, 0
+    _dev(workspace, "workspace")
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def mx_gemm_ws(A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, K, workspace, dtype=torch.float32, out=None, stream=None):
+    """mx_gemm with the scratch memory (if the route needs any) taken from `workspace`, a device tensor of at
+    least mx_gemm_workspace_bytes(...) bytes."""
+    M, N = A_scales.shape[0], B_scales.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=dtype, device=A_elems.device)
+    ldc = out.stride(0) if M > 1 else N
+    wp, wb = _ws_args(workspace)
+    _check(lib().mx_gemm_ws(M, N, K, A_elems.data_ptr(), A_scales.data_ptr(), fmtA, B_elems.data_ptr(), B_scales.data_ptr(), fmtB,
+                            out.data_ptr(), _dt(out), ldc, wp, wb, _stream(stream)))
+    return out
+
+
+def mx_gemm_qa_ws(A_bf16, fmtA, rnd, B_elems, B_scales, fmtB, workspace, dtype=torch.float32, out=None, stream=None):
+    M, K = A_bf16.shape
+    N = B_scales.shape[0]
+    lda = A_bf16.stride(0) if M > 1 else K
+    if out is None:
+        out = torch.empty((M, N), dtype=dtype, device=A_bf16.device)
+    ldc = out.stride(0) if M > 1 else N
+    wp, wb = _ws_args(workspace)
+    _check(lib().mx_gemm_qa_ws(M, N, K, A_bf16.data_ptr(), lda, fmtA, rnd, B_elems.data_ptr(), B_scales.data_ptr(), fmtB,
+                               out.data_ptr(), _dt(out), ldc, wp, wb, _stream(stream)))
+    return out
+
+
+def mx_gemm_q_ws(A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, K, fmtC, rnd, workspace, out=None, stream=None):
+    M, N = A_scales.shape[0], B_scales.shape[0]
+    w = FORMAT_BITS[fmtC] if 0 <= fmtC < 6 else 8
+    nblk = -(-N // BLOCK)
+    if out is None:
+        out = (torch.empty((M, nblk * BLOCK * w // 8), dtype=torch.uint8, device=A_elems.device),
+               torch.empty((M, nblk), dtype=torch.uint8, device=A_elems.device))
+    wp, wb = _ws_args(workspace)
+    _check(lib().mx_gemm_q_ws(M, N, K, A_elems.data_ptr(), A_scales.data_ptr(), fmtA, B_elems.data_ptr(), B_scales.data_ptr(),
+                              fmtB, fmtC, rnd, out[0].data_ptr(), out[1].data_ptr(), wp, wb, _stream(stream)))
+    return out
+
+
+def mx_workspace_bytes(kind, M, N, K, fmtA, fmtB):
+    """kind: "gemm", "gemm_qa" or "gemm_q"."""
+    return getattr(lib(), f"mx_{kind}_workspace_bytes")(M, N, K, fmtA, fmtB)

@@ -29,6 +29,9 @@ int tensor_shape_status(int64_t rows, int64_t cols, int axis, int64_t ld, bool w
 
 int64_t blocks_of(int64_t len) { return (len + mx::BLOCK - 1) / mx::BLOCK; }
 
+// a GEMM route that could not get its scratch memory (caller workspace too small, or the pool refused)
+int gemm_status(hipError_t e) { return e == hipSuccess ? MX_OK : e == hipErrorOutOfMemory ? MX_ERR_WORKSPACE : MX_ERR_LAUNCH; }
+
 }  // namespace
 
 extern "C" {
@@ -122,7 +125,8 @@ int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt, int
 
 static int gemm_common(bool qa, int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_t *A_scales,
                        const void *A_bf16, int64_t lda, int rnd, mx_format_t fmtA, const void *B_elems, const uint8_t *B_scales,
-                       mx_format_t fmtB, void *C, mx_dtype_t c_dt, int64_t ldc, void *hip_stream)
+                       mx_format_t fmtB, void *C, mx_dtype_t c_dt, int64_t ldc, void *hip_stream, void *workspace = nullptr,
+                       size_t workspace_bytes = 0)
 {
     if (!fmt_ok(fmtA) || !fmt_ok(fmtB) || !dt_ok(c_dt)) return MX_ERR_ENUM;
     if (qa && !rnd_ok(rnd)) return MX_ERR_ENUM;
@@ -132,10 +136,47 @@ static int gemm_common(bool qa, int64_t M, int64_t N, int64_t K, const void *A_e
     if (!C || (K > 0 && ((qa ? !A_bf16 : (!A_elems || !A_scales)) || !B_elems || !B_scales))) return MX_ERR_NULL;
     if (!aligned16(B_elems) || !aligned16(B_scales) || !aligned16(C)) return MX_ERR_ALIGN;
     if (qa ? (!aligned16(A_bf16) || (lda * 2) % 16) : (!aligned16(A_elems) || !aligned16(A_scales))) return MX_ERR_ALIGN;
+    if (workspace) {
+        if (!aligned16(workspace)) return MX_ERR_ALIGN;
+        const size_t need = qa ? mx::gemm_qa_workspace_bound(M, N, K, fmtA, fmtB) : mx::gemm_workspace_bound(M, N, K, fmtA, fmtB);
+        if (workspace_bytes < need) return MX_ERR_WORKSPACE;
+    }
+    mx::WorkspaceScope scope(workspace, workspace_bytes);
     hipError_t e = mx::launch_gemm(M, N, K, static_cast<const uint8_t *>(A_elems), A_scales, qa ? A_bf16 : nullptr, lda, rnd, fmtA,
                                    static_cast<const uint8_t *>(B_elems), B_scales, fmtB, C, c_dt, ldc,
                                    static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+    return gemm_status(e);
+}
+
+size_t mx_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, mx_format_t fmtA, mx_format_t fmtB)
+{
+    return fmt_ok(fmtA) && fmt_ok(fmtB) ? mx::gemm_workspace_bound(M, N, K, fmtA, fmtB) : 0;
+}
+
+size_t mx_gemm_qa_workspace_bytes(int64_t M, int64_t N, int64_t K, mx_format_t fmtA, mx_format_t fmtB)
+{
+    return fmt_ok(fmtA) && fmt_ok(fmtB) ? mx::gemm_qa_workspace_bound(M, N, K, fmtA, fmtB) : 0;
+}
+
+size_t mx_gemm_q_workspace_bytes(int64_t M, int64_t N, int64_t K, mx_format_t fmtA, mx_format_t fmtB)
+{
+    return fmt_ok(fmtA) && fmt_ok(fmtB) ? mx::gemm_q_workspace_bound(M, N, K, fmtA, fmtB) : 0;
+}
+
+int mx_gemm_ws(int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
+               const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB, void *C, mx_dtype_t c_dt, int64_t ldc,
+               void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return gemm_common(false, M, N, K, A_elems, A_scales, nullptr, 0, MX_ROUND_RNE, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc,
+                       hip_stream, workspace, workspace_bytes);
+}
+
+int mx_gemm_qa_ws(int64_t M, int64_t N, int64_t K, const void *A_bf16, int64_t lda, mx_format_t fmtA, mx_round_t rnd,
+                  const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB, void *C, mx_dtype_t c_dt, int64_t ldc,
+                  void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return gemm_common(true, M, N, K, nullptr, nullptr, A_bf16, lda, rnd, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc,
+                       hip_stream, workspace, workspace_bytes);
 }
 
 int mx_gemm(int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
@@ -154,9 +195,9 @@ int mx_gemm_qa(int64_t M, int64_t N, int64_t K, const void *A_bf16, int64_t lda,
                        hip_stream);
 }
 
-int mx_gemm_q(int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
-              const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB, mx_format_t fmtC, mx_round_t rnd, void *C_elems,
-              uint8_t *C_scales, void *hip_stream)
+static int gemm_q_common(int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
+                         const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB, mx_format_t fmtC, mx_round_t rnd,
+                         void *C_elems, uint8_t *C_scales, void *hip_stream, void *workspace, size_t workspace_bytes)
 {
     if (!fmt_ok(fmtA) || !fmt_ok(fmtB) || !fmt_ok(fmtC) || !rnd_ok(rnd)) return MX_ERR_ENUM;
     if (M < 0 || N < 0 || K < 0 || K % mx::BLOCK) return MX_ERR_SHAPE;
@@ -166,10 +207,30 @@ int mx_gemm_q(int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_
     if (!aligned16(A_elems) || !aligned16(A_scales) || !aligned16(B_elems) || !aligned16(B_scales) || !aligned16(C_elems) ||
         !aligned16(C_scales))
         return MX_ERR_ALIGN;
+    if (workspace) {
+        if (!aligned16(workspace)) return MX_ERR_ALIGN;
+        if (workspace_bytes < mx::gemm_q_workspace_bound(M, N, K, fmtA, fmtB)) return MX_ERR_WORKSPACE;
+    }
+    mx::WorkspaceScope scope(workspace, workspace_bytes);
     hipError_t e = mx::launch_gemm_q(M, N, K, static_cast<const uint8_t *>(A_elems), A_scales, fmtA,
                                      static_cast<const uint8_t *>(B_elems), B_scales, fmtB, static_cast<uint8_t *>(C_elems),
                                      C_scales, fmtC, rnd, static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+    return gemm_status(e);
+}
+
+int mx_gemm_q(int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
+              const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB, mx_format_t fmtC, mx_round_t rnd, void *C_elems,
+              uint8_t *C_scales, void *hip_stream)
+{
+    return gemm_q_common(M, N, K, A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, fmtC, rnd, C_elems, C_scales, hip_stream, nullptr, 0);
+}
+
+int mx_gemm_q_ws(int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
+                 const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB, mx_format_t fmtC, mx_round_t rnd, void *C_elems,
+                 uint8_t *C_scales, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return gemm_q_common(M, N, K, A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, fmtC, rnd, C_elems, C_scales, hip_stream, workspace,
+                         workspace_bytes);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -239,6 +300,7 @@ const char *mx_strerror(int status)
         case MX_ERR_ALIGN: return "pointer or leading dimension not 16-byte aligned";
         case MX_ERR_UNSUPPORTED: return "the GEMM pairs MX_INT8 only with MX_INT8";
         case MX_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+        case MX_ERR_WORKSPACE: return "scratch memory: the caller's workspace is too small, or the memory pool refused the request";
         case MX_ERR_TOO_LARGE: return "the problem needs more scratch memory than the entry point's static buffer holds";
         default: return "unknown status";
     }

@@ -20,6 +20,66 @@
 namespace mx {
 
 // ---------------------------------------------------------------------------
+// Workspace of the routes that need scratch memory (see mx_launch.hpp)
+// ---------------------------------------------------------------------------
+namespace {
+struct WsState { uint8_t *base; size_t bytes, used; bool active; };
+thread_local WsState g_ws = {nullptr, 0, 0, false};
+size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
+}  // namespace
+
+WorkspaceScope::WorkspaceScope(void *p, size_t bytes) { g_ws = {static_cast<uint8_t *>(p), bytes, 0, p != nullptr}; }
+WorkspaceScope::~WorkspaceScope() { g_ws = {nullptr, 0, 0, false}; }
+
+hipError_t ws_acquire(size_t bytes, hipStream_t st, uint8_t **out)
+{
+    *out = nullptr;
+    if (g_ws.active) {
+        const size_t need = up256(bytes);
+        if (g_ws.used + need > g_ws.bytes) return hipErrorOutOfMemory;
+        *out = g_ws.base + g_ws.used;
+        g_ws.used += need;
+        return hipSuccess;
+    }
+    const hipError_t e = hipMallocAsync(reinterpret_cast<void **>(out), bytes, st);
+    if (e != hipSuccess) (void)hipGetLastError();
+    return e;
+}
+
+hipError_t ws_release(uint8_t *p, hipStream_t st)
+{
+    if (g_ws.active) {
+        g_ws.used = (size_t)(p - g_ws.base);     // pieces are released in reverse order of acquisition
+        return hipSuccess;
+    }
+    return hipFreeAsync(p, st);
+}
+
+static size_t cast_ws_bytes(int64_t M, int64_t K, int fmtA)
+{
+    const size_t bits = fmtA == FP4_E2M1 ? 4 : (fmtA == FP6_E3M2 || fmtA == FP6_E2M3) ? 6 : 8;
+    return up256((size_t)M * (size_t)K * bits / 8 + 16) + up256((size_t)M * (size_t)(K / BLOCK));
+}
+
+size_t gemm_workspace_bound(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB)
+{
+    if (fmtA != INT8 || fmtB != INT8 || M <= 0 || N <= 0 || K <= 0) return 0;
+    return up256(256 + (size_t)(M + N) * (size_t)(K / BLOCK) * 100);      // the two E2M3 halves of both operands + scales
+}
+
+size_t gemm_qa_workspace_bound(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    return cast_ws_bytes(M, K, fmtA) + gemm_workspace_bound(M, N, K, fmtA, fmtB);
+}
+
+size_t gemm_q_workspace_bound(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB)
+{
+    if (M <= 0 || N <= 0) return 0;
+    return up256((size_t)M * (size_t)((N + 3) & ~(int64_t)3) * sizeof(float)) + gemm_workspace_bound(M, N, K, fmtA, fmtB);
+}
+
+// ---------------------------------------------------------------------------
 // Direct kernel: operands go from global memory straight into MFMA registers.
 // Work-group = 4 waves, each wave one 32 x 32 output tile, K step 64.
 // Handles every shape (ragged M, N; K any multiple of 32).
@@ -115,12 +175,12 @@ static hipError_t launch_gemm_part(int64_t M, int64_t N, int64_t K, const uint8_
         const size_t eb = (size_t)M * (size_t)K, sb = eb / BLOCK;
         if (eb == 0) return launch_gemm_int8(M, N, K, nullptr, nullptr, B_elems, B_scales, C, c_dt, ldc, st);
         uint8_t *ws = nullptr;
-        hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), eb + sb + 16, st);
+        hipError_t e = ws_acquire(eb + sb + 16, st, &ws);
         if (e != hipSuccess) return e;
         uint8_t *wss = ws + ((eb + 15) & ~(size_t)15);
         e = launch_cast(a_bf16, DT_BF16, M, K, lda, 1, INT8, rnd, ws, wss, st);
         if (e == hipSuccess) e = launch_gemm_int8(M, N, K, ws, wss, B_elems, B_scales, C, c_dt, ldc, st);
-        const hipError_t f = hipFreeAsync(ws, st);
+        const hipError_t f = ws_release(ws, st);
         return e != hipSuccess ? e : f;
     }
     // Quantize-on-load casts A into a workspace first (the bytes mx_quantize writes).
@@ -129,15 +189,13 @@ static hipError_t launch_gemm_part(int64_t M, int64_t N, int64_t K, const uint8_
         const size_t bits = fmtA <= FP8_E5M2 ? 8 : fmtA <= FP6_E2M3 ? 6 : 4;
         const size_t eb = ((size_t)M * (size_t)K * bits / 8 + 15) & ~(size_t)15, sb = (size_t)M * (size_t)K / BLOCK;
         uint8_t *ws = nullptr;
-        hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), eb + sb, st);
-        if (e == hipSuccess) {
-            e = launch_cast(a_bf16, DT_BF16, M, K, lda, 1, fmtA, rnd, ws, ws + eb, st);
-            if (e == hipSuccess)
-                e = launch_gemm_skinny(M, N, K, ws, ws + eb, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
-            const hipError_t f = hipFreeAsync(ws, st);
-            return e != hipSuccess ? e : f;
-        }
-        (void)hipGetLastError();   // no workspace: the direct kernel casts in registers
+        hipError_t e = ws_acquire(eb + sb, st, &ws);
+        if (e != hipSuccess) return e;
+        e = launch_cast(a_bf16, DT_BF16, M, K, lda, 1, fmtA, rnd, ws, ws + eb, st);
+        if (e == hipSuccess)
+            e = launch_gemm_skinny(M, N, K, ws, ws + eb, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
+        const hipError_t f = ws_release(ws, st);
+        return e != hipSuccess ? e : f;
     }
     // Quantize-on-load on whole tiles.  The fused kernel casts each A tile once per column of
     // output tiles and reads it as bf16 that often, so it pays only for narrow outputs (measured:
@@ -149,15 +207,13 @@ static hipError_t launch_gemm_part(int64_t M, int64_t N, int64_t K, const uint8_
         const size_t bits = fmtA <= FP8_E5M2 ? 8 : fmtA <= FP6_E2M3 ? 6 : 4;
         const size_t eb = (size_t)M * (size_t)K * bits / 8, sb = (size_t)M * (size_t)K / BLOCK;
         uint8_t *ws = nullptr;
-        hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), eb + sb, st);
-        if (e == hipSuccess) {
-            e = launch_cast_bf16_fast(a_bf16, M, K, lda, 1, fmtA, rnd, ws, ws + eb, st);
-            if (e == hipSuccess)
-                e = launch_gemm_tiled(M, N, K, ws, ws + eb, nullptr, 0, rnd, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
-            const hipError_t f = hipFreeAsync(ws, st);
-            return e != hipSuccess ? e : f;
-        }
-        (void)hipGetLastError();   // no workspace: the kernels below need none
+        hipError_t e = ws_acquire(eb + sb, st, &ws);
+        if (e != hipSuccess) return e;
+        e = launch_cast_bf16_fast(a_bf16, M, K, lda, 1, fmtA, rnd, ws, ws + eb, st);
+        if (e == hipSuccess)
+            e = launch_gemm_tiled(M, N, K, ws, ws + eb, nullptr, 0, rnd, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
+        const hipError_t f = ws_release(ws, st);
+        return e != hipSuccess ? e : f;
     }
     {
         hipError_t e = launch_gemm_tiled(M, N, K, A_elems, A_scales, a_bf16, lda, rnd, fmtA, B_elems, B_scales, fmtB, C,
@@ -188,12 +244,12 @@ hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, 
         const size_t bits = fmtA == FP4_E2M1 ? 4 : (fmtA == FP6_E3M2 || fmtA == FP6_E2M3) ? 6 : 8;
         const size_t eb = ((size_t)M * (size_t)K * bits / 8 + 15) & ~(size_t)15, sb = (size_t)M * (size_t)K / BLOCK;
         uint8_t *ws = nullptr;
-        hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), eb + sb, st);
+        hipError_t e = ws_acquire(eb + sb, st, &ws);
         if (e != hipSuccess) return e;
         e = launch_cast(a_bf16, DT_BF16, M, K, lda, 1, fmtA, rnd, ws, ws + eb, st);
         if (e == hipSuccess)
             e = launch_gemm(M, N, K, ws, ws + eb, nullptr, 0, ROUND_RNE, fmtA, B_elems, B_scales, fmtB, C, c_dt, ldc, st);
-        const hipError_t f = hipFreeAsync(ws, st);
+        const hipError_t f = ws_release(ws, st);
         return e != hipSuccess ? e : f;
     }
     const int64_t M0 = M & ~(int64_t)255, N0 = N & ~(int64_t)255;
@@ -230,11 +286,13 @@ hipError_t launch_gemm_q(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, con
     }
     float *ws = nullptr;
     const int64_t ldw = (N + 3) & ~(int64_t)3;   // rows of the workspace stay 16-byte aligned
-    hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), (size_t)M * (size_t)ldw * sizeof(float), st);
+    uint8_t *ws8 = nullptr;
+    hipError_t e = ws_acquire((size_t)M * (size_t)ldw * sizeof(float), st, &ws8);
     if (e != hipSuccess) return e;
+    ws = reinterpret_cast<float *>(ws8);
     e = launch_gemm(M, N, K, Ae, As, nullptr, 0, ROUND_RNE, fmtA, Be, Bs, fmtB, ws, DT_F32, ldw, st);
     if (e == hipSuccess) e = launch_cast(ws, DT_F32, M, N, ldw, 1, fmtC, rndC, Ce, Cs, st);
-    const hipError_t f = hipFreeAsync(ws, st);
+    const hipError_t f = ws_release(ws8, st);
     return e != hipSuccess ? e : f;
 }
 

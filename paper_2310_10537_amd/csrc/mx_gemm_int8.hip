@@ -434,8 +434,9 @@ hipError_t launch_gemm_int8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, 
         const size_t nba = (size_t)M * (size_t)(K / BLOCK), nbb = (size_t)N * (size_t)(K / BLOCK);
         const size_t off_ea = 256, off_eb = off_ea + nba * 96, off_sa = off_eb + nbb * 96, off_sb = off_sa + nba * 4;
         uint8_t *ws = nullptr;
-        hipError_t e = hipMallocAsync(reinterpret_cast<void **>(&ws), off_sb + nbb * 4, st);
-        if (e == hipSuccess) {
+        hipError_t e = ws_acquire(off_sb + nbb * 4, st, &ws);
+        if (e != hipSuccess) return e;
+        {
             uint32_t *flag = reinterpret_cast<uint32_t *>(ws);
             hipLaunchKernelGGL(int8_clear_flag_kernel, dim3(1), dim3(1), 0, st, flag);
             e = hipGetLastError();
@@ -450,10 +451,9 @@ hipError_t launch_gemm_int8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, 
                 e = launch_gemm_tiled(M, N, 4 * K, ws + off_ea, ws + off_sa, nullptr, 0, ROUND_RNE, FP6_E2M3, ws + off_eb,
                                       ws + off_sb, FP6_E2M3, C, c_dt, ldc, st);
             if (e == hipSuccess) e = launch_int8_direct(M, N, K, Ae, As, Be, Bs, C, c_dt, ldc, flag, st);
-            const hipError_t f = hipFreeAsync(ws, st);
+            const hipError_t f = ws_release(ws, st);
             return e != hipSuccess ? e : f;
         }
-        (void)hipGetLastError();   // no workspace: the direct kernel needs none
     }
     if (M > 0 && N > 0 && K % 128 == 0 && (M <= 128 ? K >= 8 * BLOCK : K >= 1024) && (M + 63) / 64 <= 65535)
         return M <= 8    ? launch_int8_lds<1, 1>(M, N, K, Ae, As, Be, Bs, C, c_dt, ldc, st)

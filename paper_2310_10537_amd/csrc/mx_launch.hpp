@@ -32,6 +32,25 @@ hipError_t launch_cast_dual(const void *src, int src_dt, int64_t rows, int64_t c
 hipError_t launch_dequant(const uint8_t *elems, const uint8_t *scales, int fmt, int64_t rows, int64_t cols, int axis,
                           void *dst, int dst_dt, int64_t ld, hipStream_t st);
 
+// Scratch memory of the GEMM routes that need it (the MX form of a bf16 operand, the two E2M3 halves of
+// MXINT8 operands, a Float32 C that is cast afterwards).  Inside a WorkspaceScope -- opened by the
+// entry points that take a caller-owned workspace -- ws_acquire carves 256-byte aligned pieces off
+// that workspace (hipErrorOutOfMemory when it is too small); outside one it takes the piece from
+// the device's memory pool in stream order.  ws_release returns the piece (last acquired first).
+// A refused request is an error of the call; no route falls back to another kernel because of it.
+struct WorkspaceScope {
+    WorkspaceScope(void *p, size_t bytes);
+    ~WorkspaceScope();
+    WorkspaceScope(const WorkspaceScope &) = delete;
+    WorkspaceScope &operator=(const WorkspaceScope &) = delete;
+};
+hipError_t ws_acquire(size_t bytes, hipStream_t st, uint8_t **out);
+hipError_t ws_release(uint8_t *p, hipStream_t st);
+// upper bounds of what mx_gemm / mx_gemm_qa / mx_gemm_q can ask for (0: the call never needs scratch)
+size_t gemm_workspace_bound(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
+size_t gemm_qa_workspace_bound(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
+size_t gemm_q_workspace_bound(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB);
+
 // a_bf16 != nullptr selects the quantize-on-load form (A_elems / A_scales unused).
 hipError_t launch_gemm(int64_t M, int64_t N, int64_t K, const uint8_t *A_elems, const uint8_t *A_scales,
                        const void *a_bf16, int64_t lda, int rnd, int fmtA, const uint8_t *B_elems,

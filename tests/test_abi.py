@@ -24,7 +24,9 @@ def test_exports_match_header(L):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(mx_[a-z0-9_]+)\s*\(", text))
     assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_sr", "mx_quantize_dual", "mx_quantize_3d", "mx_dequantize", "mx_gemm",
-                     "mx_gemm_qa", "mx_gemm_q", "mx_gemm_qa_noalloc", "mx_stream_pattern", "mx_strerror"}
+                     "mx_gemm_qa", "mx_gemm_q", "mx_gemm_qa_noalloc", "mx_stream_pattern", "mx_strerror",
+                     "mx_gemm_workspace_bytes", "mx_gemm_qa_workspace_bytes", "mx_gemm_q_workspace_bytes", "mx_gemm_ws", "mx_gemm_qa_ws",
+                     "mx_gemm_q_ws"}
     for n in names:
         assert hasattr(L, n), n
 
@@ -140,3 +142,20 @@ def test_quantize_3d_validation(L):
     assert f(p, 1, 2, 32, 6, 2048, 64, 1, 2, 0, 0, None, p, None) == 1      # fine in the block-major layout
     assert f(p, 1, 2, 32, 64, 4352, 68, 1, 0, 0, 0, p, p, None) == 4        # 68 bf16 = 136 bytes per row
     assert f(None, 1, 0, 32, 64, 2048, 64, 1, 0, 0, 0, None, None, None) == 0
+
+
+def test_workspace_queries_and_validation(L):
+    from paper_2310_10537_amd import binding
+    wb = binding.mx_workspace_bytes
+    assert wb("gemm", 8192, 4096, 4096, 0, 0) == 0                       # FP8 operands never need scratch
+    assert wb("gemm", 8192, 4096, 4096, 5, 5) >= (8192 + 4096) * 128 * 100
+    assert wb("gemm_qa", 8192, 4096, 4096, 0, 0) >= 8192 * 4096 * (1 + 1 / 32)
+    assert wb("gemm_qa", 8192, 4096, 4096, 4, 0) < wb("gemm_qa", 8192, 4096, 4096, 0, 0)
+    assert wb("gemm_q", 300, 520, 640, 0, 3) >= 300 * 520 * 4
+    p = 0x1000
+    # a workspace below the bound is refused before anything is launched
+    assert L.mx_gemm_qa_ws(8192, 4096, 4096, p, 4096, 0, 0, p, p, 0, p, 1, 4096, p, 1024, None) == 8
+    assert L.mx_gemm_ws(8192, 4096, 4096, p, p, 5, p, p, 5, p, 1, 4096, p, 4096, None) == 8
+    assert L.mx_gemm_q_ws(300, 520, 640, p, p, 0, p, p, 3, 2, 0, p, p, p, 100, None) == 8
+    assert L.mx_gemm_qa_ws(8192, 4096, 4096, p, 4096, 0, 0, p, p, 0, p, 1, 4096, p + 8, 1 << 30, None) == 4
+    assert b"workspace" in L.mx_strerror(8)
