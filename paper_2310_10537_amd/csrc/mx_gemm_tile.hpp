@@ -53,6 +53,7 @@
 
 #include "mx_convert.hpp"
 #include "mx_gemm_frag.hpp"
+#include "mx_gemm_raster.hpp"
 #include "mx_launch.hpp"
 
 namespace mx {
@@ -169,7 +170,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
                                                             const uint16_t *__restrict__ Abf, int64_t lda,
                                                             const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
                                                             void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n,
-                                                            uint8_t *__restrict__ Cs, int fcr)
+                                                            uint8_t *__restrict__ Cs, int fcr, Raster rast)
 {
     static_assert(!(QA && CDT == DT_MX), "the MX epilogue is built for plain operands");
     constexpr int WA = Fmt<FA>::bits, WB = Fmt<FB>::bits;
@@ -191,29 +192,9 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     const int wm = wave >> 1, wn = wave & 1;
     const int li = lane & 31, g = lane >> 5;
 
-    // XCD-aware rasterisation.  Work-groups are dealt round-robin to the 8 XCDs, each with its
-    // own L2, and the first 32 an XCD receives run at the same time (one per compute unit), in
-    // step over K.  What that group misses in L2 per K step is one slab per distinct tile row
-    // plus one per distinct tile column, so it should be as square as possible: each XCD gets a
-    // band of M tiles and walks it in sub-bands of 4 tile rows, column by column (4 x 8 tiles at a
-    // time instead of 2 x 16: a third fewer L2 misses, measured with the fetch counters).
-    const int n_tiles = tiles_m * tiles_n;
-    const int per_xcd = (n_tiles + 7) >> 3;
-    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    if (idx >= per_xcd) return;
+    // XCD-aware order of the tiles (mx_gemm_raster.hpp)
     int tm, tn;
-    if ((tiles_m & 7) == 0) {
-        const int band = tiles_m >> 3;                       // tile rows per XCD
-        const int H = (band & 3) == 0 ? 4 : (band & 1) == 0 ? 2 : 1;
-        const int sub = idx / (H * tiles_n), r = idx - sub * (H * tiles_n);
-        tm = xcd * band + sub * H + r % H;
-        tn = r / H;
-    } else {
-        const int tile_id = xcd * per_xcd + idx;
-        if (tile_id >= n_tiles) return;
-        tm = tile_id / tiles_n;
-        tn = tile_id % tiles_n;
-    }
+    if (!raster_tile(rast, (int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     const int64_t m0 = (int64_t)tm * TM;
     const int64_t n0 = (int64_t)tn * TN;
     const int64_t nkb = K / BLOCK;
@@ -577,9 +558,9 @@ static hipError_t launch_t(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, c
 {
     auto kern = gemm_tile_kernel<FA, FB, CDT, QA, RND>;
     const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
-    const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, M, N, K, Ae, As, Abf, lda, Be, Bs, C, ldc,
-                       tiles_m, tiles_n, Cs, fcr);
+    const Raster rast = choose_raster(tiles_m, tiles_n, Fmt<FA>::bits, Fmt<FB>::bits);
+    hipLaunchKernelGGL(kern, dim3(raster_grid(rast, tiles_m, tiles_n)), dim3(256), 0, st, M, N, K, Ae, As, Abf, lda, Be, Bs, C, ldc,
+                       tiles_m, tiles_n, Cs, fcr, rast);
     return hipGetLastError();
 }
 

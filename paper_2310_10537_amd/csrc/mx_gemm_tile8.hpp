@@ -25,7 +25,7 @@ template <int FA, int FB, int CDT>
 __global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N, int64_t K,
                                                              const uint8_t *__restrict__ Ae, const uint8_t *__restrict__ As,
                                                              const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
-                                                             void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n)
+                                                             void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n, Raster rast)
 {
     static_assert(CDT == DT_F32 || CDT == DT_BF16, "plain output types only");
     constexpr int WA = Fmt<FA>::bits, WB = Fmt<FB>::bits;
@@ -40,24 +40,9 @@ __global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N
     const int wm = wave >> 2, wn = wave & 3;          // 128-row half, 64-column quarter
     const int li = lane & 31, g = lane >> 5;
 
-    // XCD-aware rasterisation, as in the four-wave kernel
-    const int n_tiles = tiles_m * tiles_n;
-    const int per_xcd = (n_tiles + 7) >> 3;
-    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    if (idx >= per_xcd) return;
+    // XCD-aware order of the tiles (mx_gemm_raster.hpp)
     int tm, tn;
-    if ((tiles_m & 7) == 0) {
-        const int band = tiles_m >> 3;
-        const int H = (band & 3) == 0 ? 4 : (band & 1) == 0 ? 2 : 1;
-        const int sub = idx / (H * tiles_n), r = idx - sub * (H * tiles_n);
-        tm = xcd * band + sub * H + r % H;
-        tn = r / H;
-    } else {
-        const int tile_id = xcd * per_xcd + idx;
-        if (tile_id >= n_tiles) return;
-        tm = tile_id / tiles_n;
-        tn = tile_id % tiles_n;
-    }
+    if (!raster_tile(rast, (int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     const int64_t m0 = (int64_t)tm * TM;
     const int64_t n0 = (int64_t)tn * TN;
     const int64_t nkb = K / BLOCK;
@@ -281,8 +266,9 @@ static hipError_t launch_t8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, 
 {
     auto kern = gemm_tile8_kernel<FA, FB, CDT>;
     const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
-    const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(512), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc, tiles_m, tiles_n);
+    const Raster rast = choose_raster(tiles_m, tiles_n, Fmt<FA>::bits, Fmt<FB>::bits);
+    hipLaunchKernelGGL(kern, dim3(raster_grid(rast, tiles_m, tiles_n)), dim3(512), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc, tiles_m, tiles_n,
+                       rast);
     return hipGetLastError();
 }
 
