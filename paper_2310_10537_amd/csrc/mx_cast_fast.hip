@@ -11,7 +11,7 @@
 //       region until each lane owns one block.  Scale bytes (and FP6 codes) are
 //       staged in LDS so that they leave as 16-byte stores.
 //   cast_col_bf16_kernel   blocks along dimension 0, output written as the cast of
-//       the transpose.  A work-group stages a [128 rows x 64 columns] tile in LDS
+//       the transpose.  A work-group stages a [128 rows x 128 (or 64) columns] tile in LDS
 //       with coalesced row loads (rows rotated by 32 bytes per 32-row block so
 //       that column reads are bank-conflict free); each lane then reads one
 //       column of one 32-row block -- the block maximum is in-lane -- and the four
@@ -167,14 +167,19 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
 // ---------------------------------------------------------------------------
 // Column cast
 // ---------------------------------------------------------------------------
-constexpr int COL_TILE_R = 128, COL_TILE_C = 64;   // rows a multiple of 128 (256 measured slower)
+constexpr int COL_TILE_R = 128;   // rows of a tile (256 measured slower)
+constexpr int COL_TILE_C = 64;    // columns of a tile of the Float32 kernel
 
-// Work-groups are dealt round-robin to the 8 XCDs, each with its own L2.  Tile
-// t = xcd * per_xcd + i, each XCD owning a contiguous run of column strips which
-// it walks down the rows, a few adjacent strips abreast: what its work-groups
-// write (128 bytes of codes and 4 scale bytes per column each) is consecutive in
-// memory and merges into full lines in that XCD's L2.
-template <int FMT, int RND>
+// A tile is 128 rows x TC columns, TC = 128 (256-byte row segments, two lines) or 64 for narrow
+// tensors.  Work-groups are dealt round-robin to the 8 XCDs, each with its own L2.  Tile
+// t = xcd * per_xcd + i, each XCD owning a contiguous run of column strips which it walks down
+// the rows: what its work-groups write (128 bytes of codes and 4 scale bytes per column each) is
+// consecutive in memory and merges into full lines in that XCD's L2.
+// (Measured on the bare access pattern -- loads, LDS tile, stores, no arithmetic -- of an
+// 8192 x 8192 tensor: 128 x 64 tiles 38.6 us, 256 x 64 37.2, 128 x 128 35.9, 256 x 128 40.5,
+// 64 x 256 37.8; walking several adjacent strips abreast, which paid before the loads became
+// non-temporal, now costs 1-2 us.  The kernel runs within 5 % of its pattern.)
+template <int FMT, int RND, int TC, bool WHOLE>   // WHOLE: every tile lies inside the tensor (no bounds checks)
 __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__restrict__ src, int64_t rows, int64_t cols,
                                                             int64_t ld, uint8_t *__restrict__ elems,
                                                             uint8_t *__restrict__ scales, int64_t row_tiles,
@@ -182,63 +187,60 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
 {
     if constexpr (FMT == FP8_E4M3 || FMT == FP8_E5M2) fp8_saturate_mode();
     constexpr int w = Fmt<FMT>::bits;
-    __shared__ __attribute__((aligned(16))) uint8_t tile[COL_TILE_R * COL_TILE_C * 2];   // 128-byte rows
+    constexpr int PITCH = TC * 2;                        // bytes per tile row in LDS
+    __shared__ __attribute__((aligned(16))) uint8_t tile[COL_TILE_R * PITCH];
     const int t = threadIdx.x;
     const int64_t tile_id = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int64_t)(blockIdx.x >> 3) >= per_xcd || tile_id >= n_tiles) return;   // uniform over the work-group
-    int64_t ct = tile_id / row_tiles, rt = tile_id % row_tiles;
-    {
-        // groups of up to 8 adjacent column strips are walked strips-fastest (measured best of
-        // 1 / 2 / 4 / 8 / 16): the XCD then reads up to 1 KB contiguous per source row at a time,
-        // and consecutive row tiles of a strip still follow each other within 8 tiles
-        const int64_t col_tiles = n_tiles / row_tiles;
-        const int64_t sg = (col_tiles & 7) == 0 ? 8 : (col_tiles & 3) == 0 ? 4 : (col_tiles & 1) == 0 ? 2 : 1;
-        const int64_t grp = tile_id / (sg * row_tiles), in = tile_id % (sg * row_tiles);
-        ct = grp * sg + in % sg;
-        rt = in / sg;
-    }
-    const int64_t c0 = ct * COL_TILE_C;
+    const int64_t ct = tile_id / row_tiles, rt = tile_id % row_tiles;
+    const int64_t c0 = ct * TC;
     const int64_t r0 = rt * COL_TILE_R;
 
-    // ---- coalesced loads: 8 lanes per 128-byte row segment, 32 rows per pass
-    const int lr = t >> 3, lc = t & 7;
-    const bool full_cols = c0 + COL_TILE_C <= cols;
+    // ---- coalesced loads: TC / 8 lanes per row segment, all in flight before the first LDS write
+    constexpr int LPR = TC / 8, RPP = 256 / LPR, NP = COL_TILE_R / RPP;
+    const int lr = t / LPR, lc = t % LPR;
+    const bool full_cols = WHOLE || c0 + TC <= cols;
+    uint4 v[NP];
 #pragma unroll
-    for (int p = 0; p < COL_TILE_R / 32; p++) {
-        const int r = p * 32 + lr;                       // row inside the tile; its 32-row block is p
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (r0 + r < rows) {
+    for (int p = 0; p < NP; p++) {
+        const int r = p * RPP + lr;                      // row inside the tile
+        v[p] = make_uint4(0, 0, 0, 0);
+        if (WHOLE || r0 + r < rows) {
             const uint16_t *g = src + (r0 + r) * ld + c0 + lc * 8;
             if (full_cols || c0 + lc * 8 + 8 <= cols) {
-                v = ld16_nt(g);
+                v[p] = ld16_nt(g);
             } else {
                 uint16_t h[8];
 #pragma unroll
                 for (int i = 0; i < 8; i++) h[i] = (c0 + lc * 8 + i < cols) ? g[i] : (uint16_t)0;
-                v = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+                v[p] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
             }
         }
+    }
+#pragma unroll
+    for (int p = 0; p < NP; p++) {
+        const int r = p * RPP + lr;
         // rotate the row by 32 bytes per row block: column reads of four adjacent blocks then hit different banks
-        *reinterpret_cast<uint4 *>(tile + r * 128 + ((lc * 16 + p * 32) & 127)) = v;
+        *reinterpret_cast<uint4 *>(tile + r * PITCH + ((lc * 16 + (r >> 5) * 32) & (PITCH - 1))) = v[p];
     }
     __syncthreads();
 
-    // ---- lane (column c, row block rb + 4q): 32 values down the column, packed in pairs
-    const int c = t >> 2;
-    const int64_t col = c0 + c;
+    // ---- lane (column c, row block rb): 32 values down the column, packed in pairs
     const int64_t n_rb = rows / BLOCK;
-    const bool quad = (n_rb & 3) == 0;                   // scale dwords are aligned
+    const bool quad = WHOLE || (n_rb & 3) == 0;          // scale dwords are aligned
 #pragma unroll
-    for (int q = 0; q < COL_TILE_R / 128; q++) {
-        const int rb = (t & 3) + 4 * q;
+    for (int q = 0; q < TC / 64; q++) {
+        const int c = (t >> 2) + 64 * q;
+        const int64_t col = c0 + c;
+        const int rb = t & 3;
         const int64_t row_blk = r0 / BLOCK + rb;
-        const bool valid = col < cols && row_blk < n_rb;
-        const uint8_t *colp = tile + rb * 32 * 128 + ((c * 2 + rb * 32) & 127);
+        const bool valid = WHOLE || (col < cols && row_blk < n_rb);
+        const uint8_t *colp = tile + rb * 32 * PITCH + ((c * 2 + rb * 32) & (PITCH - 1));
         uint32_t d[16];
 #pragma unroll
         for (int i = 0; i < 16; i++) {
-            uint32_t lo = *reinterpret_cast<const uint16_t *>(colp + (2 * i) * 128);
-            uint32_t hi = *reinterpret_cast<const uint16_t *>(colp + (2 * i + 1) * 128);
+            uint32_t lo = *reinterpret_cast<const uint16_t *>(colp + (2 * i) * PITCH);
+            uint32_t hi = *reinterpret_cast<const uint16_t *>(colp + (2 * i + 1) * PITCH);
             d[i] = lo | (hi << 16);
         }
         uint32_t out[w];
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
             } else {
                 st16(o, make_uint4(out[0], out[1], out[2], out[3]));
             }
-            if (quad && r0 / BLOCK + 4 * q + 4 <= n_rb) {   // uniform over the work-group
+            if (WHOLE || (quad && r0 / BLOCK + 4 <= n_rb)) {   // uniform over the work-group
                 if ((t & 3) == 0) *reinterpret_cast<uint32_t *>(scales + col * n_rb + row_blk) = s4;
             } else {
                 scales[col * n_rb + row_blk] = (uint8_t)s;
@@ -384,11 +386,18 @@ static hipError_t launch_fast_t(const void *src, int64_t rows, int64_t cols, int
         return hipGetLastError();
     }
     const int64_t row_tiles = (rows + COL_TILE_R - 1) / COL_TILE_R;
-    const int64_t n_tiles = row_tiles * ((cols + COL_TILE_C - 1) / COL_TILE_C);
+    // 128-column tiles once they still give every compute unit several work-groups
+    const bool wide = row_tiles * ((cols + 127) / 128) >= 1024;
+    const int64_t n_tiles = row_tiles * (wide ? (cols + 127) / 128 : (cols + 63) / 64);
     const int64_t per_xcd = (n_tiles + 7) / 8;
     if (per_xcd * 8 > 0x7FFFFFFF) return hipErrorNotSupported;
-    hipLaunchKernelGGL((cast_col_bf16_kernel<FMT, RND>), dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, s16, rows, cols,
-                       ld, elems, scales, row_tiles, n_tiles, per_xcd);
+    const bool whole = rows % COL_TILE_R == 0 && cols % (wide ? 128 : 64) == 0;
+#define MX_COL_GO(TC_, WHOLE_)                                                                                               \
+    hipLaunchKernelGGL((cast_col_bf16_kernel<FMT, RND, TC_, WHOLE_>), dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, s16, rows, cols, \
+                       ld, elems, scales, row_tiles, n_tiles, per_xcd)
+    if (wide) { if (whole) MX_COL_GO(128, true); else MX_COL_GO(128, false); }
+    else      { if (whole) MX_COL_GO(64, true); else MX_COL_GO(64, false); }
+#undef MX_COL_GO
     return hipGetLastError();
 }
 

@@ -215,6 +215,24 @@ def test_full_size_config2_sampled(mx, oracle):
             # whole-tensor property: no NaN scale and every scale within the data's exponent range
             assert int(s.max()) < 255
 
+@pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
+@pytest.mark.parametrize("shape", [(384, 192), (4128, 4104), (4096, 4096)], ids=["whole_64", "ragged_128", "whole_128"])
+def test_cast_axis0_bf16_tile_variants(mx, oracle, fmt, shape):
+    """The axis-0 kernel for bf16 sources has four forms: 64- or 128-column tiles, with or without bounds
+    checks (every tile inside the tensor).  One shape per form not covered elsewhere; the reference is
+    evaluated on a sample of columns that includes the first and the last."""
+    x = inputs.student_t_bf16(shape, seed=40 + fmt)
+    rnd = AWAY if fmt in (1, 3) else RNE
+    e, s = mx.mx_quantize(to_dev(x), 0, fmt, rnd)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(6)
+    pick = np.sort(rng.choice(shape[1], min(shape[1], 160), replace=False))
+    pick[0], pick[-1] = 0, shape[1] - 1
+    e_ref, s_ref = oracle.quantize(np.ascontiguousarray(x[:, pick]), 0, fmt, rnd)
+    pk = torch.from_numpy(pick).cuda()
+    assert np.array_equal(to_host(s[pk]), s_ref), (fmt, shape)
+    assert np.array_equal(to_host(e[pk]), e_ref), (fmt, shape)
+
 
 @pytest.mark.parametrize("fmt", range(6), ids=NAMES)
 @pytest.mark.parametrize("rnd", [RNE, AWAY], ids=["rne", "away"])
