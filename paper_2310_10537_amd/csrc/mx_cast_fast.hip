@@ -47,7 +47,7 @@ __device__ __forceinline__ int64_t src_offset(int64_t e, int64_t cols, int64_t l
     return r * ld + (e - r * cols);
 }
 
-template <int FMT, int RND, bool FLAT>
+template <int FMT, int RND, bool FLAT, bool WHOLE = false>   // WHOLE: every wave's 2048 elements lie inside the tensor
 __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__restrict__ src, int64_t cols, int64_t ld,
                                                             uint8_t *__restrict__ elems, uint8_t *__restrict__ scales,
                                                             int64_t n_elems)
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
 
     const int64_t wave_id = (int64_t)blockIdx.x * 4 + wave;
     const int64_t e0 = wave_id * ROW_WAVE_ELEMS;          // first element of this wave
-    if (e0 >= n_elems) return;                            // whole wave out of range
+    if (!WHOLE && e0 >= n_elems) return;                  // whole wave out of range
     const int64_t blk0 = e0 / BLOCK;                      // first block of this wave
 
     // ---- coalesced loads: chunk u, lane l -> elements e0 + u*512 + l*8 .. +7
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
 #pragma unroll
     for (int u = 0; u < ROW_CHUNKS; u++) {
         const int64_t e = e0 + u * 512 + lane * 8;
-        valid[u] = e < n_elems;
+        valid[u] = WHOLE || e < n_elems;
         uint4 t = make_uint4(0, 0, 0, 0);
         if (valid[u]) t = ld16_nt(src + src_offset<FLAT>(e, cols, ld));
         d[u][0] = t.x; d[u][1] = t.y; d[u][2] = t.z; d[u][3] = t.w;
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
         for (int i = 0; i < 6; i++) l32[lane * 6 + i] = out[i];
         lds[1536 + lane] = (uint8_t)s;
         wave_lds_sync();
-        const int64_t n_blk_valid = (n_elems - e0) / BLOCK;   // blocks of this wave inside the tensor (>= 1)
+        const int64_t n_blk_valid = WHOLE ? 64 : (n_elems - e0) / BLOCK;   // blocks of this wave inside the tensor (>= 1)
         uint8_t *o = elems + blk0 * 24;
         const uint4 a = *reinterpret_cast<const uint4 *>(lds + lane * 16);
         const uint2 c = *reinterpret_cast<const uint2 *>(lds + 1024 + lane * 8);
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
     wave_lds_sync();
     {
         const uint8_t *sl = SIX ? lds + 1536 : lds;
-        const int64_t n_blk_valid = (n_elems - e0) / BLOCK;
+        const int64_t n_blk_valid = WHOLE ? 64 : (n_elems - e0) / BLOCK;
         if (lane < 4) {
             if ((lane + 1) * 16 <= n_blk_valid) {
                 st16(scales + blk0 + lane * 16, *reinterpret_cast<const uint4 *>(sl + lane * 16));
@@ -189,6 +189,7 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
     constexpr int w = Fmt<FMT>::bits;
     constexpr int PITCH = TC * 2;                        // bytes per tile row in LDS
     __shared__ __attribute__((aligned(16))) uint8_t tile[COL_TILE_R * PITCH];
+    __shared__ __attribute__((aligned(16))) uint32_t xch[(w == 6 && WHOLE) ? 256 * 6 : 4];   // FP6 codes on their way out
     const int t = threadIdx.x;
     const int64_t tile_id = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int64_t)(blockIdx.x >> 3) >= per_xcd || tile_id >= n_tiles) return;   // uniform over the work-group
@@ -258,9 +259,22 @@ __global__ __launch_bounds__(256) void cast_col_bf16_kernel(const uint16_t *__re
                 st16(o, make_uint4(out[0], out[1], out[2], out[3]));
                 st16(o + 16, make_uint4(out[4], out[5], out[6], out[7]));
             } else if constexpr (w == 6) {
-                *reinterpret_cast<uint2 *>(o) = make_uint2(out[0], out[1]);
-                *reinterpret_cast<uint2 *>(o + 8) = make_uint2(out[2], out[3]);
-                *reinterpret_cast<uint2 *>(o + 16) = make_uint2(out[4], out[5]);
+                if constexpr (WHOLE) {
+                    // the four lanes of a column hold 96 consecutive output bytes (16-byte aligned: whole
+                    // tiles are four blocks deep); through LDS they leave as six 16-byte stores
+                    uint32_t *x = xch + (t & ~3) * 6;
+#pragma unroll
+                    for (int i = 0; i < 6; i += 2) *reinterpret_cast<uint2 *>(x + (t & 3) * 6 + i) = make_uint2(out[i], out[i + 1]);
+                    wave_lds_sync();
+                    uint8_t *oq = o - (t & 3) * 24;
+                    st16(oq + (t & 3) * 16, *reinterpret_cast<const uint4 *>(x + (t & 3) * 4));
+                    if ((t & 3) < 2) st16(oq + 64 + (t & 3) * 16, *reinterpret_cast<const uint4 *>(x + 16 + (t & 3) * 4));
+                    if (q + 1 < TC / 64) wave_lds_sync();   // the exchange area is written again
+                } else {
+                    *reinterpret_cast<uint2 *>(o) = make_uint2(out[0], out[1]);
+                    *reinterpret_cast<uint2 *>(o + 8) = make_uint2(out[2], out[3]);
+                    *reinterpret_cast<uint2 *>(o + 16) = make_uint2(out[4], out[5]);
+                }
             } else {
                 st16(o, make_uint4(out[0], out[1], out[2], out[3]));
             }
@@ -377,7 +391,10 @@ static hipError_t launch_fast_t(const void *src, int64_t rows, int64_t cols, int
         const int64_t waves = (n + ROW_WAVE_ELEMS - 1) / ROW_WAVE_ELEMS;
         const int64_t nb = (waves + 3) / 4;
         if (nb > 0x7FFFFFFF) return hipErrorNotSupported;
-        if (ld == cols)
+        if (ld == cols && n % (4 * ROW_WAVE_ELEMS) == 0)
+            hipLaunchKernelGGL((cast_row_bf16_kernel<FMT, RND, true, true>), dim3((unsigned)nb), dim3(256), 0, st, s16, cols, ld,
+                               elems, scales, n);
+        else if (ld == cols)
             hipLaunchKernelGGL((cast_row_bf16_kernel<FMT, RND, true>), dim3((unsigned)nb), dim3(256), 0, st, s16, cols, ld,
                                elems, scales, n);
         else
