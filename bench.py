@@ -29,6 +29,8 @@ Also in the default run, per call and with the same protocol:
                    triple of config 5 (six casts, three GEMMs, the dual-axis casts), and config 1
                    in microseconds -- every GEMM with its fraction of the matrix peak, every cast
                    with its fraction of the HBM peak;
+  "gemm_clock"     the shader clock during the headline GEMM and the clocks one K step takes, from
+                   counters read inside the kernel (mx_gemm_probe), on the real operands and on zeros;
   "gemm_zero_operands"  the headline GEMM launch on all-zero operands: what the same kernel
                    does when operand switching activity does not hold the clock down;
   "gemm_max_rel_err"    (with the CPU baseline leg) max |dC| / sum |a||b| of sampled entries
@@ -63,35 +65,53 @@ FORMAT_INDEX = {"fp8_e4m3": 0, "fp8_e5m2": 1, "fp6_e3m2": 2, "fp6_e2m3": 3, "fp4
 
 
 def measured_traffic():
-    """HBM bytes per launch (read + write) of this file's kernels, from the committed hardware
+    """HBM bytes per launch (read + write) of this file's headline kernels, from the committed hardware
     counter summary (FETCH_SIZE / WRITE_SIZE scaled by a copy of known size; the file names its
-    commands).  label -> bytes; empty when the summary is missing or a kernel is not in it."""
-    out = {}
+    commands).  One kernel serves several workloads, so the summary has a row per kernel and grid
+    size; for each label the row of its kernel nearest to the label's algorithmic bytes is taken.
+    label -> bytes; empty when the summary is missing or a kernel is not in it."""
+    rows = []
     try:
         lines = open(TRAFFIC_SUMMARY).read().splitlines()
     except OSError:
-        return out
+        return {}
     for ln in lines:
         f = ln.split()
-        if len(f) < 8 or not f[0].isdigit():
+        if len(f) < 7 or not f[0].isdigit():
             continue
         try:
-            rd, wr = float(f[3]), float(f[4])
+            rows.append((" ".join(f[6:]), (float(f[3]) + float(f[4])) * 2 ** 20))
         except ValueError:
             continue
-        kern = " ".join(f[7:])
-        label = None
-        for kname, axis in (("cast_row_bf16_kernel<", 1), ("cast_col_bf16_kernel<", 0)):
-            if kern.startswith(kname):
-                fmt = int(kern[len(kname):].split(",")[0])
-                label = f"cast_{mx.FORMAT_NAMES[fmt]}_axis{axis}"
-        if kern.startswith("dequant_kernel"):
-            label = "dequantize_fp8_e4m3_bf16"
-        if kern.startswith("gemm_tile_kernel<0, 0, 1, false"):
-            label = "gemm_fp8_e4m3"
-        if label and label not in out and label != "cast_fp8_e4m3_axis1":   # (that kernel also serves the 8192 x 4096 cast of mx_gemm_qa)
-            out[label] = int((rd + wr) * 2 ** 20)
+    n_elem = ROWS * COLS
+    want = {"dequantize_fp8_e4m3_bf16": ("dequant_flat_kernel<0, 1>", n_elem * (1.0 + 1.0 / 32.0 + 2.0)),
+            "gemm_fp8_e4m3": ("gemm_tile_kernel<0, 0, 1, false", (GM + GN) * GK * (1.0 + 1.0 / 32.0) + GM * GN * 2.0)}
+    for fmt in range(6):
+        for kname, axis in (("cast_row_bf16_kernel<%d, 0," % fmt, 1), ("cast_col_bf16_kernel<%d, 0," % fmt, 0)):
+            want[f"cast_{mx.FORMAT_NAMES[fmt]}_axis{axis}"] = (kname, cast_bytes(fmt, n_elem))
+    out = {}
+    for label, (kname, algo) in want.items():
+        cand = [b for k, b in rows if k.startswith(kname)]
+        if cand:
+            best = min(cand, key=lambda b: abs(b - algo))
+            if 0.5 * algo <= best <= 4.0 * algo:      # a row of another workload is no measurement of this one
+                out[label] = int(best)
     return out
+
+
+def clock_probe(A, fmtA, B, fmtB, K, C, mfma_clocks_per_step, n=6):
+    """Shader clock under the tiled GEMM's load and clocks per K step, from the kernel's own counters
+    (mx_gemm_probe: per work-group, shader clocks and 100 MHz ticks from start to the end of the K loop).
+    n launches back to back so that the clock has settled; the last one is read."""
+    for _ in range(n):
+        clk, ticks = mx.mx_gemm_probe(A[0], A[1], fmtA, B[0], B[1], fmtB, K, C)
+    torch.cuda.synchronize()
+    clk, ticks = clk.double(), ticks.double()
+    steps = K // 128
+    per_step = float(clk.mean()) / steps
+    return {"shader_GHz": round(float(clk.sum() / ticks.sum()) * 0.1, 3), "clocks_per_k_step": round(per_step, 0),
+            "mfma_clocks_per_k_step": mfma_clocks_per_step,
+            "k_loop_us_per_tile": round(float(ticks.mean()) / 100.0, 2)}
 
 
 def cast_bytes(fmt, n_elem):
@@ -297,6 +317,7 @@ def other_configs(n, samples, extras):
     C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     gemm_entry("cfg4_gemm_4096x28672x8192_e3m2_e2m1", M, N, K,
                time_call(lambda: mx.mx_gemm(ga[0], ga[1], mx.FP6_E3M2, gb[0], gb[1], mx.FP4_E2M1, K, out=C), n), 6)
+    out["cfg4_gemm_4096x28672x8192_e3m2_e2m1"]["clock"] = clock_probe(ga, mx.FP6_E3M2, gb, mx.FP4_E2M1, K, C, 1024, n=3)
     del C
     accuracy_sample(samples, "cfg4_4096x28672x8192_e3m2_e2m1", ga, 2, gb, 4, K, seed=24)
     del act, ga, gb
@@ -327,6 +348,7 @@ def other_configs(n, samples, extras):
         C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
         ms = time_call(lambda: mx.mx_gemm(A[0], A[1], fmt, B[0], B[1], fmt, K, out=C), n)
         gemm_entry(f"cfg5_gemm_{name}_{M}x{N}x{K}_e3m2", M, N, K, ms, 6)
+        out[f"cfg5_gemm_{name}_{M}x{N}x{K}_e3m2"]["clock"] = clock_probe(A, fmt, B, fmt, K, C, 1024, n=3)
         total += ms
         del C
         accuracy_sample(samples, f"cfg5_{name}_{M}x{N}x{K}_e3m2", A, fmt, B, fmt, K, seed=25, n=256)
@@ -453,6 +475,8 @@ def main():
         i = nxt()
         mx.mx_gemm(zA[i % NCOPY][0], zA[i % NCOPY][1], mx.FP8_E4M3, zB[0], zB[1], mx.FP8_E4M3, GK, out=Cs[i % NCOPY])
     zero_ms = time_call(gemm_zero_call, args.steps)
+    gemm_clock = {"real_operands": clock_probe(Aq[0], mx.FP8_E4M3, (Be, Bs), mx.FP8_E4M3, GK, Cs[0], 2048),
+                  "zero_operands": clock_probe(zA[0], mx.FP8_E4M3, zB, mx.FP8_E4M3, GK, Cs[0], 2048)}
     del zA, zB
 
     n_elem = ROWS * COLS
@@ -525,6 +549,7 @@ def main():
         "ceilings": ceil,
         "gemm_zero_operands": {"avg_ms": round(zero_ms, 5), "TFLOPs": round(flop / zero_ms / 1e9, 1),
                                "frac_mfma_peak": round(flop / zero_ms / 1e9 / MFMA_PEAK_TFLOPS[8], 4)},
+        "gemm_clock": gemm_clock,
         "kernels": per_kernel,
     }
     del xs, As, Aq, Cs, outs, deq_out, deq_in, Be, Bs

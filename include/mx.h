@@ -371,6 +371,25 @@ int mx_gemm_q(int64_t M, int64_t N, int64_t K,
 int mx_stream_pattern(const void *src, void *dst, int64_t dst_bytes,
                       int read_per_write, int write, void *hip_stream);
 
+/*
+ * Measurement aid (no part of the MX path): mx_gemm's LDS-tiled kernel for one of
+ * three format pairs -- E4M3 x E4M3, E3M2 x E3M2, E3M2 x E2M1 (anything else is
+ * MX_ERR_UNSUPPORTED) -- with bf16 output, which also has every work-group
+ * record how long it ran from its start to the end of its K loop: shader clocks
+ * at probe[2*g] and ticks of the constant 100 MHz counter at probe[2*g + 1], g
+ * the work-group's index in launch order.  From the two a benchmark gets the
+ * shader clock under this load and the clocks per K step.  M and N are
+ * multiples of 256, K a multiple of 128 and at least 512 (else MX_ERR_SHAPE);
+ * probe holds probe_len >= 2 * (tiles rounded up to a multiple of 8) entries of
+ * device memory, which the caller clears first (work-groups without a tile write
+ * nothing).  C receives the same bytes as from mx_gemm.
+ */
+int mx_gemm_probe(int64_t M, int64_t N, int64_t K,
+                  const void *A_elems, const uint8_t *A_scales, mx_format_t fmtA,
+                  const void *B_elems, const uint8_t *B_scales, mx_format_t fmtB,
+                  void *C_bf16, int64_t ldc,
+                  uint64_t *probe, int64_t probe_len, void *hip_stream);
+
 /* Static, human-readable text for a status code. */
 const char *mx_strerror(int status);
 

@@ -61,6 +61,7 @@ def lib() -> ctypes.CDLL:
         L.mx_gemm_q_ws.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, ci, ci, vp, vp, vp, sz, vp]
         L.mx_quantize_3d.argtypes = [vp, ci, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, vp, vp]
         L.mx_stream_pattern.argtypes = [vp, vp, i64, ci, ci, vp]
+        L.mx_gemm_probe.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, i64, vp, i64, vp]
         L.mx_strerror.argtypes = [ci]
         L.mx_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -319,3 +320,15 @@ def mx_gemm_q_ws(A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, K, fmtC, rnd,
 def mx_workspace_bytes(kind, M, N, K, fmtA, fmtB):
     """kind: "gemm", "gemm_qa" or "gemm_q"."""
     return getattr(lib(), f"mx_{kind}_workspace_bytes")(M, N, K, fmtA, fmtB)
+
+
+def mx_gemm_probe(A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, K, out, stream=None):
+    """Measurement aid: the tiled GEMM with per-work-group timing.  Returns (shader clocks, 100 MHz ticks)
+    of the work-groups' K loops as two int64 tensors (work-groups that had a tile only)."""
+    M, N = A_scales.shape[0], B_scales.shape[0]
+    wgs = (-(-((M // 256) * (N // 256)) // 8)) * 8
+    probe = torch.zeros((wgs, 2), dtype=torch.int64, device=A_elems.device)
+    _check(lib().mx_gemm_probe(M, N, K, A_elems.data_ptr(), A_scales.data_ptr(), fmtA, B_elems.data_ptr(), B_scales.data_ptr(), fmtB,
+                               out.data_ptr(), out.stride(0), probe.data_ptr(), probe.numel(), _stream(stream)))
+    ran = probe[:, 1] > 0
+    return probe[ran, 0], probe[ran, 1]

@@ -164,14 +164,21 @@ __device__ __forceinline__ uint32_t quantize_store_block_rt(int fc, int rc, cons
 #undef MX_QS
 }
 
-template <int FA, int FB, int CDT, bool QA, int RND>
+// PROBE (measurement aid): thread 0 of every work-group also records how long it took from its start
+// to the end of its K loop, in shader clocks and in ticks of the constant 100 MHz counter, at
+// probe[2 * blockIdx.x] and [.. + 1]: what the shader clock was under this load, and how many
+// clocks a K step took.
+template <int FA, int FB, int CDT, bool QA, int RND, bool PROBE = false>
 __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N, int64_t K,
                                                             const uint8_t *__restrict__ Ae, const uint8_t *__restrict__ As,
                                                             const uint16_t *__restrict__ Abf, int64_t lda,
                                                             const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
                                                             void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n,
-                                                            uint8_t *__restrict__ Cs, int fcr, Raster rast)
+                                                            uint8_t *__restrict__ Cs, int fcr, Raster rast,
+                                                            unsigned long long *__restrict__ probe)
 {
+    unsigned long long probe_c0 = 0, probe_r0 = 0;
+    if constexpr (PROBE) { probe_c0 = __builtin_readcyclecounter(); probe_r0 = __builtin_amdgcn_s_memrealtime(); }
     static_assert(!(QA && CDT == DT_MX), "the MX epilogue is built for plain operands");
     constexpr int WA = Fmt<FA>::bits, WB = Fmt<FB>::bits;
     static_assert(!QA || WA == 8, "the fused cast is written for 8-bit A operands");
@@ -472,6 +479,12 @@ __global__ __launch_bounds__(256, 1) void gemm_tile_kernel(int64_t M, int64_t N,
     // every direct load (the last, clamped, stages included) must have landed before this
     // work-group's LDS can be handed to another one
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (PROBE) {
+        if (threadIdx.x == 0) {
+            probe[2 * blockIdx.x] = __builtin_readcyclecounter() - probe_c0;
+            probe[2 * blockIdx.x + 1] = __builtin_amdgcn_s_memrealtime() - probe_r0;
+        }
+    }
 #undef MX_FENCE
 
     // ---- quantize-on-load: exact recomputation of the tile if any block needed the exact cast
@@ -560,7 +573,7 @@ static hipError_t launch_t(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, c
     const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
     const Raster rast = choose_raster(tiles_m, tiles_n, Fmt<FA>::bits, Fmt<FB>::bits);
     hipLaunchKernelGGL(kern, dim3(raster_grid(rast, tiles_m, tiles_n)), dim3(256), 0, st, M, N, K, Ae, As, Abf, lda, Be, Bs, C, ldc,
-                       tiles_m, tiles_n, Cs, fcr, rast);
+                       tiles_m, tiles_n, Cs, fcr, rast, static_cast<unsigned long long *>(nullptr));
     return hipGetLastError();
 }
 

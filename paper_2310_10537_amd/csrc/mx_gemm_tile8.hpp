@@ -21,12 +21,15 @@ namespace mx {
 
 constexpr int NW8 = 8;   // waves per work-group
 
-template <int FA, int FB, int CDT>
+template <int FA, int FB, int CDT, bool PROBE = false>   // PROBE: as in the four-wave kernel
 __global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N, int64_t K,
                                                              const uint8_t *__restrict__ Ae, const uint8_t *__restrict__ As,
                                                              const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
-                                                             void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n, Raster rast)
+                                                             void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n, Raster rast,
+                                                             unsigned long long *__restrict__ probe)
 {
+    unsigned long long probe_c0 = 0, probe_r0 = 0;
+    if constexpr (PROBE) { probe_c0 = __builtin_readcyclecounter(); probe_r0 = __builtin_amdgcn_s_memrealtime(); }
     static_assert(CDT == DT_F32 || CDT == DT_BF16, "plain output types only");
     constexpr int WA = Fmt<FA>::bits, WB = Fmt<FB>::bits;
     typedef TileFmt<WA> TA;
@@ -230,6 +233,12 @@ __global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N
     for (int h = 0; h < T - Tfull; h++) k_step(Tfull, h);
 #undef MX8_MFMA
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (PROBE) {
+        if (threadIdx.x == 0) {
+            probe[2 * blockIdx.x] = __builtin_readcyclecounter() - probe_c0;
+            probe[2 * blockIdx.x + 1] = __builtin_amdgcn_s_memrealtime() - probe_r0;
+        }
+    }
 #undef MX8_FENCE
 
     // ---- epilogue: lane (li, g), register t of tile (x, y) -> C[8*(t/4) + 4g + t%4][li]
@@ -268,7 +277,7 @@ static hipError_t launch_t8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, 
     const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
     const Raster rast = choose_raster(tiles_m, tiles_n, Fmt<FA>::bits, Fmt<FB>::bits);
     hipLaunchKernelGGL(kern, dim3(raster_grid(rast, tiles_m, tiles_n)), dim3(512), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc, tiles_m, tiles_n,
-                       rast);
+                       rast, static_cast<unsigned long long *>(nullptr));
     return hipGetLastError();
 }
 

@@ -26,7 +26,7 @@ def test_exports_match_header(L):
     assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_sr", "mx_quantize_dual", "mx_quantize_3d", "mx_dequantize", "mx_gemm",
                      "mx_gemm_qa", "mx_gemm_q", "mx_gemm_qa_noalloc", "mx_stream_pattern", "mx_strerror",
                      "mx_gemm_workspace_bytes", "mx_gemm_qa_workspace_bytes", "mx_gemm_q_workspace_bytes", "mx_gemm_ws", "mx_gemm_qa_ws",
-                     "mx_gemm_q_ws"}
+                     "mx_gemm_q_ws", "mx_gemm_probe"}
     for n in names:
         assert hasattr(L, n), n
 
@@ -159,3 +159,13 @@ def test_workspace_queries_and_validation(L):
     assert L.mx_gemm_q_ws(300, 520, 640, p, p, 0, p, p, 3, 2, 0, p, p, p, 100, None) == 8
     assert L.mx_gemm_qa_ws(8192, 4096, 4096, p, 4096, 0, 0, p, p, 0, p, 1, 4096, p + 8, 1 << 30, None) == 4
     assert b"workspace" in L.mx_strerror(8)
+
+
+def test_gemm_probe_validation(L):
+    p = 0x1000
+    args = lambda M, N, K, fa, fb, plen: (M, N, K, p, p, fa, p, p, fb, p, N, p, plen, None)
+    assert L.mx_gemm_probe(*args(512, 512, 512, 0, 1, 64)) == 5          # pair without a probe build
+    assert L.mx_gemm_probe(*args(500, 512, 512, 0, 0, 64)) == 3          # whole tiles only
+    assert L.mx_gemm_probe(*args(512, 512, 256, 0, 0, 64)) == 3
+    assert L.mx_gemm_probe(*args(512, 512, 512, 0, 0, 8)) == 3           # probe buffer too short
+    assert L.mx_gemm_probe(512, 512, 512, p, p, 0, p, p, 0, p, 512, None, 64, None) == 1
