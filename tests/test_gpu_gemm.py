@@ -874,3 +874,23 @@ def test_gemm_few_rows_qa_and_one_hot(mx, oracle):
         Bd = oracle.dequantize(eb, sb, fb, N, K, 1)
         C = to_host(mx.mx_gemm(to_dev(eh), to_dev(sh), 1, to_dev(eb), to_dev(sb), fb, K))
         assert np.array_equal(C, Bd[:, pos].T.astype(np.float32))
+
+
+@pytest.mark.parametrize("fa,fb", [(0, 0), (2, 2), (2, 4)], ids=["e4m3", "e3m2", "e3m2xe2m1"])
+def test_gemm_probe_is_the_same_product(mx, oracle, fa, fb):
+    """The measurement aid runs the tiled kernel with counters added: same bytes as mx_gemm, and one
+    (clocks, ticks) pair per work-group that is plausible (a K loop takes at least its matrix instructions)."""
+    M, N, K = 1024, 768, 1024
+    a = to_dev(inputs.student_t_bf16((M, K), seed=71))
+    b = to_dev(inputs.gaussian_f32((N, K), seed=72, std=0.02))
+    ga, gb = mx.mx_quantize(a, 1, fa), mx.mx_quantize(b, 1, fb)
+    want = mx.mx_gemm(ga[0], ga[1], fa, gb[0], gb[1], fb, K, dtype=torch.bfloat16)
+    got = torch.full((M, N), 7.0, dtype=torch.bfloat16, device="cuda")
+    clk, ticks = mx.mx_gemm_probe(ga[0], ga[1], fa, gb[0], gb[1], fb, K, got)
+    torch.cuda.synchronize()
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    assert clk.numel() == (M // 256) * (N // 256)
+    steps = K // 128
+    assert int(clk.min()) >= steps * (2048 if fa == 0 else 1024)          # matrix instructions alone
+    ghz = clk.double().sum().item() / ticks.double().sum().item() * 0.1
+    assert 0.3 < ghz < 3.0
