@@ -33,6 +33,8 @@ Also in the default run, per call and with the same protocol:
                    counters read inside the kernel (mx_gemm_probe), on the real operands and on zeros;
   "gemm_zero_operands"  the headline GEMM launch on all-zero operands: what the same kernel
                    does when operand switching activity does not hold the clock down;
+  "vendor_reference_8192x4096x4096"  context only: the vendor library's FP8 GEMM (one scale per tensor) and
+                   its MX block-scaled FP8 GEMM through torch._scaled_mm, same shape, same box;
   "gemm_max_rel_err"    (with the CPU baseline leg) max |dC| / sum |a||b| of sampled entries
                    against the double-precision reference, per GEMM workload.
 --quick leaves out "other_configs"; --all-configs adds decoding shapes, MXINT8, the added
@@ -112,6 +114,34 @@ def clock_probe(A, fmtA, B, fmtB, K, C, mfma_clocks_per_step, n=6):
     return {"shader_GHz": round(float(clk.sum() / ticks.sum()) * 0.1, 3), "clocks_per_k_step": round(per_step, 0),
             "mfma_clocks_per_k_step": mfma_clocks_per_step,
             "k_loop_us_per_tile": round(float(ticks.mean()) / 100.0, 2)}
+
+
+def vendor_reference(n):
+    """Context, not a target and no part of the product: the vendor library's FP8 GEMMs (through
+    torch._scaled_mm) on the same box and shape as the headline GEMM, on N(0,1) x N(0,1) operands --
+    with one scale per tensor (no MX blocks) and with E8M0 scales per 32 elements (the MX product).
+    None where this torch build does not offer the call."""
+    out = {}
+    M, N, K = GM, GN, GK
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    a = torch.randn((M, K), device="cuda", generator=g).to(torch.float8_e4m3fn)
+    b = torch.randn((N, K), device="cuda", generator=g).to(torch.float8_e4m3fn)
+    one = torch.tensor(1.0, device="cuda")
+    flop = 2.0 * M * N * K
+    try:
+        ms = time_call(lambda: torch._scaled_mm(a, b.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16), n)
+        out["fp8_one_scale_per_tensor_TFLOPs"] = round(flop / ms / 1e9, 1)
+    except Exception:                      # noqa: BLE001  (an unsupported call is reported as absent)
+        out["fp8_one_scale_per_tensor_TFLOPs"] = None
+    try:
+        sa = torch.full((M, K // 32), 127, dtype=torch.uint8, device="cuda").view(torch.float8_e8m0fnu)
+        sb = torch.full((N, K // 32), 127, dtype=torch.uint8, device="cuda").view(torch.float8_e8m0fnu)
+        ms = time_call(lambda: torch._scaled_mm(a, b.t(), scale_a=sa, scale_b=sb, out_dtype=torch.bfloat16), n)
+        out["mxfp8_block_scaled_TFLOPs"] = round(flop / ms / 1e9, 1)
+    except Exception:                      # noqa: BLE001
+        out["mxfp8_block_scaled_TFLOPs"] = None
+    return out
 
 
 def cast_bytes(fmt, n_elem):
@@ -556,6 +586,7 @@ def main():
     torch.cuda.empty_cache()
     if not args.quick:
         line["other_configs"] = other_configs(args.steps, samples, args.all_configs)
+        line["vendor_reference_8192x4096x4096"] = vendor_reference(args.steps)
     if not args.no_cpu_baseline:
         line["cpu_baseline"], line["gemm_max_rel_err"] = cpu_leg(x_bits, samples)
     print(json.dumps(line))
