@@ -632,5 +632,9 @@ hipError_t launch_gemm_tiled_a4(const TileArgs &a, int fmtA, int fmtB);
 // the eight-wave form of the kernel (plain operands, Float32 / bf16 output), same split
 hipError_t launch_gemm_tiled8_a6(const TileArgs &a, int fmtA, int fmtB);
 hipError_t launch_gemm_tiled8_a4(const TileArgs &a, int fmtA, int fmtB);
+// the half-width form (256 x 128 tiles, four waves), plain operands, Float32 / bf16 output, every pair
+hipError_t launch_gemm_tiledh_a8(const TileArgs &a, int fmtA, int fmtB);
+hipError_t launch_gemm_tiledh_a6(const TileArgs &a, int fmtA, int fmtB);
+hipError_t launch_gemm_tiledh_a4(const TileArgs &a, int fmtA, int fmtB);
 
 }  // namespace mx

@@ -13,16 +13,20 @@
 // operands takes 92 us.  So the dispatcher sends only pairs without an 8-bit operand here.
 // Plain operands and Float32 / bf16 output only; quantize-on-load and the MX epilogue stay with
 // the four-wave kernel.
+//
+// Half-width form (NW = 4): the same kernel with four waves and a 256 x 128 tile (two 64-column
+// quarters), for every format pair.  A half tile costs about 0.6 of a whole one (it needs the whole A
+// tile for half the products), so it pays where whole tiles leave most compute units idle: the last,
+// partly filled round of a large problem, and problems of at most 128 tiles (launch_gemm_tiled
+// decides).  An entry's K chain is the same in every form, so the results are bit-identical.
 #pragma once
 
 #include "mx_gemm_tile.hpp"
 
 namespace mx {
 
-constexpr int NW8 = 8;   // waves per work-group
-
-template <int FA, int FB, int CDT, bool PROBE = false>   // PROBE: as in the four-wave kernel
-__global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N, int64_t K,
+template <int FA, int FB, int CDT, bool PROBE = false, int NW8 = 8>   // PROBE: as in the four-wave kernel; NW8: waves (8 or 4)
+__global__ __launch_bounds__(64 * NW8, 1) void gemm_tile8_kernel(int64_t M, int64_t N, int64_t K,
                                                              const uint8_t *__restrict__ Ae, const uint8_t *__restrict__ As,
                                                              const uint8_t *__restrict__ Be, const uint8_t *__restrict__ Bs,
                                                              void *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n, Raster rast,
@@ -34,25 +38,27 @@ __global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N
     constexpr int WA = Fmt<FA>::bits, WB = Fmt<FB>::bits;
     typedef TileFmt<WA> TA;
     typedef TileFmt<WB> TB;
-    constexpr int A_BYTES = TM * TA::ROW, B_BYTES = TN * TB::ROW, STAGE_BYTES = A_BYTES + B_BYTES;
+    static_assert(NW8 == 8 || NW8 == 4, "eight waves (256 x 256) or four (256 x 128)");
+    constexpr int TNW = 32 * NW8;                        // tile width: 64 columns per pair of waves
+    constexpr int A_BYTES = TM * TA::ROW, B_BYTES = TNW * TB::ROW, STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int NSTAGE = (WA < 8 && WB < 8 && 3 * STAGE_BYTES + 2 * SCL_BYTES <= 160 * 1024) ? 3 : 2;
     __shared__ __attribute__((aligned(16))) uint8_t lds[NSTAGE * STAGE_BYTES + 2 * SCL_BYTES];
     constexpr int HA = hw_fmt(FA), HB = hw_fmt(FB);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: everything derived from it stays in scalar registers
-    const int wm = wave >> 2, wn = wave & 3;          // 128-row half, 64-column quarter
+    const int wm = wave / (NW8 / 2), wn = wave % (NW8 / 2);   // 128-row half, 64-column quarter
     const int li = lane & 31, g = lane >> 5;
 
     // XCD-aware order of the tiles (mx_gemm_raster.hpp)
     int tm, tn;
     if (!raster_tile(rast, (int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     const int64_t m0 = (int64_t)tm * TM;
-    const int64_t n0 = (int64_t)tn * TN;
+    const int64_t n0 = (int64_t)tn * TNW;
     const int64_t nkb = K / BLOCK;
     const int T = (int)(K / TK);
     const int Tfull = T & ~(SCL_GROUP - 1);
 
-    // ---- staging map: wave w, load j fills LDS bytes (8j + w) * 1024 .. + 1023 of an operand tile
+    // ---- staging map: wave w, load j fills LDS bytes (NW8 * j + w) * 1024 .. + 1023 of an operand tile
     const int a_r = WA == 4 ? lane >> 2 : lane >> 3, b_r = WB == 4 ? lane >> 2 : lane >> 3;
     const int a_u = WA == 4 ? (lane & 3) ^ ((a_r >> 2) & 3) : (lane & 7) ^ (((wave * 8 + a_r) >> 1) & 7);
     const int b_u = WB == 4 ? (lane & 3) ^ ((b_r >> 2) & 3) : (lane & 7) ^ (((wave * 8 + b_r) >> 1) & 7);
@@ -64,18 +70,22 @@ __global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N
     const uint8_t *sB = WB == 6 ? Be + n0 * b_row_bytes : Be + (n0 + wave * TB::RPI) * b_row_bytes;
     const uint32_t vA = (uint32_t)(a_r * a_row_bytes + a_u * TA::UNIT), vB = (uint32_t)(b_r * b_row_bytes + b_u * TB::UNIT);
     constexpr int NJA = A_BYTES / (NW8 * 1024), NJB = B_BYTES / (NW8 * 1024);   // direct loads per wave per stage
-    uint32_t a6[3] = {}, b6[3] = {};
+    constexpr int N6A = WA == 6 ? NJA : 1, N6B = WB == 6 ? NJB : 1;   // 6-bit: one lane offset per load number
+    uint32_t a6[N6A] = {}, b6[N6B] = {};
     if (WA == 6 || WB == 6) {
 #pragma unroll
-        for (int j = 0; j < 3; j++) {
+        for (int j = 0; j < (N6A > N6B ? N6A : N6B); j++) {
             const uint32_t q = (uint32_t)((NW8 * j + wave) * 64 + lane), row = q / 6, c = (q - row * 6) ^ ((row >> 3) & 1);
-            if (WA == 6) a6[j] = row * (uint32_t)a_row_bytes + c * 16;
-            if (WB == 6) b6[j] = row * (uint32_t)b_row_bytes + c * 16;
+            if (WA == 6 && j < N6A) a6[j] = row * (uint32_t)a_row_bytes + c * 16;
+            if (WB == 6 && j < N6B) b6[j] = row * (uint32_t)b_row_bytes + c * 16;
         }
     }
     const int st_l = wave * 1024;
-    // ---- scale staging: waves 0-3 fetch the A rows 64w .. 64w+63, waves 4-7 the B rows
-    const uint8_t *sS = wave < 4 ? As + (m0 + wave * 64) * nkb : Bs + (n0 + (wave - 4) * 64) * nkb;
+    // ---- scale staging: 64 rows per wave-wide load, A's four groups then B's (TNW / 64); wave w takes
+    // groups w and w + NW8 (eight waves: one each; four waves: A's group w, and B's for w < 2)
+    constexpr int N_SCL = 4 + TNW / 64;
+    auto scl_src = [&](int idx) { return idx < 4 ? As + (m0 + idx * 64) * nkb : Bs + (n0 + (idx - 4) * 64) * nkb; };
+    const uint8_t *sS0 = scl_src(wave), *sS1 = scl_src(wave + NW8 < N_SCL ? wave + NW8 : wave);
     const uint32_t vS = (uint32_t)(lane * nkb);
     const int rsa = (wm * 128 + li) * 16, rsb = TM * 16 + (wn * 64 + li) * 16;
     const FragOfs<WA> ra0 = frag_ofs<WA>(wm * 128 + li, g);
@@ -96,13 +106,13 @@ __global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N
     auto stage_a1 = [&](int ts, uint8_t *dst, int j) {
         const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
         const uint8_t *sp = WA == 6 ? sA + (int64_t)ts * (TK * WA / 8) : sA + (int64_t)ts * (TK * WA / 8) + j * (NW8 * TA::RPI) * a_row_bytes;
-        const uint32_t vo = WA == 6 ? a6[j < 3 ? j : 0] : vA;
+        const uint32_t vo = WA == 6 ? a6[j < N6A ? j : 0] : vA;
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(vo), "s"(sp), "s"(l0 + j * (NW8 * 1024)) : "m0");
     };
     auto stage_b1 = [&](int ts, uint8_t *dst, int j) {
         const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + st_l));
         const uint8_t *sp = WB == 6 ? sB + (int64_t)ts * (TK * WB / 8) : sB + (int64_t)ts * (TK * WB / 8) + j * (NW8 * TB::RPI) * b_row_bytes;
-        const uint32_t vo = WB == 6 ? b6[j < 3 ? j : 0] : vB;
+        const uint32_t vo = WB == 6 ? b6[j < N6B ? j : 0] : vB;
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(vo), "s"(sp), "s"(l0 + j * (NW8 * 1024)) : "m0");
     };
     auto stage_all = [&](int ts, uint8_t *dst) {
@@ -111,6 +121,7 @@ __global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N
 #pragma unroll
         for (int j = 0; j < NJB; j++) stage_b1(ts, dst + A_BYTES, j);
     };
+    static_assert(NJA + NJB <= 12, "the second half of a step has twelve slots for direct loads");
     auto stage_one = [&](int k, int ts, uint8_t *dstA, uint8_t *dstB) {
         if (k < NJA) stage_a1(ts, dstA, k);
         else if (k - NJA < NJB) stage_b1(ts, dstB, k - NJA);
@@ -123,8 +134,12 @@ __global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N
         uint8_t *dst = scl + (G & 1) * SCL_BYTES;
         const uint32_t l0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t *)(dst + wave * 1024));
         const int64_t src_ofs = G * SCL_GROUP + SCL_GROUP <= T ? (int64_t)G * 16 : (int64_t)T * 4 - 16;
-        const uint8_t *p = sS + src_ofs;
+        const uint8_t *p = sS0 + src_ofs;
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(vS), "s"(p), "s"(l0) : "m0");
+        if (NW8 < N_SCL && wave + NW8 < N_SCL) {            // wave-uniform
+            const uint8_t *p1 = sS1 + src_ofs;
+            asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(vS), "s"(p1), "s"(l0 + NW8 * 1024) : "m0");
+        }
     };
     auto read_scales = [&](int ts) {
         ts = ts < T ? ts : T - 1;
@@ -199,13 +214,13 @@ __global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N
         // ---- Y: sub-step 1; stage t+NSTAGE is requested into the buffer stage t just vacated, one direct
         // load per matrix instruction, and the fragments of sub-step 0 of stage t+1 are read
         b0[0] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 0);
-        stage_one(0, t2, bufA, bufB); MX8_MFMA(af, b1, 0, 0, 2); MX8_FENCE();
-        stage_one(1, t2, bufA, bufB); MX8_MFMA(af, b1, 0, 1, 2);
+        stage_one(0, t2, bufA, bufB); stage_one(0 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 0, 0, 2); MX8_FENCE();
+        stage_one(1, t2, bufA, bufB); stage_one(1 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 0, 1, 2);
         af[0] = read_frag<WA>(nxt, ra0, 0, 0);
         MX8_FENCE();
         b0[1] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 1);
-        stage_one(2, t2, bufA, bufB); MX8_MFMA(af, b1, 1, 0, 2); MX8_FENCE();
-        stage_one(3, t2, bufA, bufB); MX8_MFMA(af, b1, 1, 1, 2);
+        stage_one(2, t2, bufA, bufB); stage_one(2 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 1, 0, 2); MX8_FENCE();
+        stage_one(3, t2, bufA, bufB); stage_one(3 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 1, 1, 2);
         af[1] = read_frag<WA>(nxt, ra0, 0, 1);
         MX8_FENCE();
         if (h == 0) stage_scales(tt / SCL_GROUP + 1);
@@ -269,14 +284,15 @@ __global__ __launch_bounds__(512, 1) void gemm_tile8_kernel(int64_t M, int64_t N
         }
 }
 
-template <int FA, int FB, int CDT>
+template <int FA, int FB, int CDT, int NW = 8>
 static hipError_t launch_t8(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint8_t *As, const uint8_t *Be,
                             const uint8_t *Bs, void *C, int64_t ldc, hipStream_t st)
 {
-    auto kern = gemm_tile8_kernel<FA, FB, CDT>;
-    const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
-    const Raster rast = choose_raster(tiles_m, tiles_n, Fmt<FA>::bits, Fmt<FB>::bits);
-    hipLaunchKernelGGL(kern, dim3(raster_grid(rast, tiles_m, tiles_n)), dim3(512), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc, tiles_m, tiles_n,
+    auto kern = gemm_tile8_kernel<FA, FB, CDT, false, NW>;
+    const int tiles_m = (int)(M / TM), tiles_n = (int)(N / (32 * NW));
+    // (a half tile's B slab is half as heavy as its A slab)
+    const Raster rast = choose_raster(tiles_m, tiles_n, Fmt<FA>::bits * 8, Fmt<FB>::bits * NW);
+    hipLaunchKernelGGL(kern, dim3(raster_grid(rast, tiles_m, tiles_n)), dim3(64 * NW), 0, st, M, N, K, Ae, As, Be, Bs, C, ldc, tiles_m, tiles_n,
                        rast, static_cast<unsigned long long *>(nullptr));
     return hipGetLastError();
 }
@@ -286,6 +302,27 @@ static hipError_t launch_pair8(const TileArgs &a)
 {
     return a.c_dt == DT_F32 ? launch_t8<FA, FB, DT_F32>(a.M, a.N, a.K, a.Ae, a.As, a.Be, a.Bs, a.C, a.ldc, a.st)
                             : launch_t8<FA, FB, DT_BF16>(a.M, a.N, a.K, a.Ae, a.As, a.Be, a.Bs, a.C, a.ldc, a.st);
+}
+
+// the half-width form: 256 x 128 tiles, four waves, every format pair
+template <int FA, int FB>
+static hipError_t launch_pair_half(const TileArgs &a)
+{
+    return a.c_dt == DT_F32 ? launch_t8<FA, FB, DT_F32, 4>(a.M, a.N, a.K, a.Ae, a.As, a.Be, a.Bs, a.C, a.ldc, a.st)
+                            : launch_t8<FA, FB, DT_BF16, 4>(a.M, a.N, a.K, a.Ae, a.As, a.Be, a.Bs, a.C, a.ldc, a.st);
+}
+
+template <int FA>
+static hipError_t launch_a_half(const TileArgs &a, int fmtB)
+{
+    switch (fmtB) {
+        case FP8_E4M3: return launch_pair_half<FA, FP8_E4M3>(a);
+        case FP8_E5M2: return launch_pair_half<FA, FP8_E5M2>(a);
+        case FP6_E3M2: return launch_pair_half<FA, FP6_E3M2>(a);
+        case FP6_E2M3: return launch_pair_half<FA, FP6_E2M3>(a);
+        case FP4_E2M1: return launch_pair_half<FA, FP4_E2M1>(a);
+        default:       return hipErrorNotSupported;
+    }
 }
 
 template <int FA>
