@@ -281,6 +281,19 @@ def test_quantize_dual_full_size_sampled(mx, oracle):
         re_, rs = oracle.quantize(np.ascontiguousarray(x[:, lo:lo + 128]), 0, 0, 0)
         assert np.array_equal(to_host(e0[lo:lo + 128]), re_) and np.array_equal(to_host(s0[lo:lo + 128]), rs)
 
+@pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
+def test_quantize_dual_wide_tiles_all_formats(mx, oracle, fmt):
+    """4096 x 4096: the dual-axis kernel's 128-column tiles (FP6: its 16-byte store paths) in every format,
+    slices of both outputs against the reference."""
+    x = inputs.student_t_bf16((4096, 4096), seed=50 + fmt)
+    rnd = AWAY if fmt in (2, 5) else RNE
+    (e1, s1), (e0, s0) = mx.mx_quantize_dual(to_dev(x), fmt, rnd)
+    for lo in (0, 1984, 4096 - 160):
+        re_, rs = oracle.quantize(np.ascontiguousarray(x[lo:lo + 160]), 1, fmt, rnd)
+        assert np.array_equal(to_host(s1[lo:lo + 160]), rs) and np.array_equal(to_host(e1[lo:lo + 160]), re_), (fmt, lo, "axis 1")
+        re_, rs = oracle.quantize(np.ascontiguousarray(x[:, lo:lo + 160]), 0, fmt, rnd)
+        assert np.array_equal(to_host(s0[lo:lo + 160]), rs) and np.array_equal(to_host(e0[lo:lo + 160]), re_), (fmt, lo, "axis 0")
+
 
 @pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
 @pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
