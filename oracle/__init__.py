@@ -49,6 +49,7 @@ def lib():
         L.mxo_sr_uniform.restype = ctypes.c_double
         L.mxo_quantize_3d.argtypes = [vp, ci, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, vp]
         L.mxo_dequantize.argtypes = [vp, vp, ci, i64, i64, ci, vp, ci, i64]
+        L.mxo_dequantize_3d.argtypes = [vp, vp, ci, i64, i64, i64, ci, ci, vp, ci, i64, i64]
         L.mxo_gemm.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, vp]
         L.mxo_gemm_entries.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, i64, vp, vp, vp, vp]
         _lib = L
@@ -172,6 +173,26 @@ def quantize_3d(src, axis, fmt, rnd=ROUND_RNE, keep_order=False, strides=None):
     if st != 0:
         raise ValueError("mxo_quantize_3d rejected its arguments")
     return elems, scales
+
+
+def dequantize_3d(elems, scales, fmt, shape, axis, keep_order=False, dst_dt=DT_F32, strides=None):
+    """Inverse of quantize_3d.  Returns the [d0, d1, d2] tensor (float32, or uint16 bf16 bits); with
+    strides = (stride0, stride1) a flat buffer of (d0 - 1) * stride0 + (d1 - 1) * stride1 + d2 entries
+    whose untouched entries keep the value 0x7777 / 7.0 (so a test sees what was written)."""
+    d0, d1, d2 = shape
+    elems = np.ascontiguousarray(elems, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.uint8)
+    dt = np.float32 if dst_dt == DT_F32 else np.uint16
+    if strides is None:
+        dst = np.zeros((d0, d1, d2), dtype=dt)
+        s0, s1 = d1 * d2, d2
+    else:
+        s0, s1 = strides
+        dst = np.full((d0 - 1) * s0 + (d1 - 1) * s1 + d2, 7.0 if dst_dt == DT_F32 else 0x7777, dtype=dt)
+    st = lib().mxo_dequantize_3d(_ptr(elems), _ptr(scales), fmt, d0, d1, d2, axis, 1 if keep_order else 0, _ptr(dst), dst_dt, s0, s1)
+    if st != 0:
+        raise ValueError("mxo_dequantize_3d rejected its arguments")
+    return dst
 
 
 def dequantize(elems, scales, fmt, rows, cols, axis, dst_dt=DT_F32):

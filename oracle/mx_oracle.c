@@ -537,6 +537,47 @@ int mxo_dequantize(const uint8_t *elems, const uint8_t *scales, int fmt,
     return MXO_OK;
 }
 
+/* Inverse of mxo_quantize_3d (Section 2: v_i = X * P_i), for both of its layouts: element
+ * (i0, i1, i2) of the [d0][d1][d2] result, written at dst[i0*stride0 + i1*stride1 + i2], is the
+ * code that mxo_quantize_3d put there times the scale of the block it lies in. */
+int mxo_dequantize_3d(const uint8_t *elems, const uint8_t *scales, int fmt, int64_t d0, int64_t d1,
+                      int64_t d2, int axis, int keep_order, void *dst, int dst_dt,
+                      int64_t stride0, int64_t stride1)
+{
+    if (!elems || !scales || !dst || !fmt_ok(fmt)) return MXO_ERR_ARG;
+    if (dst_dt != MXO_DT_F32 && dst_dt != MXO_DT_BF16) return MXO_ERR_ARG;
+    if (d0 <= 0 || d1 <= 0 || d2 <= 0 || axis < 0 || axis > 2) return MXO_ERR_ARG;
+    int w = FMT[fmt].bits;
+    if (keep_order && (d2 * w) % 8) return MXO_ERR_ARG;
+    const int64_t dim[3] = {d0, d1, d2};
+    const int64_t L = dim[axis], nblk = (L + MXO_BLOCK - 1) / MXO_BLOCK;
+    const int a1 = axis == 0 ? 1 : 0, a2 = axis == 2 ? 1 : 2;
+    const int64_t n2 = dim[a2];
+    const int64_t line_bytes = nblk * MXO_BLOCK * w / 8, row_bytes = d2 * w / 8;
+    const int64_t sd1 = axis == 1 ? nblk : d1, sd2 = axis == 2 ? nblk : d2;
+
+    for (int64_t i0 = 0; i0 < d0; i0++)
+        for (int64_t i1 = 0; i1 < d1; i1++)
+            for (int64_t i2 = 0; i2 < d2; i2++) {
+                const int64_t idx[3] = {i0, i1, i2};
+                const int64_t l = idx[axis], b = l / MXO_BLOCK;
+                unsigned code;
+                uint8_t sc;
+                if (!keep_order) {
+                    const int64_t line = idx[a1] * n2 + idx[a2];
+                    code = get_code(elems + line * line_bytes, l, w);
+                    sc = scales[line * nblk + b];
+                } else {
+                    int64_t sidx[3] = {i0, i1, i2};
+                    sidx[axis] = b;
+                    code = get_code(elems + (i0 * d1 + i1) * row_bytes, i2, w);
+                    sc = scales[(sidx[0] * sd1 + sidx[1]) * sd2 + sidx[2]];
+                }
+                store_scalar(dst, dst_dt, i0 * stride0 + i1 * stride1 + i2, block_value(fmt, code, sc));
+            }
+    return MXO_OK;
+}
+
 /* ------------------------------------------------------------------------
  * MX dot product.  Because every X is a power of two, sum over blocks of
  * X_A * X_B * sum_j a_j * b_j equals the plain sum of products of the

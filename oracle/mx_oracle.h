@@ -134,6 +134,10 @@ int mxo_quantize_3d(const void *src, int src_dt, int64_t d0, int64_t d1, int64_t
  * beyond Float32 range become +-Inf.  Writes row-major [rows, cols]; with a
  * block-axis length that is not a multiple of 32 the stored rows hold whole
  * blocks (as mxo_quantize writes them) and the fill positions are skipped. */
+/* inverse of mxo_quantize_3d for both layouts; dst [d0][d1][d2] with element strides (stride0, stride1, 1) */
+int mxo_dequantize_3d(const uint8_t *elems, const uint8_t *scales, int fmt, int64_t d0, int64_t d1,
+                      int64_t d2, int axis, int keep_order, void *dst, int dst_dt,
+                      int64_t stride0, int64_t stride1);
 int mxo_dequantize(const uint8_t *elems, const uint8_t *scales, int fmt,
                    int64_t rows, int64_t cols, int axis,
                    void *dst, int dst_dt, int64_t ld);

@@ -70,3 +70,83 @@ def test_hand_worked_fibre(oracle):
     assert e[0, 0, 0] == 0x78 and e[1, 0, 0] == 0x6A and e[2, 0, 0] == 0xA8 and e[5, 0, 1] == 0x7E
     e2, s2 = oracle.quantize_3d(x, 0, 0)
     assert e2.shape == (1, 2, 32) and e2[0, 0, 0] == 0x78 and e2[0, 1, 5] == 0x7E and s2[0, 1, 0] == 119
+
+
+# ---------------------------------------------------------------------------------------------
+# the inverse: mxo_dequantize_3d (Section 2: v_i = X * P_i) for both layouts
+# ---------------------------------------------------------------------------------------------
+def decode_table(oracle, fmt):
+    return np.array([oracle.decode(fmt, c) for c in range(1 << BITS[fmt])], dtype=np.float64)
+
+
+@pytest.mark.parametrize("fmt", range(6))
+@pytest.mark.parametrize("axis", [0, 1, 2])
+@pytest.mark.parametrize("shape", [(3, 64, 96), (5, 40, 72), (33, 2, 8)])
+def test_dequantize_block_major_equals_2d_dequantize_moved_back(oracle, fmt, axis, shape):
+    """The 3-D routine indexes the tensor itself; the pinned 2-D routine dequantizes the lines, and numpy
+    moves the block axis back."""
+    x = inputs.student_t_f32((shape[0] * shape[1], shape[2]), seed=27 + fmt).reshape(shape)
+    e, s = oracle.quantize_3d(x, axis, fmt)
+    got = oracle.dequantize_3d(e, s, fmt, shape, axis)
+    L = shape[axis]
+    lines = oracle.dequantize(e.reshape(-1, e.shape[-1]), s.reshape(-1, s.shape[-1]), fmt, e.shape[0] * e.shape[1], L, 1)
+    want = np.moveaxis(lines.reshape(e.shape[0], e.shape[1], L), -1, axis)
+    assert got.shape == tuple(shape) and np.array_equal(got.view(np.uint32), np.ascontiguousarray(want).view(np.uint32))
+
+
+@pytest.mark.parametrize("fmt", range(6))
+@pytest.mark.parametrize("axis", [0, 1, 2])
+def test_dequantize_source_order_against_numpy(oracle, fmt, axis):
+    """codes unpacked with numpy, decoded through the pinned table, scaled by 2^(s - 127) with the scale
+    array repeated 32 times along the block axis."""
+    shape = (40, 70, 24)
+    w = BITS[fmt]
+    x = inputs.student_t_f32((shape[0] * shape[1], shape[2]), seed=37 + fmt).reshape(shape)
+    ek, sk = oracle.quantize_3d(x, axis, fmt, keep_order=True)
+    sk = sk.copy()
+    sk.reshape(-1)[sk.size // 2] = 255                  # one NaN block
+    got = oracle.dequantize_3d(ek, sk, fmt, shape, axis, keep_order=True)
+    codes = unpack(ek, w, shape[2])
+    scale = np.repeat(sk, 32, axis=axis)
+    scale = scale[tuple(slice(0, n) for n in shape)]
+    want = np.ldexp(decode_table(oracle, fmt)[codes], scale.astype(np.int64) - 127)
+    want = np.where(scale == 255, np.nan, want).astype(np.float32)
+    nan = np.isnan(want)
+    assert nan.sum() >= 1 and np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))
+    # and it is the same tensor as the block-major route gives
+    e, s = oracle.quantize_3d(x, axis, fmt)
+    plain = oracle.dequantize_3d(e, s, fmt, shape, axis)
+    assert np.array_equal(plain[~nan].view(np.uint32), got[~nan].view(np.uint32))
+
+
+@pytest.mark.parametrize("keep", [False, True])
+def test_dequantize_3d_strides_and_bf16(oracle, keep):
+    shape, axis, fmt = (4, 6, 64), 1, 0
+    x = inputs.student_t_f32((24, 64), seed=47).reshape(shape)
+    e, s = oracle.quantize_3d(x, axis, fmt, keep_order=keep)
+    dense = oracle.dequantize_3d(e, s, fmt, shape, axis, keep_order=keep)
+    s0, s1 = 6 * 80 + 16, 80
+    flat = oracle.dequantize_3d(e, s, fmt, shape, axis, keep_order=keep, strides=(s0, s1))
+    touched = np.zeros(flat.size, dtype=bool)
+    for i0 in range(4):
+        for i1 in range(6):
+            lo = i0 * s0 + i1 * s1
+            assert np.array_equal(flat[lo:lo + 64], dense[i0, i1])
+            touched[lo:lo + 64] = True
+    assert np.all(flat[~touched] == 7.0)                 # nothing outside the tensor was written
+    # E4M3 values have 4 significant bits: the bf16 result is the Float32 one with the low half dropped
+    bf = oracle.dequantize_3d(e, s, fmt, shape, axis, keep_order=keep, dst_dt=1)
+    assert np.array_equal(bf, (dense.view(np.uint32) >> 16).astype(np.uint16))
+
+
+def test_dequantize_3d_hand_block(oracle):
+    """One block along axis 0 of a [32][1][2] tensor, E2M1 codes 0..15 twice, scale byte 130 (X = 8)."""
+    codes = (np.arange(32) % 16).astype(np.uint8)
+    # source order: row i0 holds the two codes of (i0, 0, 0..1) in one byte, low nibble first
+    ek = (codes | (codes << 4)).reshape(32, 1, 1)
+    sk = np.full((1, 1, 2), 130, dtype=np.uint8)
+    got = oracle.dequantize_3d(ek, sk, 4, (32, 1, 2), 0, keep_order=True)
+    mags = np.array([0, 0.5, 1, 1.5, 2, 3, 4, 6], dtype=np.float32) * 8
+    want = np.concatenate([mags, -mags])[codes]
+    assert np.array_equal(got[:, 0, 0], want) and np.array_equal(got[:, 0, 1], want)
