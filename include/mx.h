@@ -197,6 +197,21 @@ int mx_quantize_3d(const void *src, mx_dtype_t src_dt,
                    void *elems_out, uint8_t *scales_out, void *hip_stream);
 
 /*
+ * Inverse of mx_quantize_3d (Section 2: v_i = X * P_i): elems / scales in either
+ * of its layouts (keep_order as there; axis names the block axis) back to a
+ * [d0][d1][d2] tensor of type dst_dt written at dst[i0*stride0 + i1*stride1 + i2]
+ * (elements; stride1 >= d2, stride0 >= d1*stride1, dst 16-byte aligned and both
+ * strides a multiple of 16 bytes).  Nothing outside the tensor's elements is
+ * written.  A scale byte 0xFF gives NaN for its block; fill positions of a
+ * partial last block (keep_order = 0) are skipped.  keep_order = 0 with axis 1,
+ * or with axis 0 / 2 and padded rows, issues one launch per slice.
+ */
+int mx_dequantize_3d(const void *elems, const uint8_t *scales, mx_format_t fmt,
+                     int64_t d0, int64_t d1, int64_t d2, int axis, int keep_order,
+                     void *dst, mx_dtype_t dst_dt, int64_t stride0, int64_t stride1,
+                     void *hip_stream);
+
+/*
  * v = X * P (Section 2) for an MX tensor produced by mx_quantize with the same
  * rows, cols and axis; writes row-major dst [rows, cols] with leading
  * dimension ld (elements).  Scale byte 0xFF gives NaN for the whole block;

@@ -59,6 +59,7 @@ def lib() -> ctypes.CDLL:
         L.mx_gemm_ws.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, ci, i64, vp, sz, vp]
         L.mx_gemm_qa_ws.argtypes = [i64, i64, i64, vp, i64, ci, ci, vp, vp, ci, vp, ci, i64, vp, sz, vp]
         L.mx_gemm_q_ws.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, ci, ci, vp, vp, vp, sz, vp]
+        L.mx_dequantize_3d.argtypes = [vp, vp, ci, i64, i64, i64, ci, ci, vp, ci, i64, i64, vp]
         L.mx_quantize_3d.argtypes = [vp, ci, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, vp, vp]
         L.mx_stream_pattern.argtypes = [vp, vp, i64, ci, ci, vp]
         L.mx_gemm_probe.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, i64, vp, i64, vp]
@@ -332,3 +333,19 @@ def mx_gemm_probe(A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, K, out, stre
                                out.data_ptr(), out.stride(0), probe.data_ptr(), probe.numel(), _stream(stream)))
     ran = probe[:, 1] > 0
     return probe[ran, 0], probe[ran, 1]
+
+
+def mx_dequantize_3d(elems, scales, fmt, shape, axis, keep_order=False, dtype=torch.float32, out=None, stream=None):
+    """Inverse of mx_quantize_3d.  out: a [d0, d1, d2] tensor whose last axis is contiguous (strides are taken
+    from it); a dense one is allocated when it is None."""
+    _dev(elems, "elems")
+    _dev(scales, "scales")
+    d0, d1, d2 = shape
+    if out is None:
+        out = torch.empty((d0, d1, d2), dtype=dtype, device=elems.device)
+    assert tuple(out.shape) == (d0, d1, d2) and (d2 == 0 or out.stride(2) == 1)
+    s0 = out.stride(0) if d0 > 1 else d1 * max(out.stride(1), d2)
+    s1 = out.stride(1) if d1 > 1 else d2
+    _check(lib().mx_dequantize_3d(elems.data_ptr(), scales.data_ptr(), fmt, d0, d1, d2, axis, 1 if keep_order else 0,
+                                  out.data_ptr(), _dt(out), s0, s1, _stream(stream)))
+    return out

@@ -123,6 +123,21 @@ int mx_dequantize(const void *elems, const uint8_t *scales, mx_format_t fmt, int
     return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
 }
 
+int mx_dequantize_3d(const void *elems, const uint8_t *scales, mx_format_t fmt, int64_t d0, int64_t d1, int64_t d2, int axis,
+                     int keep_order, void *dst, mx_dtype_t dst_dt, int64_t stride0, int64_t stride1, void *hip_stream)
+{
+    if (!fmt_ok(fmt) || !dt_ok(dst_dt) || axis < 0 || axis > 2 || (keep_order != 0 && keep_order != 1)) return MX_ERR_ENUM;
+    if (d0 < 0 || d1 < 0 || d2 < 0 || stride1 < d2 || stride0 < d1 * stride1) return MX_ERR_SHAPE;
+    if (keep_order && (d2 * mx::fmt_bits(fmt)) % 8) return MX_ERR_SHAPE;
+    if (d0 == 0 || d1 == 0 || d2 == 0) return MX_OK;
+    if (!elems || !scales || !dst) return MX_ERR_NULL;
+    if (!aligned16(elems) || !aligned16(scales) || !aligned16(dst) || (stride0 * esize(dst_dt)) % 16 || (stride1 * esize(dst_dt)) % 16)
+        return MX_ERR_ALIGN;
+    hipError_t e = mx::launch_dequant_3d(static_cast<const uint8_t *>(elems), scales, fmt, d0, d1, d2, axis, keep_order != 0, dst, dst_dt,
+                                         stride0, stride1, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? MX_OK : MX_ERR_LAUNCH;
+}
+
 static int gemm_common(bool qa, int64_t M, int64_t N, int64_t K, const void *A_elems, const uint8_t *A_scales,
                        const void *A_bf16, int64_t lda, int rnd, mx_format_t fmtA, const void *B_elems, const uint8_t *B_scales,
                        mx_format_t fmtB, void *C, mx_dtype_t c_dt, int64_t ldc, void *hip_stream, void *workspace = nullptr,

@@ -32,6 +32,10 @@ hipError_t launch_cast_dual(const void *src, int src_dt, int64_t rows, int64_t c
 hipError_t launch_dequant(const uint8_t *elems, const uint8_t *scales, int fmt, int64_t rows, int64_t cols, int axis,
                           void *dst, int dst_dt, int64_t ld, hipStream_t st);
 
+// inverse of launch_cast_3d for both layouts; dst [d0][d1][d2] with element strides (stride0, stride1, 1)
+hipError_t launch_dequant_3d(const uint8_t *elems, const uint8_t *scales, int fmt, int64_t d0, int64_t d1, int64_t d2, int axis,
+                             bool keep_order, void *dst, int dst_dt, int64_t stride0, int64_t stride1, hipStream_t st);
+
 // Scratch memory of the GEMM routes that need it (the MX form of a bf16 operand, the two E2M3 halves of
 // MXINT8 operands, a Float32 C that is cast afterwards).  Inside a WorkspaceScope -- opened by the
 // entry points that take a caller-owned workspace -- ws_acquire carves 256-byte aligned pieces off

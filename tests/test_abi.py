@@ -26,7 +26,7 @@ def test_exports_match_header(L):
     assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_sr", "mx_quantize_dual", "mx_quantize_3d", "mx_dequantize", "mx_gemm",
                      "mx_gemm_qa", "mx_gemm_q", "mx_gemm_qa_noalloc", "mx_stream_pattern", "mx_strerror",
                      "mx_gemm_workspace_bytes", "mx_gemm_qa_workspace_bytes", "mx_gemm_q_workspace_bytes", "mx_gemm_ws", "mx_gemm_qa_ws",
-                     "mx_gemm_q_ws", "mx_gemm_probe"}
+                     "mx_gemm_q_ws", "mx_gemm_probe", "mx_dequantize_3d"}
     for n in names:
         assert hasattr(L, n), n
 
@@ -169,3 +169,17 @@ def test_gemm_probe_validation(L):
     assert L.mx_gemm_probe(*args(512, 512, 256, 0, 0, 64)) == 3
     assert L.mx_gemm_probe(*args(512, 512, 512, 0, 0, 8)) == 3           # probe buffer too short
     assert L.mx_gemm_probe(512, 512, 512, p, p, 0, p, p, 0, p, 512, None, 64, None) == 1
+
+
+def test_dequantize_3d_validation(L):
+    p = 0x1000
+    ok = (p, p, 0, 4, 6, 64, 1, 0, p, 0, 6 * 64, 64, None)
+    bad = lambda **kw: tuple(kw.get(k, v) for k, v in zip("elems scales fmt d0 d1 d2 axis keep dst dt s0 s1 st".split(), ok))
+    assert L.mx_dequantize_3d(*bad(axis=3)) == 2
+    assert L.mx_dequantize_3d(*bad(keep=2)) == 2
+    assert L.mx_dequantize_3d(*bad(s1=60)) == 3
+    assert L.mx_dequantize_3d(*bad(s0=5 * 64)) == 3
+    assert L.mx_dequantize_3d(*bad(fmt=2, d2=65, s1=80, s0=480, keep=1)) == 3      # 65 six-bit codes are no whole bytes
+    assert L.mx_dequantize_3d(*bad(d0=0)) == 0
+    assert L.mx_dequantize_3d(*bad(dst=None)) == 1
+    assert L.mx_dequantize_3d(*bad(s1=66, s0=6 * 66)) == 4                          # Float32 rows must start 16-byte aligned

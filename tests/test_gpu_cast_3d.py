@@ -77,3 +77,80 @@ def test_matrix_with_untransposed_axis0_output(mx, oracle):
     e, s = mx.mx_quantize_3d(to_dev(x).reshape(1, 2048, 1024), 1, 0, 0, True)
     et, st = mx.mx_quantize(to_dev(x), 0, 0)              # the transposed form of the same cast
     assert torch.equal(e[0].T.contiguous(), et) and torch.equal(s[0].T.contiguous(), st)
+
+
+# ---------------------------------------------------------------------------------------------
+# mx_dequantize_3d: the inverse, against the reference's mxo_dequantize_3d, bit for bit
+# ---------------------------------------------------------------------------------------------
+def same_bits(got, want):
+    """Float32 arrays (or uint16 bf16 bits): equal bit patterns, NaN matched by position."""
+    if got.dtype == np.uint16:
+        gn, wn = (got & 0x7FFF) > 0x7F80, (want & 0x7FFF) > 0x7F80
+        return np.array_equal(gn, wn) and np.array_equal(got[~gn], want[~wn])
+    gn, wn = np.isnan(got), np.isnan(want)
+    return np.array_equal(gn, wn) and np.array_equal(got[~gn].view(np.uint32), want[~wn].view(np.uint32))
+
+
+def check_deq(mx, oracle, x, axis, fmt, keep, dt, out=None, nan_block=False):
+    shape = x.shape
+    e, s = oracle.quantize_3d(x, axis, fmt, 0, keep)
+    if nan_block:
+        s = s.copy()
+        s.reshape(-1)[s.size // 3] = 255
+    want = oracle.dequantize_3d(e, s, fmt, shape, axis, keep, dst_dt=0 if dt == torch.float32 else 1)
+    got = mx.mx_dequantize_3d(to_dev(e), to_dev(s), fmt, shape, axis, keep, dtype=dt, out=out)
+    torch.cuda.synchronize()
+    g = to_host(got.contiguous() if dt == torch.float32 else got.contiguous().view(torch.int16)).view(np.float32 if dt == torch.float32 else np.uint16)
+    assert same_bits(g, want), (fmt, axis, keep, dt)
+
+
+@pytest.mark.parametrize("fmt", range(6), ids=NAMES)
+@pytest.mark.parametrize("axis", [0, 1, 2])
+@pytest.mark.parametrize("keep", [False, True], ids=["block_major", "source_order"])
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_dequantize_every_axis_and_layout(mx, oracle, fmt, axis, keep, dt):
+    shape = (40, 70, 24) if keep else (40, 70, 72)      # two axes end in a partial block
+    x = inputs.student_t_f32((shape[0] * shape[1], shape[2]), seed=60 + fmt).reshape(shape)
+    check_deq(mx, oracle, x, axis, fmt, keep, dt, nan_block=True)
+
+
+@pytest.mark.parametrize("axis", [0, 1, 2])
+@pytest.mark.parametrize("keep", [False, True], ids=["block_major", "source_order"])
+def test_dequantize_whole_tiles_and_degenerate_values(mx, oracle, axis, keep):
+    """4 x 128 x 256: the slices are whole tiles of the fast 2-D dequantize kernels; adversarial blocks."""
+    x = inputs.adversarial_f32(4 * 128, 256, seed=19).reshape(4, 128, 256)
+    for fmt in (0, 3, 4, 5):
+        check_deq(mx, oracle, x, axis, fmt, keep, torch.float32)
+        check_deq(mx, oracle, x, axis, fmt, keep, torch.bfloat16)
+
+
+@pytest.mark.parametrize("axis", [0, 1, 2])
+@pytest.mark.parametrize("keep", [False, True], ids=["block_major", "source_order"])
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_dequantize_into_a_strided_view(mx, oracle, axis, keep, dt):
+    """The result is a slice of a larger tensor: both leading strides are padded, and nothing outside the
+    slice may be written."""
+    shape = (3, 37, 64)
+    x = inputs.gaussian_f32((3 * 37, 64), seed=23).reshape(shape)
+    big = torch.full((5, 48, 96), 7.0, dtype=dt, device="cuda")
+    view = big[1:4, 8:45, 32:96]
+    for fmt in (1, 2, 4):
+        check_deq(mx, oracle, x, axis, fmt, keep, dt, out=view)
+        mask = torch.ones_like(big, dtype=torch.bool)
+        mask[1:4, 8:45, 32:96] = False
+        assert torch.all(big[mask] == 7.0)
+
+
+def test_round_trip_with_the_gpu_cast(mx, oracle):
+    """quantize_3d then dequantize_3d on the GPU, both layouts: the same tensor, and casting it again
+    returns the same bytes (idempotence)."""
+    x = to_dev(inputs.student_t_bf16((6 * 96, 128), seed=31)).reshape(6, 96, 128)
+    for axis in (0, 1, 2):
+        outs = []
+        for keep in (False, True):
+            e, s = mx.mx_quantize_3d(x, axis, 0, 0, keep)
+            y = mx.mx_dequantize_3d(e, s, 0, (6, 96, 128), axis, keep, dtype=torch.bfloat16)
+            e2, s2 = mx.mx_quantize_3d(y, axis, 0, 0, keep)
+            assert torch.equal(e, e2) and torch.equal(s, s2)
+            outs.append(y)
+        assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
