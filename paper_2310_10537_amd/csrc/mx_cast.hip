@@ -215,8 +215,9 @@ hipError_t launch_cast(const void *src, int src_dt, int64_t rows, int64_t cols, 
         hipError_t e = launch_cast_bf16_fast(src, rows, cols, ld, axis, fmt, rnd, elems, scales, st);
         if (e != hipErrorNotSupported) return e;
     }
-    if (scales_aligned && src_dt == DT_F32 && axis == 0) {
-        hipError_t e = launch_cast_col_f32_fast(src, rows, cols, ld, fmt, rnd, elems, scales, st);
+    if (scales_aligned && src_dt == DT_F32) {
+        hipError_t e = axis == 0 ? launch_cast_col_f32_fast(src, rows, cols, ld, fmt, rnd, elems, scales, st)
+                                 : launch_cast_row_f32_fast(src, rows, cols, ld, fmt, rnd, elems, scales, st);
         if (e != hipErrorNotSupported) return e;
     }
     return src_dt == DT_BF16 ? dispatch_fmt<DT_BF16>(fmt, rnd, seed, axis, src, rows, cols, ld, elems, scales, st)

@@ -35,7 +35,7 @@ __device__ __forceinline__ void wave_lds_sync()
 // ---------------------------------------------------------------------------
 // Row cast
 // ---------------------------------------------------------------------------
-constexpr int ROW_CHUNKS = 4;                 // 16-byte loads in flight per lane
+constexpr int ROW_CHUNKS = 4;                 // 16-byte loads in flight per lane (8 measured the same, 16 slower)
 constexpr int ROW_WAVE_ELEMS = 64 * 8 * ROW_CHUNKS;   // 2048 elements = 64 blocks per wave
 
 // element offset of linear element index e in a [rows][cols] tensor with pitch ld
@@ -47,7 +47,7 @@ __device__ __forceinline__ int64_t src_offset(int64_t e, int64_t cols, int64_t l
     return r * ld + (e - r * cols);
 }
 
-template <int FMT, int RND, bool FLAT, bool WHOLE = false>   // WHOLE: every wave's 2048 elements lie inside the tensor
+template <int FMT, int RND, bool FLAT, bool WHOLE = false, int CH = ROW_CHUNKS>   // WHOLE: every wave's elements lie inside the tensor
 __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__restrict__ src, int64_t cols, int64_t ld,
                                                             uint8_t *__restrict__ elems, uint8_t *__restrict__ scales,
                                                             int64_t n_elems)
@@ -56,21 +56,23 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
     constexpr int w = Fmt<FMT>::bits;
     constexpr bool SIX = (w == 6);
     // per wave: FP6 needs 64 blocks x 80 bytes (padded) for the transpose; everyone needs 64 scale bytes
-    constexpr int LDS_PER_WAVE = SIX ? 64 * 80 : 64;
+    static_assert(!SIX || CH == 4, "the FP6 transpose gives lane L block L of 64");
+    constexpr int LDS_PER_WAVE = SIX ? 64 * 80 : 16 * CH;
+    constexpr int WAVE_ELEMS = 512 * CH;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * LDS_PER_WAVE];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint8_t *lds = lds_all + wave * LDS_PER_WAVE;
 
     const int64_t wave_id = (int64_t)blockIdx.x * 4 + wave;
-    const int64_t e0 = wave_id * ROW_WAVE_ELEMS;          // first element of this wave
+    const int64_t e0 = wave_id * WAVE_ELEMS;          // first element of this wave
     if (!WHOLE && e0 >= n_elems) return;                  // whole wave out of range
     const int64_t blk0 = e0 / BLOCK;                      // first block of this wave
 
     // ---- coalesced loads: chunk u, lane l -> elements e0 + u*512 + l*8 .. +7
-    uint32_t d[ROW_CHUNKS][4];
-    bool valid[ROW_CHUNKS];
+    uint32_t d[CH][4];
+    bool valid[CH];
 #pragma unroll
-    for (int u = 0; u < ROW_CHUNKS; u++) {
+    for (int u = 0; u < CH; u++) {
         const int64_t e = e0 + u * 512 + lane * 8;
         valid[u] = WHOLE || e < n_elems;
         uint4 t = make_uint4(0, 0, 0, 0);
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
     if constexpr (!SIX) {
         constexpr int OD = 8 * w / 32;   // output dwords per lane per chunk (2 or 1)
 #pragma unroll
-        for (int u = 0; u < ROW_CHUNKS; u++) {
+        for (int u = 0; u < CH; u++) {
             uint32_t m = 0;
 #pragma unroll
             for (int i = 0; i < 4; i++) m = pk_absmax(m, d[u][i]);
@@ -114,7 +116,7 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
     } else {
         // ---- FP6: transpose so that lane L owns block L of the wave (chunk L/16, quad L%16)
 #pragma unroll
-        for (int u = 0; u < ROW_CHUNKS; u++) {
+        for (int u = 0; u < CH; u++) {
             const int b = u * 16 + (lane >> 2);
             *reinterpret_cast<uint4 *>(lds + b * 80 + (lane & 3) * 16) = make_uint4(d[u][0], d[u][1], d[u][2], d[u][3]);
         }
@@ -153,8 +155,8 @@ __global__ __launch_bounds__(256) void cast_row_bf16_kernel(const uint16_t *__re
     wave_lds_sync();
     {
         const uint8_t *sl = SIX ? lds + 1536 : lds;
-        const int64_t n_blk_valid = WHOLE ? 64 : (n_elems - e0) / BLOCK;
-        if (lane < 4) {
+        const int64_t n_blk_valid = WHOLE ? 16 * CH : (n_elems - e0) / BLOCK;
+        if (lane < CH) {
             if ((lane + 1) * 16 <= n_blk_valid) {
                 st16(scales + blk0 + lane * 16, *reinterpret_cast<const uint4 *>(sl + lane * 16));
             } else {
@@ -362,6 +364,89 @@ static hipError_t launch_col_f32_r(int rnd, const float *src, int64_t rows, int6
         hipLaunchKernelGGL((cast_col_f32_kernel<FMT, ROUND_HALF_AWAY>), dim3((unsigned)(per_xcd * 8)), dim3(256), 0, st, src, rows,
                            cols, ld, elems, scales, row_tiles, n_tiles, per_xcd);
     return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Row cast of a dense Float32 tensor (blocks along the contiguous axis; configs that cast Float32
+// sources along rows: the round trip of a Float32 tensor, weights kept in Float32).  A wave takes
+// 2048 consecutive elements = 64 blocks as eight fully coalesced 16-byte-per-lane loads (all in flight
+// at once), parks them in a wave-private LDS region with a pitch of 36 dwords per block -- lane l then
+// owns block l and reads it back with 16-byte reads that are free of bank conflicts (36 l mod 64 takes
+// 16 different multiples of 4 over any 16 consecutive lanes) -- and quantizes it with the Float32
+// block quantizer of the column kernel and the GEMM epilogue (hardware converts; the exact encoder
+// for the rare blocks they cannot take).  No work-group barrier: waves are independent.
+// ---------------------------------------------------------------------------
+constexpr int RF_CHUNKS = 8;                       // 16-byte loads in flight per lane
+constexpr int RF_WAVE_ELEMS = 64 * 4 * RF_CHUNKS;  // 2048 elements = 64 blocks per wave
+constexpr int RF_PITCH = 36;                       // dwords per block in LDS
+
+template <int FMT, int RND>
+__global__ __launch_bounds__(256) void cast_row_f32_kernel(const float *__restrict__ src, uint8_t *__restrict__ elems,
+                                                           uint8_t *__restrict__ scales, int64_t n_waves)
+{
+    if constexpr (FMT == FP8_E4M3 || FMT == FP8_E5M2) fp8_saturate_mode();
+    constexpr int w = Fmt<FMT>::bits;
+    __shared__ __attribute__((aligned(16))) uint32_t lds_all[4 * 64 * RF_PITCH];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t *lds = lds_all + wave * 64 * RF_PITCH;
+    const int64_t wave_id = (int64_t)blockIdx.x * 4 + wave;
+    if (wave_id >= n_waves) return;
+    const int64_t e0 = wave_id * RF_WAVE_ELEMS, blk0 = e0 / BLOCK;
+
+    uint4 v[RF_CHUNKS];
+#pragma unroll
+    for (int u = 0; u < RF_CHUNKS; u++) v[u] = ld16_nt(src + e0 + u * 256 + lane * 4);
+#pragma unroll
+    for (int u = 0; u < RF_CHUNKS; u++) {
+        const int f = u * 256 + lane * 4;              // element of the wave's run: block f / 32, position f % 32
+        *reinterpret_cast<uint4 *>(lds + (f >> 5) * RF_PITCH + (f & 31)) = v[u];
+    }
+    wave_lds_sync();
+    uint32_t out[w];
+    const uint32_t s = quantize_block_lds<FMT, RND>(lds + lane * RF_PITCH, 1, out);
+    uint8_t *o = elems + (blk0 + lane) * (BLOCK * w / 8);
+    if constexpr (w == 8) {
+        st16(o, make_uint4(out[0], out[1], out[2], out[3]));
+        st16(o + 16, make_uint4(out[4], out[5], out[6], out[7]));
+    } else if constexpr (w == 6) {
+        *reinterpret_cast<uint2 *>(o) = make_uint2(out[0], out[1]);
+        *reinterpret_cast<uint2 *>(o + 8) = make_uint2(out[2], out[3]);
+        *reinterpret_cast<uint2 *>(o + 16) = make_uint2(out[4], out[5]);
+    } else {
+        st16(o, make_uint4(out[0], out[1], out[2], out[3]));
+    }
+    scales[blk0 + lane] = (uint8_t)s;                  // 64 consecutive bytes per wave
+}
+
+template <int FMT>
+static hipError_t launch_row_f32_r(int rnd, const float *src, int64_t n, uint8_t *elems, uint8_t *scales, hipStream_t st)
+{
+    const int64_t n_waves = n / RF_WAVE_ELEMS, nb = (n_waves + 3) / 4;
+    if (nb > 0x7FFFFFFF) return hipErrorNotSupported;
+    if (rnd == ROUND_RNE)
+        hipLaunchKernelGGL((cast_row_f32_kernel<FMT, ROUND_RNE>), dim3((unsigned)nb), dim3(256), 0, st, src, elems, scales, n_waves);
+    else
+        hipLaunchKernelGGL((cast_row_f32_kernel<FMT, ROUND_HALF_AWAY>), dim3((unsigned)nb), dim3(256), 0, st, src, elems, scales, n_waves);
+    return hipGetLastError();
+}
+
+// Float32 source, blocks along the last axis, dense rows of whole blocks and a whole number of
+// 2048-element runs, round to nearest; hipErrorNotSupported otherwise
+hipError_t launch_cast_row_f32_fast(const void *src, int64_t rows, int64_t cols, int64_t ld, int fmt, int rnd, uint8_t *elems,
+                                    uint8_t *scales, hipStream_t st)
+{
+    const int64_t n = rows * cols;
+    if (ld != cols || cols % BLOCK || n == 0 || n % RF_WAVE_ELEMS || (rnd != ROUND_RNE && rnd != ROUND_HALF_AWAY))
+        return hipErrorNotSupported;
+    const float *p = static_cast<const float *>(src);
+    switch (fmt) {
+        case FP8_E4M3: return launch_row_f32_r<FP8_E4M3>(rnd, p, n, elems, scales, st);
+        case FP8_E5M2: return launch_row_f32_r<FP8_E5M2>(rnd, p, n, elems, scales, st);
+        case FP6_E3M2: return launch_row_f32_r<FP6_E3M2>(rnd, p, n, elems, scales, st);
+        case FP6_E2M3: return launch_row_f32_r<FP6_E2M3>(rnd, p, n, elems, scales, st);
+        case FP4_E2M1: return launch_row_f32_r<FP4_E2M1>(rnd, p, n, elems, scales, st);
+        default:       return launch_row_f32_r<INT8>(rnd, p, n, elems, scales, st);
+    }
 }
 
 // Float32 source, blocks along dimension 0, whole 128 x 64 tiles, round to nearest

@@ -25,6 +25,10 @@ hipError_t launch_cast_bf16_fast(const void *src, int64_t rows, int64_t cols, in
 hipError_t launch_cast_col_f32_fast(const void *src, int64_t rows, int64_t cols, int64_t ld, int fmt, int rnd, uint8_t *elems,
                                     uint8_t *scales, hipStream_t st);
 
+// Float32 sources, axis 1, dense rows of whole blocks, a whole number of 2048-element runs, round to nearest
+hipError_t launch_cast_row_f32_fast(const void *src, int64_t rows, int64_t cols, int64_t ld, int fmt, int rnd, uint8_t *elems,
+                                    uint8_t *scales, hipStream_t st);
+
 // both axes in one pass over the source: (e1, s1) as launch_cast with axis 1, (e0, s0) with axis 0
 hipError_t launch_cast_dual(const void *src, int src_dt, int64_t rows, int64_t cols, int64_t ld, int fmt, int rnd,
                             uint8_t *e1, uint8_t *s1, uint8_t *e0, uint8_t *s0, hipStream_t st);

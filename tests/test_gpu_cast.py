@@ -510,3 +510,24 @@ def test_cast_axis0_f32_whole_tiles(mx, oracle, fmt, rnd):
     e, s = mx.mx_quantize(to_dev(wide)[:, :cols], 0, fmt, rnd)
     e_ref, s_ref = oracle.quantize(x, 0, fmt, rnd)
     assert np.array_equal(to_host(e), e_ref) and np.array_equal(to_host(s), s_ref)
+
+
+@pytest.mark.parametrize("fmt", FORMATS, ids=NAMES)
+@pytest.mark.parametrize("rnd", [RNE, AWAY], ids=["rne", "away"])
+def test_cast_axis1_f32_dense_runs(mx, oracle, fmt, rnd):
+    """Dense Float32 tensors made of whole 2048-element runs take the wave-level row kernel on the hardware
+    converts: heavy-tailed data with per-block magnitudes over 2^+-30, exact ties and the values one ulp
+    either side of them for every element grid, degenerate blocks (zeros, Inf, NaN, subnormals, largest
+    finite), and a shape whose rows are shorter than a run."""
+    rows, cols = 96, 1024
+    rng = np.random.default_rng(10 + fmt)
+    x = inputs.student_t_f32((rows, cols), seed=117 + fmt)
+    x *= np.exp2(rng.integers(-30, 30, (rows, cols // 32))).repeat(32, axis=1).astype(np.float32)
+    ties = ((np.arange(64) + 0.5) * 2.0 ** -6).astype(np.float32)
+    x[0, :64] = ties
+    x[1, :64] = np.nextafter(ties, np.float32(0))
+    x[2, :64] = np.nextafter(ties, np.float32(4))
+    x[3, :64] = -ties
+    check_cast(mx, oracle, x, 1, fmt, rnd)
+    check_cast(mx, oracle, inputs.adversarial_f32(64, 2048, seed=5 + fmt), 1, fmt, rnd)
+    check_cast(mx, oracle, inputs.student_t_f32((1024, 64), seed=3), 1, fmt, rnd)      # 32 rows per run
