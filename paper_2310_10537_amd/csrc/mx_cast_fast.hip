@@ -310,22 +310,17 @@ __global__ __launch_bounds__(256) void cast_col_f32_kernel(const float *__restri
     const int t = threadIdx.x;
     const int64_t tile_id = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int64_t)(blockIdx.x >> 3) >= per_xcd || tile_id >= n_tiles) return;   // uniform over the work-group
-    int64_t ct, rt;
-    {
-        // groups of up to 8 adjacent column strips are walked strips-fastest, as in the bf16 kernel
-        const int64_t col_tiles = n_tiles / row_tiles;
-        const int64_t sg = (col_tiles & 7) == 0 ? 8 : (col_tiles & 3) == 0 ? 4 : (col_tiles & 1) == 0 ? 2 : 1;
-        const int64_t grp = tile_id / (sg * row_tiles), in = tile_id % (sg * row_tiles);
-        ct = grp * sg + in % sg;
-        rt = in / sg;
-    }
+    // strips one at a time, as in the bf16 kernel (several abreast cost 3 % with non-temporal loads)
+    const int64_t ct = tile_id / row_tiles, rt = tile_id % row_tiles;
     const int64_t c0 = ct * COL_TILE_C, r0 = rt * COL_TILE_R;
     const int lr = t >> 4, lc = t & 15;
+    uint4 v[COL_TILE_R / 16];
+#pragma unroll
+    for (int p = 0; p < COL_TILE_R / 16; p++) v[p] = ld16_nt(src + (r0 + p * 16 + lr) * ld + c0 + lc * 4);
 #pragma unroll
     for (int p = 0; p < COL_TILE_R / 16; p++) {
         const int r = p * 16 + lr;                    // row inside the tile; its 32-row block is r / 32
-        const uint4 v = ld16_nt(src + (r0 + r) * ld + c0 + lc * 4);
-        *reinterpret_cast<uint4 *>(tile + r * COL_TILE_C + ((lc * 4 + (r >> 5) * 16) & 63)) = v;
+        *reinterpret_cast<uint4 *>(tile + r * COL_TILE_C + ((lc * 4 + (r >> 5) * 16) & 63)) = v[p];
     }
     __syncthreads();
     const int c = t >> 2, rb = t & 3;
