@@ -895,3 +895,31 @@ def test_gemm_probe_is_the_same_product(mx, oracle, fa, fb):
     assert int(clk.min()) >= steps * (2048 if fa == 0 else 1024)          # matrix instructions alone
     ghz = clk.double().sum().item() / ticks.double().sum().item() * 0.1
     assert 0.3 < ghz < 3.0
+
+
+@pytest.mark.parametrize("fa,fb,shape", [(0, 0, (1280, 15360, 512)), (2, 4, (2560, 7680, 640)), (4, 1, (1024, 2048, 1024))],
+                         ids=["e4m3_300_tiles", "e3m2xe2m1_300_tiles", "e2m1xe5m2_32_tiles"])
+def test_whole_and_half_width_tiles_give_the_same_bits(mx, oracle, fa, fb, shape):
+    """Problems whose last round of 256 x 256 tiles is at most half full run their last tile columns as
+    256 x 128 tiles, and problems of at most 128 tiles run on those alone.  An entry's K chain does not
+    depend on the tile it lies in: the same columns computed inside a problem of another size (150 or 160
+    tiles: whole tiles only) have the same bits, and sampled entries match the reference."""
+    M, N, K = shape
+    a = to_dev(inputs.student_t_bf16((M, K), seed=81))
+    b = to_dev(inputs.gaussian_f32((N, K), seed=82, std=0.02))
+    ga, gb = mx.mx_quantize(a, 1, fa), mx.mx_quantize(b, 1, fb)
+    C = mx.mx_gemm(ga[0], ga[1], fa, gb[0], gb[1], fb, K)
+    if (M // 256) * (N // 256) > 128:
+        # 300 tiles = 255 whole + 90 half-width; each half of the columns alone is 150 whole tiles
+        for lo, hi in ((0, N // 2), (N // 2, N)):
+            part = mx.mx_gemm(ga[0], ga[1], fa, gb[0][lo:hi].contiguous(), gb[1][lo:hi].contiguous(), fb, K)
+            assert torch.equal(part.view(torch.int32), C[:, lo:hi].contiguous().view(torch.int32)), (lo, hi)
+    else:
+        # 32 tiles run as 64 half-width tiles; five copies of B side by side are 160 whole tiles
+        big = mx.mx_gemm(ga[0], ga[1], fa, gb[0].repeat(5, 1), gb[1].repeat(5, 1), fb, K)
+        for r in range(5):
+            assert torch.equal(big[:, r * N:(r + 1) * N].contiguous().view(torch.int32), C.view(torch.int32)), r
+    A = (to_host(ga[0]), to_host(ga[1]))
+    B = (to_host(gb[0]), to_host(gb[1]))
+    got, C_ref, C_abs, hw = sampled_check(mx, oracle, C, A, fa, B, fb, K, seed=83, n=512)
+    check_gemm(got, C_ref, C_abs, "whole + half-width tiles", hw)
