@@ -31,6 +31,9 @@ Also in the default run, per call and with the same protocol:
                    with its fraction of the HBM peak;
   "gemm_clock"     the shader clock during the headline GEMM and the clocks one K step takes, from
                    counters read inside the kernel (mx_gemm_probe), on the real operands and on zeros;
+  "mfma_instruction_ceiling"  what the GEMM's matrix instruction sustains from registers alone on
+                   the headline GEMM's MX-quantized operand values (mx_mfma_stream_probe), per element width
+                   and on zeros: the power-limited ceiling of the instruction on such operand values;
   "gemm_zero_operands"  the headline GEMM launch on all-zero operands: what the same kernel
                    does when operand switching activity does not hold the clock down;
   "vendor_reference_8192x4096x4096"  context only: the vendor library's FP8 GEMM (one scale per tensor) and
@@ -116,11 +119,37 @@ def clock_probe(A, fmtA, B, fmtB, K, C, mfma_clocks_per_step, n=6):
             "k_loop_us_per_tile": round(float(ticks.mean()) / 100.0, 2)}
 
 
+def instruction_ceiling(a_bf16):
+    """What the GEMM kernels' matrix instruction sustains on this machine from registers alone
+    (mx_mfma_stream_probe: four waves per compute unit, no memory access in the loop), with the A
+    registers holding MX-quantized activations of the headline GEMM and the B registers MX-quantized
+    weights drawn like its weights, per element width, and on zeros: the chip's power limit holds the
+    clock down as operand switching activity rises, so this, not the nominal peak, is what a kernel
+    that fed the instruction perfectly would reach on such operand values."""
+    out = {}
+    a = a_bf16[:256].contiguous()
+    w = torch.from_numpy(inputs.gaussian_f32((256, GK), seed=103, std=0.02)).cuda()
+    for name, fmt, iters, zero in (("fp8_e4m3", mx.FP8_E4M3, 2000, False), ("fp6_e3m2", mx.FP6_E3M2, 4000, False),
+                                   ("fp4_e2m1", mx.FP4_E2M1, 4000, False), ("fp8_e4m3_zero_operands", mx.FP8_E4M3, 2000, True)):
+        codes = torch.cat([mx.mx_quantize(t, 1, fmt)[0].reshape(-1)[:32768] for t in (a, w)]).contiguous()
+        if zero:
+            codes.zero_()
+        res = []
+        ms = time_call(lambda: res.append(mx.mx_mfma_stream_probe(fmt, codes, iters)), 5)
+        clk, ticks = res[-1]
+        flop = mx.MX_MFMA_STREAM_WGS * 4 * 16.0 * iters * 131072
+        tf = flop / ms / 1e9
+        out[name] = {"TFLOPs": round(tf, 1), "frac_mfma_peak": round(tf / MFMA_PEAK_TFLOPS[mx.FORMAT_BITS[fmt]], 4),
+                     "shader_GHz": round(float(clk.double().sum() / ticks.double().sum()) * 0.1, 3)}
+    return out
+
+
 def vendor_reference(n):
     """Context, not a target and no part of the product: the vendor library's FP8 GEMMs (through
     torch._scaled_mm) on the same box and shape as the headline GEMM, on N(0,1) x N(0,1) operands --
-    with one scale per tensor (no MX blocks) and with E8M0 scales per 32 elements (the MX product).
-    None where this torch build does not offer the call."""
+    with one scale per tensor (no MX blocks) and with E8M0 scales per 32 elements (the MX product) --
+    and this library's mx_gemm on the same operand bytes with unit scales, since the operands'
+    switching activity sets the clock.  None where this torch build does not offer the call."""
     out = {}
     M, N, K = GM, GN, GK
     g = torch.Generator(device="cuda")
@@ -134,6 +163,12 @@ def vendor_reference(n):
         out["fp8_one_scale_per_tensor_TFLOPs"] = round(flop / ms / 1e9, 1)
     except Exception:                      # noqa: BLE001  (an unsupported call is reported as absent)
         out["fp8_one_scale_per_tensor_TFLOPs"] = None
+    # this library's MX GEMM on the very same operand bytes (every scale byte 127: X = 1)
+    s_a = torch.full((M, K // 32), 127, dtype=torch.uint8, device="cuda")
+    s_b = torch.full((N, K // 32), 127, dtype=torch.uint8, device="cuda")
+    c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    ms = time_call(lambda: mx.mx_gemm(a.view(torch.uint8), s_a, mx.FP8_E4M3, b.view(torch.uint8), s_b, mx.FP8_E4M3, K, out=c), n)
+    out["this_library_same_operands_TFLOPs"] = round(flop / ms / 1e9, 1)
     try:
         sa = torch.full((M, K // 32), 127, dtype=torch.uint8, device="cuda").view(torch.float8_e8m0fnu)
         sb = torch.full((N, K // 32), 127, dtype=torch.uint8, device="cuda").view(torch.float8_e8m0fnu)
@@ -580,6 +615,7 @@ def main():
         "gemm_zero_operands": {"avg_ms": round(zero_ms, 5), "TFLOPs": round(flop / zero_ms / 1e9, 1),
                                "frac_mfma_peak": round(flop / zero_ms / 1e9 / MFMA_PEAK_TFLOPS[8], 4)},
         "gemm_clock": gemm_clock,
+        "mfma_instruction_ceiling": instruction_ceiling(As[0]),
         "kernels": per_kernel,
     }
     del xs, As, Aq, Cs, outs, deq_out, deq_in, Be, Bs

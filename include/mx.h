@@ -405,6 +405,25 @@ int mx_gemm_probe(int64_t M, int64_t N, int64_t K,
                   void *C_bf16, int64_t ldc,
                   uint64_t *probe, int64_t probe_len, void *hip_stream);
 
+/*
+ * Measurement aid (no part of the MX path): the matrix instruction of mx_gemm's
+ * kernels on its own.  MX_MFMA_STREAM_WGS work-groups of four waves (one per
+ * compute unit) each issue 16 * iters scaled 32 x 32 x 64 instructions of the
+ * pair fmt x fmt (an FP8 / FP6 / FP4 format, else MX_ERR_UNSUPPORTED) on operand
+ * registers loaded once from `codes` -- 65536 bytes of device memory, 32-byte
+ * aligned: eight fragments of 256 lanes x 32 bytes, of which the narrower formats
+ * use the first 24 / 16 -- with unit scales and 256 accumulator registers per
+ * lane, and touch no memory inside the loop: what the instruction sustains on
+ * these operand values under the chip's power limit, whatever feeds it.  A launch
+ * performs MX_MFMA_STREAM_WGS * 4 * 16 * iters * 131072 flops.  Every work-group
+ * writes (shader clocks, ticks of the constant 100 MHz counter) to probe[2*g],
+ * probe[2*g + 1] (2 * MX_MFMA_STREAM_WGS entries) and each lane a checksum to
+ * sink (MX_MFMA_STREAM_WGS * 256 floats); iters in [1, 2^20] (else MX_ERR_SHAPE).
+ */
+#define MX_MFMA_STREAM_WGS 256
+int mx_mfma_stream_probe(mx_format_t fmt, const void *codes, int iters,
+                         float *sink, uint64_t *probe, void *hip_stream);
+
 /* Static, human-readable text for a status code. */
 const char *mx_strerror(int status);
 

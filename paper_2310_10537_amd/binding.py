@@ -63,6 +63,7 @@ def lib() -> ctypes.CDLL:
         L.mx_quantize_3d.argtypes = [vp, ci, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, vp, vp]
         L.mx_stream_pattern.argtypes = [vp, vp, i64, ci, ci, vp]
         L.mx_gemm_probe.argtypes = [i64, i64, i64, vp, vp, ci, vp, vp, ci, vp, i64, vp, i64, vp]
+        L.mx_mfma_stream_probe.argtypes = [ci, vp, ci, vp, vp, vp]
         L.mx_strerror.argtypes = [ci]
         L.mx_strerror.restype = ctypes.c_char_p
         _lib = L
@@ -333,6 +334,21 @@ def mx_gemm_probe(A_elems, A_scales, fmtA, B_elems, B_scales, fmtB, K, out, stre
                                out.data_ptr(), out.stride(0), probe.data_ptr(), probe.numel(), _stream(stream)))
     ran = probe[:, 1] > 0
     return probe[ran, 0], probe[ran, 1]
+
+
+MX_MFMA_STREAM_WGS = 256
+
+
+def mx_mfma_stream_probe(fmt, codes, iters, stream=None):
+    """Measurement aid: the GEMM kernels' matrix instruction alone, from registers filled with the first 64 KiB
+    of `codes` (uint8, device).  Returns (shader clocks, 100 MHz ticks) per work-group as two int64 tensors;
+    one launch performs MX_MFMA_STREAM_WGS * 4 * 16 * iters * 131072 flops."""
+    _dev(codes, "codes")
+    assert codes.dtype == torch.uint8 and codes.is_contiguous() and codes.numel() >= 65536
+    probe = torch.zeros((MX_MFMA_STREAM_WGS, 2), dtype=torch.int64, device=codes.device)
+    sink = torch.empty((MX_MFMA_STREAM_WGS * 256,), dtype=torch.float32, device=codes.device)
+    _check(lib().mx_mfma_stream_probe(fmt, codes.data_ptr(), iters, sink.data_ptr(), probe.data_ptr(), _stream(stream)))
+    return probe[:, 0], probe[:, 1]
 
 
 def mx_dequantize_3d(elems, scales, fmt, shape, axis, keep_order=False, dtype=torch.float32, out=None, stream=None):

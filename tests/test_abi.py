@@ -26,7 +26,7 @@ def test_exports_match_header(L):
     assert names == {"mx_elem_bytes", "mx_scale_bytes", "mx_quantize", "mx_quantize_sr", "mx_quantize_dual", "mx_quantize_3d", "mx_dequantize", "mx_gemm",
                      "mx_gemm_qa", "mx_gemm_q", "mx_gemm_qa_noalloc", "mx_stream_pattern", "mx_strerror",
                      "mx_gemm_workspace_bytes", "mx_gemm_qa_workspace_bytes", "mx_gemm_q_workspace_bytes", "mx_gemm_ws", "mx_gemm_qa_ws",
-                     "mx_gemm_q_ws", "mx_gemm_probe", "mx_dequantize_3d"}
+                     "mx_gemm_q_ws", "mx_gemm_probe", "mx_mfma_stream_probe", "mx_dequantize_3d"}
     for n in names:
         assert hasattr(L, n), n
 
@@ -169,6 +169,16 @@ def test_gemm_probe_validation(L):
     assert L.mx_gemm_probe(*args(512, 512, 256, 0, 0, 64)) == 3
     assert L.mx_gemm_probe(*args(512, 512, 512, 0, 0, 8)) == 3           # probe buffer too short
     assert L.mx_gemm_probe(512, 512, 512, p, p, 0, p, p, 0, p, 512, None, 64, None) == 1
+
+
+def test_mfma_stream_probe_validation(L):
+    p = 0x1000
+    f = L.mx_mfma_stream_probe
+    assert f(5, p, 10, p, p, None) == 5          # INT8 has no such instruction
+    assert f(0, p, 0, p, p, None) == 3
+    assert f(0, p, (1 << 20) + 1, p, p, None) == 3
+    assert f(0, None, 10, p, p, None) == 1
+    assert f(0, p + 16, 10, p, p, None) == 4     # operand registers are loaded 32 bytes at a time
 
 
 def test_dequantize_3d_validation(L):

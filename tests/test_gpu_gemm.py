@@ -897,6 +897,20 @@ def test_gemm_probe_is_the_same_product(mx, oracle, fa, fb):
     assert 0.3 < ghz < 3.0
 
 
+@pytest.mark.parametrize("fmt", [0, 1, 2, 3, 4], ids=["e4m3", "e5m2", "e3m2", "e2m3", "e2m1"])
+def test_mfma_stream_probe_counts_its_instructions(mx, fmt):
+    """The instruction-only measurement aid: every work-group reports a run at least as long as its
+    16 * iters matrix instructions (64 clocks each for 8-bit operands, 32 for narrower ones)."""
+    a = to_dev(inputs.student_t_bf16((256, 1024), seed=91))
+    codes = mx.mx_quantize(a, 1, fmt)[0].reshape(-1)[:65536].contiguous()
+    iters = 50
+    clk, ticks = mx.mx_mfma_stream_probe(fmt, codes, iters)
+    torch.cuda.synchronize()
+    assert clk.numel() == mx.MX_MFMA_STREAM_WGS and int(ticks.min()) > 0
+    assert int(clk.min()) >= 16 * iters * (64 if fmt <= 1 else 32)
+    assert int(clk.max()) < 16 * iters * 64 * 20
+
+
 @pytest.mark.parametrize("fa,fb,shape", [(0, 0, (1280, 15360, 512)), (2, 4, (2560, 7680, 640)), (4, 1, (1024, 2048, 1024))],
                          ids=["e4m3_300_tiles", "e3m2xe2m1_300_tiles", "e2m1xe5m2_32_tiles"])
 def test_whole_and_half_width_tiles_give_the_same_bits(mx, oracle, fa, fb, shape):
