@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libmx.so")
 SOURCES = ["mx_api.hip", "mx_pattern.hip", "mx_cast.hip", "mx_cast_3d.hip", "mx_cast_fast.hip", "mx_cast_dual.hip", "mx_dequant.hip", "mx_dequant_3d.hip", "mx_gemm.hip", "mx_gemm_int8.hip", "mx_gemm_skinny.hip", "mx_gemm_tile_a8.hip",
-           "mx_gemm_tile_a6.hip", "mx_gemm_tile_a4.hip", "mx_gemm_tile8_a6.hip", "mx_gemm_tile8_a4.hip", "mx_gemm_probe.hip", "mx_gemm_tileh_a8.hip", "mx_gemm_tileh_a6.hip", "mx_gemm_tileh_a4.hip"]
+           "mx_gemm_tile_a6.hip", "mx_gemm_tile_a4.hip", "mx_gemm_tile16_a8.hip", "mx_gemm_tile8_a6.hip", "mx_gemm_tile8_a4.hip", "mx_gemm_probe.hip", "mx_gemm_tileh_a8.hip", "mx_gemm_tileh_a6.hip", "mx_gemm_tileh_a4.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

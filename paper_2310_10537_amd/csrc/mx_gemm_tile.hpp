@@ -629,6 +629,8 @@ static hipError_t launch_a(const TileArgs &a, int fmtB)
 hipError_t launch_gemm_tiled_a8(const TileArgs &a, int fmtA, int fmtB);
 hipError_t launch_gemm_tiled_a6(const TileArgs &a, int fmtA, int fmtB);
 hipError_t launch_gemm_tiled_a4(const TileArgs &a, int fmtA, int fmtB);
+// pairs of 8-bit formats on the 16 x 16 x 128 instruction (mx_gemm_tile16.hpp; plain operands, Float32 / bf16 output)
+hipError_t launch_gemm_tiled16_a8(const TileArgs &a, int fmtA, int fmtB);
 // the eight-wave form of the kernel (plain operands, Float32 / bf16 output), same split
 hipError_t launch_gemm_tiled8_a6(const TileArgs &a, int fmtA, int fmtB);
 hipError_t launch_gemm_tiled8_a4(const TileArgs &a, int fmtA, int fmtB);
