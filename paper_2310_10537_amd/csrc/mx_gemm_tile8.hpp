@@ -141,18 +141,45 @@ __global__ __launch_bounds__(64 * NW8, 1) void gemm_tile8_kernel(int64_t M, int6
             asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(vS), "s"(p1), "s"(l0 + NW8 * 1024) : "m0");
         }
     };
-    auto read_scales = [&](int ts) {
+    // Scale bytes.  A row's 16-byte LDS slot holds the dwords of the four K steps of a scale group.  Reading
+    // one dword per step from 32 consecutive slots conflicts four ways (16-byte pitch: 16 banks for 32 rows,
+    // and the two half-waves do not merge), a quarter of this kernel's LDS cycles; so a group's slots are
+    // read whole, 16 bytes per row block and conflict-free, once per group, and a step takes its dword from
+    // registers.  The registers of a group are dead once the dwords of its last step have been taken (one
+    // step ahead), which is when the next group's are read into them.
+    u32x4_t qa4[4], qb4[2];
+    auto read_group = [&](int ts) {          // the group holding K step ts (clamped to the last step)
         ts = ts < T ? ts : T - 1;
-        const uint8_t *src = scl + ((ts / SCL_GROUP) & 1) * SCL_BYTES + scl_ofs(ts);
+        const uint8_t *src = scl + ((ts / SCL_GROUP) & 1) * SCL_BYTES;
+#pragma unroll
+        for (int x = 0; x < 4; x++) qa4[x] = *reinterpret_cast<const u32x4_t *>(src + rsa + x * 512);
+#pragma unroll
+        for (int y = 0; y < 2; y++) qb4[y] = *reinterpret_cast<const u32x4_t *>(src + rsb + y * 512);
+    };
+    // dword d (0..3, a literal wherever the steps are unrolled) of the group in registers -> next step's scales
+    auto take_scales = [&](int d) {
 #pragma unroll
         for (int x = 0; x < 4; x++) {
-            const uint32_t da = *reinterpret_cast<const uint32_t *>(src + rsa + x * 512);
+            const uint32_t da = d == 0 ? qa4[x][0] : d == 1 ? qa4[x][1] : d == 2 ? qa4[x][2] : qa4[x][3];
             sa_n[x] = g ? da >> 8 : da;
         }
 #pragma unroll
         for (int y = 0; y < 2; y++) {
-            const uint32_t db = *reinterpret_cast<const uint32_t *>(src + rsb + y * 512);
+            const uint32_t db = d == 0 ? qb4[y][0] : d == 1 ? qb4[y][1] : d == 2 ? qb4[y][2] : qb4[y][3];
             sb_n[y] = g ? db >> 8 : db;
+        }
+    };
+    // The scales of step t+1, taken during step t = tt + h.  In the unrolled loop over whole groups (MAIN, h
+    // a literal) the dword number is h + 1 for the first three steps; the fourth reads the group that step
+    // tt + 4 belongs to (the next whole one, the partial last one, or -- behind the last step -- its own
+    // again) and takes that step's dword, whose number only the run-time K decides.
+    auto next_scales = [&](const int tt, const int h, const bool MAIN) __attribute__((always_inline)) {
+        if (MAIN && h < SCL_GROUP - 1) {
+            take_scales(h + 1);
+        } else {
+            const int ts = tt + h + 1 < T ? tt + h + 1 : T - 1;
+            if (MAIN) read_group(ts);
+            take_scales(scl_ofs(ts) >> 2);
         }
     };
 #define MX8_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -173,14 +200,15 @@ __global__ __launch_bounds__(64 * NW8, 1) void gemm_tile8_kernel(int64_t M, int6
     for (int x = 0; x < 4; x++) af[x] = read_frag<WA>(lds, ra0, 0, x);
 #pragma unroll
     for (int y = 0; y < 2; y++) b0[y] = read_frag<WB>(lds + A_BYTES, rb0, 0, y);
-    read_scales(0);
+    read_group(0);
+    take_scales(0);
 #pragma unroll
     for (int x = 0; x < 4; x++) sa[x] = sa_n[x];
 #pragma unroll
     for (int y = 0; y < 2; y++) sb[y] = sb_n[y];
 
     int ring = 0;
-    auto k_step = [&](const int tt, const int h) __attribute__((always_inline)) {
+    auto k_step = [&](const int tt, const int h, const bool MAIN) __attribute__((always_inline)) {
         const int t = tt + h;
         const int cur = NSTAGE == 2 ? (h & 1) : ring;
         uint8_t *bufA = lds + cur * STAGE_BYTES;
@@ -224,7 +252,7 @@ __global__ __launch_bounds__(64 * NW8, 1) void gemm_tile8_kernel(int64_t M, int6
         af[1] = read_frag<WA>(nxt, ra0, 0, 1);
         MX8_FENCE();
         if (h == 0) stage_scales(tt / SCL_GROUP + 1);
-        read_scales(t + 1);
+        next_scales(tt, h, MAIN);
         stage_one(4, t2, bufA, bufB); MX8_MFMA(af, b1, 2, 0, 2); MX8_FENCE();
         stage_one(5, t2, bufA, bufB); MX8_MFMA(af, b1, 2, 1, 2);
         af[2] = read_frag<WA>(nxt, ra0, 0, 2);
@@ -242,10 +270,10 @@ __global__ __launch_bounds__(64 * NW8, 1) void gemm_tile8_kernel(int64_t M, int6
     };
     for (int tt = 0; tt < Tfull; tt += SCL_GROUP) {
 #pragma unroll
-        for (int h = 0; h < SCL_GROUP; h++) k_step(tt, h);
+        for (int h = 0; h < SCL_GROUP; h++) k_step(tt, h, true);
     }
 #pragma unroll 1
-    for (int h = 0; h < T - Tfull; h++) k_step(Tfull, h);
+    for (int h = 0; h < T - Tfull; h++) k_step(Tfull, h, false);
 #undef MX8_MFMA
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if constexpr (PROBE) {
