@@ -90,7 +90,7 @@ def measured_traffic():
             continue
     n_elem = ROWS * COLS
     want = {"dequantize_fp8_e4m3_bf16": ("dequant_flat_kernel<0, 1>", n_elem * (1.0 + 1.0 / 32.0 + 2.0)),
-            "gemm_fp8_e4m3": ("gemm_tile_kernel<0, 0, 1, false", (GM + GN) * GK * (1.0 + 1.0 / 32.0) + GM * GN * 2.0)}
+            "gemm_fp8_e4m3": ("gemm_tile16_kernel<0, 0, 1, false", (GM + GN) * GK * (1.0 + 1.0 / 32.0) + GM * GN * 2.0)}
     for fmt in range(6):
         for kname, axis in (("cast_row_bf16_kernel<%d, 0," % fmt, 1), ("cast_col_bf16_kernel<%d, 0," % fmt, 0)):
             want[f"cast_{mx.FORMAT_NAMES[fmt]}_axis{axis}"] = (kname, cast_bytes(fmt, n_elem))
