@@ -17,8 +17,13 @@ hipError_t probe4(int64_t M, int64_t N, int64_t K, const uint8_t *Ae, const uint
 {
     const int tiles_m = (int)(M / TM), tiles_n = (int)(N / TN);
     const Raster rast = choose_raster(tiles_m, tiles_n, Fmt<FA>::bits, Fmt<FB>::bits);
-    hipLaunchKernelGGL((gemm_tile16_kernel<FA, FB, DT_BF16, true>), dim3(raster_grid(rast, tiles_m, tiles_n)), dim3(256), 0, st, M, N, K, Ae,
-                       As, Be, Bs, C, ldc, tiles_m, tiles_n, rast, probe);
+    if (K >= 1024)      // as mx_gemm picks them
+        hipLaunchKernelGGL((gemm_tile16_kernel<FA, FB, DT_BF16, true>), dim3(raster_grid(rast, tiles_m, tiles_n)), dim3(256), 0, st, M, N, K,
+                           Ae, As, Be, Bs, C, ldc, tiles_m, tiles_n, rast, probe);
+    else
+        hipLaunchKernelGGL((gemm_tile_kernel<FA, FB, DT_BF16, false, ROUND_RNE, true>), dim3(raster_grid(rast, tiles_m, tiles_n)), dim3(256),
+                           0, st, M, N, K, Ae, As, static_cast<const uint16_t *>(nullptr), (int64_t)0, Be, Bs, C, ldc, tiles_m, tiles_n,
+                           static_cast<uint8_t *>(nullptr), 0, rast, probe);
     return hipGetLastError();
 }
 

@@ -61,7 +61,13 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
     typedef TileFmt<8> TF;
     constexpr int A_BYTES = TM * TF::ROW, B_BYTES = TN * TF::ROW, STAGE_BYTES = A_BYTES + B_BYTES;
     // {A tile, B tile} x two stages, then {A scale dwords, B scale dwords} x two groups
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * STAGE_BYTES + 2 * SCL_BYTES];
+    // Scale bytes travel in groups of eight K steps: 32 bytes per row, fetched by two lanes, so a wave-wide
+    // load touches 32 cache lines.  The load path's cost is per line, and with 16 bytes per row (64 lines
+    // per load, one load pair per four steps) the scale loads took 260 clocks per K step, 9 % of the loop,
+    // for 3 % of its bytes; the 160 KB of LDS have room for exactly this doubling, no more.
+    constexpr int SG = 8, SG_ROW = 4 * SG, SG_BYTES = (TM + TN) * SG_ROW;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * STAGE_BYTES + 2 * SG_BYTES];
+    static_assert(sizeof(lds) <= 160 * 1024, "LDS of a compute unit");
     constexpr int HA = hw_fmt(FA), HB = hw_fmt(FB);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -72,8 +78,9 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
     if (!raster_tile(rast, (int)blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
     const int64_t m0 = (int64_t)tm * TM, n0 = (int64_t)tn * TN;
     const int64_t nkb = K / BLOCK;
-    const int T = (int)(K / TK);                  // K steps; at least 4
-    const int Tfull = T & ~(SCL_GROUP - 1);
+    const int T = (int)(K / TK);                  // K steps; at least 8
+    const int Tfull = T & ~3;                     // the loop below takes four steps per trip
+    const int Tg = T & ~(SG - 1);                 // steps in whole scale groups; the rest form a last, partial group
 
     // ---- staging map (as in gemm_tile_kernel): wave w, load j fills rows (4j + w) * 8 .. + 7; lane l
     // writes slot l % 8 of row l / 8 of that group and fetches the chunk the swizzle keeps there
@@ -82,13 +89,15 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
     const uint8_t *gA = Ae + (m0 + wave * TF::RPI + s_r) * K + s_u * TF::UNIT;
     const uint8_t *gB = Be + (n0 + wave * TF::RPI + s_r) * K + s_u * TF::UNIT;
     const int st_l = wave * 1024;
-    const uint8_t *sA = As + (m0 + wave * 64 + lane) * nkb;
-    const uint8_t *sB = Bs + (n0 + wave * 64 + lane) * nkb;
+    // scale staging: wave w fetches the rows 64w .. 64w+63 of A and of B, 32 rows per load, lane l the
+    // half l % 2 of row l / 2
+    const uint8_t *sA = As + (m0 + wave * 64 + (lane >> 1)) * nkb + (lane & 1) * 16;
+    const uint8_t *sB = Bs + (n0 + wave * 64 + (lane >> 1)) * nkb + (lane & 1) * 16;
     // ---- operand reads: tile row wm*128 + 16x + i (A) / wn*128 + 16y + i (B), chunks q and q + 4
     const int ra0 = (wm * 128 + i) * 128 + ((q ^ ((i >> 1) & 7)) << 4);
     const int rb0 = (wn * 128 + i) * 128 + ((q ^ ((i >> 1) & 7)) << 4);
     // ---- scale reads: byte q of the step's dword of the same rows
-    const int rsa = (wm * 128 + i) * 16 + q, rsb = TM * 16 + (wn * 128 + i) * 16 + q;
+    const int rsa = (wm * 128 + i) * SG_ROW + q, rsb = TM * SG_ROW + (wn * 128 + i) * SG_ROW + q;
 
     v4f_t acc[8][8];
 #pragma unroll
@@ -115,15 +124,22 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
         else stage_b1(ts, dstB, k - NJ);
     };
     uint8_t *const scl = lds + 2 * STAGE_BYTES;
-    const int n_groups = (T + SCL_GROUP - 1) / SCL_GROUP;
-    auto scl_ofs = [&](int ts) { return ts < Tfull ? (ts & (SCL_GROUP - 1)) * 4 : (ts - (T - SCL_GROUP)) * 4; };
+    const int n_groups = (T + SG - 1) / SG;
+    // Byte offset, inside a row's 32-byte LDS slot, of the scale dword of K step ts.  The partial last group
+    // is loaded as the row's LAST 32 scale bytes (steps T-8 .. T-1), so that the load never reaches past the
+    // row, and its steps sit further back in the slot accordingly.
+    auto scl_ofs = [&](int ts) { return ts < Tg ? (ts & (SG - 1)) * 4 : (ts - (T - SG)) * 4; };
+    // scale bytes of K steps 8G .. 8G+7 (group G, clamped to the last) into slot G & 1: A rows, then B rows
     auto stage_scales = [&](int G) {
         G = G < n_groups ? G : n_groups - 1;
-        const uint32_t l0 = lds0 + 2 * STAGE_BYTES + (G & 1) * SCL_BYTES;
-        const int64_t src_ofs = G * SCL_GROUP + SCL_GROUP <= T ? (int64_t)G * 16 : (int64_t)T * 4 - 16;
-        const uint8_t *pa = sA + src_ofs, *pb = sB + src_ofs;
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pa), "s"(l0) : "m0");
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pb), "s"(l0 + TM * 16) : "m0");
+        const uint32_t l0 = lds0 + 2 * STAGE_BYTES + (G & 1) * SG_BYTES + wave * (64 * SG_ROW - 1024);   // lds0 holds wave * 1024
+        const int64_t src_ofs = G * SG + SG <= T ? (int64_t)G * SG_ROW : (int64_t)T * 4 - SG_ROW;
+#pragma unroll
+        for (int j = 0; j < 2; j++) {
+            const uint8_t *pa = sA + src_ofs + j * 32 * nkb, *pb = sB + src_ofs + j * 32 * nkb;
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pa), "s"(l0 + j * 1024) : "m0");
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pb), "s"(l0 + TM * SG_ROW + j * 1024) : "m0");
+        }
     };
     // fragment of 16-row block xb of the tile at buf
     auto frag = [&](const uint8_t *buf, int ofs, int xb) {
@@ -139,15 +155,15 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
     // byte offset, from the scale area, of the dword row 0 holds for K step ts (clamped to the last step)
     auto scale_ofs = [&](int ts) {
         ts = ts < T ? ts : T - 1;
-        return ((ts / SCL_GROUP) & 1) * SCL_BYTES + scl_ofs(ts);
+        return ((ts / SG) & 1) * SG_BYTES + scl_ofs(ts);
     };
     auto read_sa = [&](int so, int x0) {
 #pragma unroll
-        for (int x = 0; x < 4; x++) sa[x0 + x] = scl[so + rsa + (x0 + x) * 256];
+        for (int x = 0; x < 4; x++) sa[x0 + x] = scl[so + rsa + (x0 + x) * (16 * SG_ROW)];
     };
     auto read_sb = [&](int so, int y0) {
 #pragma unroll
-        for (int y = 0; y < 4; y++) sb[y0 + y] = scl[so + rsb + (y0 + y) * 256];
+        for (int y = 0; y < 4; y++) sb[y0 + y] = scl[so + rsb + (y0 + y) * (16 * SG_ROW)];
     };
 
 #define MX_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -221,7 +237,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
         // one behind the barrier are refilled for step t+1 in the last quadrant; the other halves follow in
         // the first quadrant of step t+1, see below)
         if ((h & 1) == 0) {
-            MX_QUAD_LOAD(aH, bH, 4, 4, aL, nxtA, ra0, 0, 0, t2, dA, dB, if (h == 0) stage_scales(tt / SCL_GROUP + 1));
+            MX_QUAD_LOAD(aH, bH, 4, 4, aL, nxtA, ra0, 0, 0, t2, dA, dB, if (h == 0 && (tt & 4) == 0) stage_scales(tt / SG + 1));
             MX_QUAD_LOAD(aH, bL, 4, 0, bH, nxtB, rb0, 4, 8, t2, dA, dB, read_sa(so1, 0); read_sb(so1, 4));
         } else {
             MX_QUAD_LOAD(aH, bL, 4, 0, aL, nxtA, ra0, 0, 0, t2, dA, dB, (void)0);
@@ -229,16 +245,16 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
         }
         MX_FENCE();
     };
-    // whole scale groups: the four steps read dwords 0..3 of the group's slot; only the step after the
-    // group needs the general rule
-    for (int tt = 0; tt < Tfull; tt += SCL_GROUP) {
-        const int so = ((tt / SCL_GROUP) & 1) * SCL_BYTES, so4 = scale_ofs(tt + SCL_GROUP);
+    // four steps per trip: a trip never straddles a scale group, so its steps read consecutive dwords of one
+    // slot; only the step after the trip needs the general rule
+    for (int tt = 0; tt < Tfull; tt += 4) {
+        const int so = scale_ofs(tt), so4 = scale_ofs(tt + 4);
         k_step(tt, 0, so, so + 4);
         k_step(tt, 1, so + 4, so + 8);
         k_step(tt, 2, so + 8, so + 12);
         k_step(tt, 3, so + 12, so4);
     }
-    // the partial last group (Tfull is a multiple of four: the parity of a step is that of h)
+    // the last one to three steps (Tfull is a multiple of four: the parity of a step is that of h)
     if (T - Tfull > 0) k_step(Tfull, 0, scale_ofs(Tfull), scale_ofs(Tfull + 1));
     if (T - Tfull > 1) k_step(Tfull, 1, scale_ofs(Tfull + 1), scale_ofs(Tfull + 2));
     if (T - Tfull > 2) k_step(Tfull, 2, scale_ofs(Tfull + 2), scale_ofs(Tfull + 3));

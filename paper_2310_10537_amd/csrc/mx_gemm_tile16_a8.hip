@@ -12,7 +12,7 @@ static hipError_t launch_pair16(const TileArgs &a)
 
 hipError_t launch_gemm_tiled16_a8(const TileArgs &a, int fmtA, int fmtB)
 {
-    if (a.Abf || (a.c_dt != DT_F32 && a.c_dt != DT_BF16)) return hipErrorNotSupported;
+    if (a.Abf || (a.c_dt != DT_F32 && a.c_dt != DT_BF16) || a.K < 1024) return hipErrorNotSupported;
     if (fmtA == FP8_E4M3) return fmtB == FP8_E4M3 ? launch_pair16<FP8_E4M3, FP8_E4M3>(a) : launch_pair16<FP8_E4M3, FP8_E5M2>(a);
     return fmtB == FP8_E4M3 ? launch_pair16<FP8_E5M2, FP8_E4M3>(a) : launch_pair16<FP8_E5M2, FP8_E5M2>(a);
 }

@@ -15,11 +15,11 @@ bool gemm_tiled_applies(int64_t M, int64_t N, int64_t K, int fmtA, int fmtB)
 
 bool gemm_tiled_fuses_cast(int fmtA, int fmtB) { return fmtA <= FP8_E5M2 && fmtB <= FP8_E5M2; }
 
-// whole 256 x 256 tiles: four waves, on the 16 x 16 x 128 instruction for plain pairs of 8-bit formats
-// (mx_gemm_tile16.hpp), or eight waves for pairs without an 8-bit operand (mx_gemm_tile8.hpp)
+// whole 256 x 256 tiles: four waves, on the 16 x 16 x 128 instruction for plain pairs of 8-bit formats with
+// K >= 1024 (mx_gemm_tile16.hpp: its scale bytes travel in groups of eight K steps), or eight waves for pairs without an 8-bit operand (mx_gemm_tile8.hpp)
 static hipError_t launch_whole(const TileArgs &a, int fmtA, int fmtB)
 {
-    if (!a.Abf && fmtA <= FP8_E5M2 && fmtB <= FP8_E5M2) return launch_gemm_tiled16_a8(a, fmtA, fmtB);
+    if (!a.Abf && fmtA <= FP8_E5M2 && fmtB <= FP8_E5M2 && a.K >= 1024) return launch_gemm_tiled16_a8(a, fmtA, fmtB);
     if (!a.Abf && fmtA >= FP6_E3M2 && fmtB >= FP6_E3M2)
         return fmtA <= FP6_E2M3 ? launch_gemm_tiled8_a6(a, fmtA, fmtB) : launch_gemm_tiled8_a4(a, fmtA, fmtB);
     switch (fmtA) {

@@ -145,13 +145,15 @@ def test_tiled_kernel_matches_model(mx, oracle, fa, fb, wide):
     assert_bits(C[mi, ni], want, f"tiled {NAMES[fa]} x {NAMES[fb]}")
 
 
-@pytest.mark.parametrize("fa,fb,K,wide", [(0, 0, 640, True), (0, 1, 768, False), (1, 0, 896, True), (1, 1, 640, False), (0, 0, 1024, False),
-                                          (0, 0, 896, False)], ids=lambda v: str(v))
+@pytest.mark.parametrize("fa,fb,K,wide", [(0, 0, 640, True), (0, 1, 1024, False), (1, 0, 1152, True), (1, 1, 1408, False), (0, 0, 1920, False),
+                                          (0, 0, 1536, True), (1, 0, 2176, False), (0, 0, 896, False)], ids=lambda v: str(v))
 def test_whole_tile_fp8_kernel_matches_model(mx, oracle, fa, fb, K, wide):
     """135 whole 256 x 256 tiles -- above the limit below which half-width tiles take over -- of a pair of
-    8-bit formats: the kernel built on the 16 x 16 x 128 form of the instruction, which adds an entry's
-    products in the order of two chained 32 x 32 x 64 instructions.  K = 640 / 768 / 896 end in a partial
-    scale group of one / two / three steps.  Sampled entries and tile corners, bit for bit; bf16 output and
+    8-bit formats.  From K = 1024 on that is the kernel built on the 16 x 16 x 128 form of the instruction,
+    which adds an entry's products in the order of two chained 32 x 32 x 64 instructions; its scale bytes
+    travel in groups of eight K steps, and K = 1152 / 1408 / 1536 / 1920 / 2176 end in a partial group of
+    one / three / four / seven / one steps (1408 and 1920 also in an odd trip of the four-step loop).  K = 640
+    and 896 stay on the 32 x 32 x 64 kernel.  Sampled entries and tile corners, bit for bit; bf16 output and
     row pitches that rule out the wide stores give the same values."""
     M, N = 2304, 3840
     ea, sa, eb, sb = quantized_operands(oracle, M, N, K, fa, fb, 700 + 10 * fa + fb + K, wide)
