@@ -263,9 +263,6 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
 #undef MX_QUAD_READ
 #undef MX_MF
 #undef MX_FENCE
-    // every direct load (the last, clamped, stages included) must have landed before this
-    // work-group's LDS can be handed to another one
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     // The compiler does not know that the assembly above is matrix instructions, so it leaves no wait
     // states between the last of them (8 passes) and the first read of an accumulator register.  The
     // waits are written here, and every accumulator passes through a statement behind them (volatile
@@ -336,6 +333,10 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
                 o[0] = (uint16_t)p0; o[1] = (uint16_t)(p0 >> 16); o[2] = (uint16_t)p1; o[3] = (uint16_t)(p1 >> 16);
             }
     }
+    // The last steps requested stages beyond the end of K (clamped to the last one: harmless, branch-free);
+    // those direct loads must have landed before this work-group's LDS is handed to another one.  The
+    // epilogue above does not touch LDS, so the wait stands here, behind the stores, where it costs nothing.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 template <int FA, int FB, int CDT>

@@ -275,7 +275,6 @@ __global__ __launch_bounds__(64 * NW8, 1) void gemm_tile8_kernel(int64_t M, int6
 #pragma unroll 1
     for (int h = 0; h < T - Tfull; h++) k_step(Tfull, h, false);
 #undef MX8_MFMA
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if constexpr (PROBE) {
         if (threadIdx.x == 0) {
             probe[2 * blockIdx.x] = __builtin_readcyclecounter() - probe_c0;
@@ -310,6 +309,10 @@ __global__ __launch_bounds__(64 * NW8, 1) void gemm_tile8_kernel(int64_t M, int6
                 }
             }
         }
+    // The last steps requested stages beyond the end of K (clamped to the last one: harmless, branch-free);
+    // those direct loads must have landed before this work-group's LDS is handed to another one.  The
+    // epilogue above does not touch LDS, so the wait stands here, behind the stores, where it costs nothing.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 template <int FA, int FB, int CDT, int NW = 8>
