@@ -62,7 +62,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
     constexpr int A_BYTES = TM * TF::ROW, B_BYTES = TN * TF::ROW, STAGE_BYTES = A_BYTES + B_BYTES;
     // {A tile, B tile} x two stages, then {A scale dwords, B scale dwords} x two groups
     // Scale bytes travel in groups of eight K steps: 32 bytes per row, fetched by two lanes, so a wave-wide
-    // load touches 32 cache lines.  The load path's cost is per line, and with 16 bytes per row (64 lines
+    // load touches 32 cache lines; each four-step trip of the loop below requests half of the next group's rows
+    // (no branch in the loop: with one, the register allocator moves every accumulator at the back edge).  The load path's cost is per line, and with 16 bytes per row (64 lines
     // per load, one load pair per four steps) the scale loads took 260 clocks per K step, 9 % of the loop,
     // for 3 % of its bytes; the 160 KB of LDS have room for exactly this doubling, no more.
     constexpr int SG = 8, SG_ROW = 4 * SG, SG_BYTES = (TM + TN) * SG_ROW;
@@ -90,14 +91,16 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
     const uint8_t *gB = Be + (n0 + wave * TF::RPI + s_r) * K + s_u * TF::UNIT;
     const int st_l = wave * 1024;
     // scale staging: wave w fetches the rows 64w .. 64w+63 of A and of B, 32 rows per load, lane l the
-    // half l % 2 of row l / 2
-    const uint8_t *sA = As + (m0 + wave * 64 + (lane >> 1)) * nkb + (lane & 1) * 16;
-    const uint8_t *sB = Bs + (n0 + wave * 64 + (lane >> 1)) * nkb + (lane & 1) * 16;
+    // half l / 32 (steps 0-3 | 4-7 of the group) of row l % 32.  A load's 1 KB of LDS is therefore
+    // [half][32 rows][16 bytes]: rows stay at a 16-byte pitch, as the byte reads below want them (at a
+    // 32-byte pitch they cost three times the LDS cycles)
+    const uint8_t *sA = As + (m0 + wave * 64 + (lane & 31)) * nkb + (lane >> 5) * 16;
+    const uint8_t *sB = Bs + (n0 + wave * 64 + (lane & 31)) * nkb + (lane >> 5) * 16;
     // ---- operand reads: tile row wm*128 + 16x + i (A) / wn*128 + 16y + i (B), chunks q and q + 4
     const int ra0 = (wm * 128 + i) * 128 + ((q ^ ((i >> 1) & 7)) << 4);
     const int rb0 = (wn * 128 + i) * 128 + ((q ^ ((i >> 1) & 7)) << 4);
     // ---- scale reads: byte q of the step's dword of the same rows
-    const int rsa = (wm * 128 + i) * SG_ROW + q, rsb = TM * SG_ROW + (wn * 128 + i) * SG_ROW + q;
+    const int rsa = wm * 4096 + i * 16 + q, rsb = TM * SG_ROW + wn * 4096 + i * 16 + q;   // 16-row block x: + (x / 2) * 1024 + (x % 2) * 256
 
     v4f_t acc[8][8];
 #pragma unroll
@@ -125,21 +128,22 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
     };
     uint8_t *const scl = lds + 2 * STAGE_BYTES;
     const int n_groups = (T + SG - 1) / SG;
-    // Byte offset, inside a row's 32-byte LDS slot, of the scale dword of K step ts.  The partial last group
+    // Byte offset of the scale dword of K step ts from that of the group's first step (same row).  The partial last group
     // is loaded as the row's LAST 32 scale bytes (steps T-8 .. T-1), so that the load never reaches past the
     // row, and its steps sit further back in the slot accordingly.
-    auto scl_ofs = [&](int ts) { return ts < Tg ? (ts & (SG - 1)) * 4 : (ts - (T - SG)) * 4; };
-    // scale bytes of K steps 8G .. 8G+7 (group G, clamped to the last) into slot G & 1: A rows, then B rows
-    auto stage_scales = [&](int G) {
+    auto scl_ofs = [&](int ts) {
+        const int hh = ts < Tg ? (ts & (SG - 1)) : ts - (T - SG);      // position in the group, 0..7
+        return (hh >> 2) * 512 + (hh & 3) * 4;
+    };
+    // scale bytes of K steps 8G .. 8G+7 (group G, clamped to the last) into slot G & 1, for the 32 rows j (0 / 1)
+    // of this wave's 64 rows of A and of B
+    auto stage_scales = [&](int G, int j) {
         G = G < n_groups ? G : n_groups - 1;
-        const uint32_t l0 = lds0 + 2 * STAGE_BYTES + (G & 1) * SG_BYTES + wave * (64 * SG_ROW - 1024);   // lds0 holds wave * 1024
-        const int64_t src_ofs = G * SG + SG <= T ? (int64_t)G * SG_ROW : (int64_t)T * 4 - SG_ROW;
-#pragma unroll
-        for (int j = 0; j < 2; j++) {
-            const uint8_t *pa = sA + src_ofs + j * 32 * nkb, *pb = sB + src_ofs + j * 32 * nkb;
-            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pa), "s"(l0 + j * 1024) : "m0");
-            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pb), "s"(l0 + TM * SG_ROW + j * 1024) : "m0");
-        }
+        const uint32_t l0 = lds0 + 2 * STAGE_BYTES + (G & 1) * SG_BYTES + wave * (64 * SG_ROW - 1024) + j * 1024;   // lds0 holds wave * 1024
+        const int64_t src_ofs = (G * SG + SG <= T ? (int64_t)G * SG_ROW : (int64_t)T * 4 - SG_ROW) + j * 32 * nkb;
+        const uint8_t *pa = sA + src_ofs, *pb = sB + src_ofs;
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pa), "s"(l0) : "m0");
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(pb), "s"(l0 + TM * SG_ROW) : "m0");
     };
     // fragment of 16-row block xb of the tile at buf
     auto frag = [&](const uint8_t *buf, int ofs, int xb) {
@@ -159,11 +163,11 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
     };
     auto read_sa = [&](int so, int x0) {
 #pragma unroll
-        for (int x = 0; x < 4; x++) sa[x0 + x] = scl[so + rsa + (x0 + x) * (16 * SG_ROW)];
+        for (int x = 0; x < 4; x++) sa[x0 + x] = scl[so + rsa + ((x0 + x) >> 1) * 1024 + ((x0 + x) & 1) * 256];
     };
     auto read_sb = [&](int so, int y0) {
 #pragma unroll
-        for (int y = 0; y < 4; y++) sb[y0 + y] = scl[so + rsb + (y0 + y) * (16 * SG_ROW)];
+        for (int y = 0; y < 4; y++) sb[y0 + y] = scl[so + rsb + ((y0 + y) >> 1) * 1024 + ((y0 + y) & 1) * 256];
     };
 
 #define MX_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -198,7 +202,8 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
         const int t1 = T > 1 ? 1 : 0;
 #pragma unroll
         for (int j = 0; j < NJ; j++) stage_b1(0, A_BYTES, j);
-        stage_scales(0);
+        stage_scales(0, 0);
+        stage_scales(0, 1);
 #pragma unroll
         for (int j = 0; j < NJ; j++) stage_a1(0, 0, j);
 #pragma unroll
@@ -237,7 +242,7 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
         // one behind the barrier are refilled for step t+1 in the last quadrant; the other halves follow in
         // the first quadrant of step t+1, see below)
         if ((h & 1) == 0) {
-            MX_QUAD_LOAD(aH, bH, 4, 4, aL, nxtA, ra0, 0, 0, t2, dA, dB, if (h == 0 && (tt & 4) == 0) stage_scales(tt / SG + 1));
+            MX_QUAD_LOAD(aH, bH, 4, 4, aL, nxtA, ra0, 0, 0, t2, dA, dB, if (h == 0) stage_scales(tt / SG + 1, (tt >> 2) & 1));
             MX_QUAD_LOAD(aH, bL, 4, 0, bH, nxtB, rb0, 4, 8, t2, dA, dB, read_sa(so1, 0); read_sb(so1, 4));
         } else {
             MX_QUAD_LOAD(aH, bL, 4, 0, aL, nxtA, ra0, 0, 0, t2, dA, dB, (void)0);
@@ -245,14 +250,14 @@ __global__ __launch_bounds__(256, 1) void gemm_tile16_kernel(int64_t M, int64_t 
         }
         MX_FENCE();
     };
-    // four steps per trip: a trip never straddles a scale group, so its steps read consecutive dwords of one
-    // slot; only the step after the trip needs the general rule
+    // four steps per trip (the steps of the partial last group do not sit at consecutive offsets, so every
+    // step's is worked out: scalar arithmetic, once per trip)
     for (int tt = 0; tt < Tfull; tt += 4) {
-        const int so = scale_ofs(tt), so4 = scale_ofs(tt + 4);
-        k_step(tt, 0, so, so + 4);
-        k_step(tt, 1, so + 4, so + 8);
-        k_step(tt, 2, so + 8, so + 12);
-        k_step(tt, 3, so + 12, so4);
+        const int so0 = scale_ofs(tt), so1 = scale_ofs(tt + 1), so2 = scale_ofs(tt + 2), so3 = scale_ofs(tt + 3), so4 = scale_ofs(tt + 4);
+        k_step(tt, 0, so0, so1);
+        k_step(tt, 1, so1, so2);
+        k_step(tt, 2, so2, so3);
+        k_step(tt, 3, so3, so4);
     }
     // the last one to three steps (Tfull is a multiple of four: the parity of a step is that of h)
     if (T - Tfull > 0) k_step(Tfull, 0, scale_ofs(Tfull), scale_ofs(Tfull + 1));
