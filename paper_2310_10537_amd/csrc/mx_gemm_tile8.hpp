@@ -122,9 +122,17 @@ __global__ __launch_bounds__(64 * NW8, 1) void gemm_tile8_kernel(int64_t M, int6
         for (int j = 0; j < NJB; j++) stage_b1(ts, dst + A_BYTES, j);
     };
     static_assert(NJA + NJB <= 12, "the second half of a step has twelve slots for direct loads");
+    // Three stages: a stage's buffer is free from the barrier of the step that read it until two steps later,
+    // so its refill need not be crammed into the half step behind that barrier, where the eight waves' loads
+    // together ask more of the load path than it gives (12 loads x 8 waves x 16 clocks against the 1024 clocks
+    // of the half step).  The first NLY loads are requested there, the rest in the first half of the next step.
+    constexpr int NL = NJA + NJB, NLY = NSTAGE == 3 ? (NL + 1) / 2 : NL;
     auto stage_one = [&](int k, int ts, uint8_t *dstA, uint8_t *dstB) {
         if (k < NJA) stage_a1(ts, dstA, k);
         else if (k - NJA < NJB) stage_b1(ts, dstB, k - NJA);
+    };
+    auto stage_y = [&](int k, int ts, uint8_t *dstA, uint8_t *dstB) {
+        if (k < NLY) stage_one(k, ts, dstA, dstB);
     };
     uint8_t *const scl = lds + NSTAGE * STAGE_BYTES;
     const int n_groups = (T + SCL_GROUP - 1) / SCL_GROUP;
@@ -192,8 +200,11 @@ __global__ __launch_bounds__(64 * NW8, 1) void gemm_tile8_kernel(int64_t M, int6
     {
         const int t1 = T > 1 ? 1 : 0;
         stage_all(t1, lds + STAGE_BYTES);
-        if (NSTAGE == 3) stage_all(T > 2 ? 2 : T - 1, lds + 2 * STAGE_BYTES);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 1) * (NJA + NJB)) : "memory");
+        if (NSTAGE == 3) {      // stage 2: the share of the second half step; the first step brings the rest
+#pragma unroll
+            for (int k = 0; k < NLY; k++) stage_one(k, T > 2 ? 2 : T - 1, lds + 2 * STAGE_BYTES, lds + 2 * STAGE_BYTES + A_BYTES);
+        }
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NSTAGE == 3 ? NL + NLY : NL) : "memory");
     }
     __syncthreads();
 #pragma unroll
@@ -215,24 +226,29 @@ __global__ __launch_bounds__(64 * NW8, 1) void gemm_tile8_kernel(int64_t M, int6
         uint8_t *nxt = lds + (NSTAGE == 2 ? (cur ^ 1) : (cur == 2 ? 0 : cur + 1)) * STAGE_BYTES;
         uint8_t *bufB = bufA + A_BYTES;
         const int t2 = t + NSTAGE < T ? t + NSTAGE : T - 1;
+        // three stages: the rest of stage t+2 goes into the buffer stage t-1 vacated at the previous barrier
+        uint8_t *prvA = lds + (cur == 0 ? 2 : cur - 1) * STAGE_BYTES, *prvB = prvA + A_BYTES;
+        const int t2x = t + 2 < T ? t + 2 : T - 1;
+#define MX8_XLOAD(I) do { if (NSTAGE == 3) stage_one(NLY + (I), t2x, prvA, prvB); } while (0)
         MX8_FENCE();
         // ---- X: sub-step 0 (8 matrix instructions, A fragment by A fragment).  An A fragment is dead
         // after its two instructions and is refilled at once with the same rows of sub-step 1, so only
         // one set of A fragments is ever live; the two B fragments of sub-step 1 are read meanwhile.
         b1[0] = read_frag<WB>(bufB, rb0, 1, 0);
-        MX8_MFMA(af, b0, 0, 0, 0); MX8_MFMA(af, b0, 0, 1, 0);
+        MX8_XLOAD(0); MX8_MFMA(af, b0, 0, 0, 0); MX8_XLOAD(1); MX8_MFMA(af, b0, 0, 1, 0);
         af[0] = read_frag<WA>(bufA, ra0, 1, 0);
         MX8_FENCE();
         b1[1] = read_frag<WB>(bufB, rb0, 1, 1);
-        MX8_MFMA(af, b0, 1, 0, 0); MX8_MFMA(af, b0, 1, 1, 0);
+        MX8_XLOAD(2); MX8_MFMA(af, b0, 1, 0, 0); MX8_XLOAD(3); MX8_MFMA(af, b0, 1, 1, 0);
         af[1] = read_frag<WA>(bufA, ra0, 1, 1);
         MX8_FENCE();
-        MX8_MFMA(af, b0, 2, 0, 0); MX8_MFMA(af, b0, 2, 1, 0);
+        MX8_XLOAD(4); MX8_MFMA(af, b0, 2, 0, 0); MX8_XLOAD(5); MX8_MFMA(af, b0, 2, 1, 0);
         af[2] = read_frag<WA>(bufA, ra0, 1, 2);
         MX8_FENCE();
         MX8_MFMA(af, b0, 3, 0, 0); MX8_MFMA(af, b0, 3, 1, 0);
         af[3] = read_frag<WA>(bufA, ra0, 1, 3);
         MX8_FENCE();
+#undef MX8_XLOAD
         // Stage t+1 must be in LDS, and every wave must have issued its last read of stage t,
         // before the buffers change roles.
         if (NSTAGE == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -242,23 +258,24 @@ __global__ __launch_bounds__(64 * NW8, 1) void gemm_tile8_kernel(int64_t M, int6
         // ---- Y: sub-step 1; stage t+NSTAGE is requested into the buffer stage t just vacated, one direct
         // load per matrix instruction, and the fragments of sub-step 0 of stage t+1 are read
         b0[0] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 0);
-        stage_one(0, t2, bufA, bufB); stage_one(0 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 0, 0, 2); MX8_FENCE();
-        stage_one(1, t2, bufA, bufB); stage_one(1 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 0, 1, 2);
+        // (stage_y: load k of the stage, if it belongs to this half step)
+        stage_y(0, t2, bufA, bufB); stage_y(0 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 0, 0, 2); MX8_FENCE();
+        stage_y(1, t2, bufA, bufB); stage_y(1 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 0, 1, 2);
         af[0] = read_frag<WA>(nxt, ra0, 0, 0);
         MX8_FENCE();
         b0[1] = read_frag<WB>(nxt + A_BYTES, rb0, 0, 1);
-        stage_one(2, t2, bufA, bufB); stage_one(2 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 1, 0, 2); MX8_FENCE();
-        stage_one(3, t2, bufA, bufB); stage_one(3 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 1, 1, 2);
+        stage_y(2, t2, bufA, bufB); stage_y(2 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 1, 0, 2); MX8_FENCE();
+        stage_y(3, t2, bufA, bufB); stage_y(3 + 8, t2, bufA, bufB); MX8_MFMA(af, b1, 1, 1, 2);
         af[1] = read_frag<WA>(nxt, ra0, 0, 1);
         MX8_FENCE();
         if (h == 0) stage_scales(tt / SCL_GROUP + 1);
         next_scales(tt, h, MAIN);
-        stage_one(4, t2, bufA, bufB); MX8_MFMA(af, b1, 2, 0, 2); MX8_FENCE();
-        stage_one(5, t2, bufA, bufB); MX8_MFMA(af, b1, 2, 1, 2);
+        stage_y(4, t2, bufA, bufB); MX8_MFMA(af, b1, 2, 0, 2); MX8_FENCE();
+        stage_y(5, t2, bufA, bufB); MX8_MFMA(af, b1, 2, 1, 2);
         af[2] = read_frag<WA>(nxt, ra0, 0, 2);
         MX8_FENCE();
-        stage_one(6, t2, bufA, bufB); MX8_MFMA(af, b1, 3, 0, 2); MX8_FENCE();
-        stage_one(7, t2, bufA, bufB); MX8_MFMA(af, b1, 3, 1, 2);
+        stage_y(6, t2, bufA, bufB); MX8_MFMA(af, b1, 3, 0, 2); MX8_FENCE();
+        stage_y(7, t2, bufA, bufB); MX8_MFMA(af, b1, 3, 1, 2);
         af[3] = read_frag<WA>(nxt, ra0, 0, 3);
         MX8_FENCE();
 #pragma unroll
